@@ -1,0 +1,338 @@
+"""Pins for the oracle's arithmetic (no GPU needed).
+
+What the oracle is held to here is written from the definitions, not from the
+oracle's own linear-cost formulas:
+  * the prediction is the dense Tucker contraction (Eq. tucker) with the core
+    built explicitly from Eq. kruskal_approximation -- exponential in N, which
+    is exactly what Theorem 1 says the linear form must equal;
+  * every parameter change of one step is minus the step size times a central
+    finite difference of the sampled loss evaluated with that dense model;
+  * special cases with textbook closed forms, and invariants of the model.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2204_07104_amd import synth
+
+
+# ----------------------------------------------------------------------------
+# the definition, written out (float64, exponential cost)
+# ----------------------------------------------------------------------------
+def dense_core(B):
+    """G[j_1..j_N] = sum_r prod_n B^(n)[j_n, r]   (Eq. kruskal_approximation)."""
+    N = len(B)
+    R = B[0].shape[1]
+    G = np.zeros([b.shape[0] for b in B])
+    for r in range(R):
+        outer = np.array(1.0)
+        for n in range(N):
+            outer = np.multiply.outer(outer, B[n][:, r].astype(np.float64))
+        G = G + outer
+    return G
+
+
+def tucker_entry(G, rows):
+    """xhat = sum_{j_1..j_N} G[j_1..j_N] prod_n a^(n)[j_n]   (Eq. tucker, one entry)."""
+    total = 0.0
+    for js in itertools.product(*[range(s) for s in G.shape]):
+        term = G[js]
+        for n, j in enumerate(js):
+            term *= float(rows[n][j])
+        total += term
+    return total
+
+
+def tucker_entry_fast(G, rows):
+    out = G
+    for n in range(len(rows)):
+        out = np.tensordot(np.asarray(rows[n], dtype=np.float64), out, axes=(0, 0))
+    return float(out)
+
+
+def loss_A(A, B, idx, vals, pos, lam_A):
+    """F = sum_{k in Psi} [ e_k^2 / 2 + lam_A/2 sum_n |a^(n)_{i_n(k)}|^2 ]  (M = 1 for factor rows)."""
+    G = dense_core(B)
+    F = 0.0
+    for p in pos:
+        rows = [A[n][idx[n][p]] for n in range(len(A))]
+        e = float(vals[p]) - tucker_entry_fast(G, rows)
+        F += 0.5 * e * e + 0.5 * lam_A * sum(float(np.dot(r.astype(np.float64), r.astype(np.float64))) for r in rows)
+    return F
+
+
+def loss_B(A, B, idx, vals, pos, lam_B):
+    """F = (1/|Psi|) sum_k e_k^2 / 2 + lam_B/2 sum_n |B^(n)|_F^2   (M = |Psi| for the core)."""
+    G = dense_core(B)
+    F = 0.0
+    for p in pos:
+        rows = [A[n][idx[n][p]] for n in range(len(A))]
+        e = float(vals[p]) - tucker_entry_fast(G, rows)
+        F += 0.5 * e * e
+    F /= len(pos)
+    return F + 0.5 * lam_B * sum(float((b.astype(np.float64) ** 2).sum()) for b in B)
+
+
+def random_problem(seed, dims, J, R, nnz, scale=1.0):
+    rng = np.random.default_rng(seed)
+    N = len(dims)
+    idx = [rng.integers(0, dims[n], size=nnz, dtype=np.int32) for n in range(N)]
+    vals = rng.normal(size=nnz).astype(np.float32)
+    A = [(scale * rng.uniform(-1, 1, size=(dims[n], J[n]))).astype(np.float32) for n in range(N)]
+    B = [(scale * rng.uniform(-1, 1, size=(J[n], R))).astype(np.float32) for n in range(N)]
+    return idx, vals, A, B
+
+
+SHAPES = [
+    ((4, 5, 3), (2, 3, 4), 2),
+    ((3, 3, 3, 3), (2, 2, 2, 2), 3),
+    ((6, 4), (3, 5), 4),
+    ((3, 2, 4, 2, 3), (2, 1, 3, 2, 2), 5),
+    ((7,), (3,), 2),
+]
+
+
+# ----------------------------------------------------------------------------
+# prediction: linear Kruskal form == dense Tucker contraction   (Theorem 1)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dims,J,R", SHAPES)
+def test_prediction_equals_dense_tucker(dims, J, R):
+    idx, vals, A, B = random_problem(1, dims, J, R, nnz=6)
+    G = dense_core(B)
+    for p in range(6):
+        rows = [A[n][idx[n][p]] for n in range(len(dims))]
+        xhat, c, w, gs = oracle.nonzero_terms(rows, B)
+        ref = tucker_entry(G, rows)
+        assert abs(ref - tucker_entry_fast(G, rows)) < 1e-12
+        assert xhat == pytest.approx(ref, rel=1e-12, abs=1e-13)
+
+
+@pytest.mark.parametrize("dims,J,R", SHAPES)
+def test_leave_one_out_and_gs_against_definition(dims, J, R):
+    """GS^(n) = G^(n) S^(n)T: contract the dense core with every row except mode n's."""
+    N = len(dims)
+    idx, vals, A, B = random_problem(2, dims, J, R, nnz=3)
+    G = dense_core(B)
+    for p in range(3):
+        rows = [A[n][idx[n][p]] for n in range(N)]
+        xhat, c, w, gs = oracle.nonzero_terms(rows, B)
+        for n in range(N):
+            out = G
+            for k in range(N - 1, -1, -1):          # contract trailing axes first so positions stay valid
+                if k != n:
+                    out = np.tensordot(out, rows[k].astype(np.float64), axes=(k, 0))
+            assert out.shape == (J[n],)
+            np.testing.assert_allclose(gs[n], out, rtol=1e-11, atol=1e-13)
+            # a^(n) . GS^(n) = xhat for every mode, and sum_r c^(n)_r w^(n)_r = xhat
+            assert float(np.dot(rows[n].astype(np.float64), gs[n])) == pytest.approx(xhat, rel=1e-11, abs=1e-13)
+            assert float(np.dot(c[n], w[n])) == pytest.approx(xhat, rel=1e-11, abs=1e-13)
+            # c^(n)_r is the plain dot product of the row with column r of B^(n)
+            np.testing.assert_allclose(c[n], rows[n].astype(np.float64) @ B[n].astype(np.float64), rtol=1e-13)
+
+
+def test_order_two_is_a_bilinear_form():
+    idx, vals, A, B = random_problem(3, (5, 6), (3, 4), 2, nnz=4)
+    core = B[0].astype(np.float64) @ B[1].astype(np.float64).T
+    for p in range(4):
+        rows = [A[0][idx[0][p]], A[1][idx[1][p]]]
+        xhat = oracle.nonzero_terms(rows, B)[0]
+        assert xhat == pytest.approx(float(rows[0].astype(np.float64) @ core @ rows[1].astype(np.float64)), rel=1e-12)
+
+
+def test_identity_core_factors_reduce_to_cp():
+    rng = np.random.default_rng(4)
+    Jr = 3
+    rows = [rng.normal(size=Jr).astype(np.float32) for _ in range(4)]
+    B = [np.eye(Jr, dtype=np.float32) for _ in range(4)]
+    xhat = oracle.nonzero_terms(rows, B)[0]
+    cp = float(np.prod(np.stack([r.astype(np.float64) for r in rows]), axis=0).sum())
+    assert xhat == pytest.approx(cp, rel=1e-13)
+
+
+def test_rank_one_scalar_case_by_hand():
+    # N = 3, J_n = 1, R = 1: xhat = prod a_n b_n; d(e^2/2)/da_1 = -e b_1 (a_2 b_2)(a_3 b_3)
+    a = [np.array([v], dtype=np.float32) for v in (0.5, -2.0, 1.5)]
+    b = [np.array([[v]], dtype=np.float32) for v in (2.0, 0.25, -1.0)]
+    xhat, c, w, gs = oracle.nonzero_terms(a, b)
+    assert xhat == 0.5 * 2.0 * -2.0 * 0.25 * 1.5 * -1.0
+    assert gs[0][0] == 2.0 * (-2.0 * 0.25) * (1.5 * -1.0)
+    assert w[1][0] == (0.5 * 2.0) * (1.5 * -1.0)
+
+
+def test_scaling_factor_against_core_leaves_prediction_unchanged():
+    idx, vals, A, B = random_problem(5, (4, 4, 4), (3, 3, 3), 4, nnz=1)
+    rows = [A[n][idx[n][0]] for n in range(3)]
+    x0 = oracle.nonzero_terms(rows, B)[0]
+    rows2 = [rows[0] * np.float32(4.0), rows[1], rows[2]]
+    B2 = [B[0] * np.float32(0.25), B[1], B[2]]
+    assert oracle.nonzero_terms(rows2, B2)[0] == pytest.approx(x0, rel=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# the step: parameter change == -lr * finite-difference gradient of the sampled loss
+# ----------------------------------------------------------------------------
+def fd_grad(fun, arrays, which, h=1e-5):
+    """Central differences of fun() with respect to every entry of arrays[which] (float32 storage
+    is perturbed in float64 copies)."""
+    base = arrays[which]
+    g = np.zeros(base.shape)
+    for q in np.ndindex(*base.shape):
+        keep = base[q]
+        base[q] = keep + h
+        fp = fun()
+        base[q] = keep - h
+        fm = fun()
+        base[q] = keep
+        g[q] = (fp - fm) / (2 * h)
+    return g
+
+
+@pytest.mark.parametrize("dims,J,R", SHAPES[:4])
+def test_sync_step_is_gradient_descent_on_sampled_loss(dims, J, R):
+    N = len(dims)
+    nnz = 12
+    idx, vals, A, B = random_problem(6, dims, J, R, nnz, scale=0.7)
+    # Psi with a duplicated position and (small dims) many repeated rows
+    pos = np.array([0, 3, 3, 7, 11, 5, 0, 9], dtype=np.int64)
+    lam_A, lam_B = 0.3, 0.2
+    lr_A, lr_B = 1.0, 1.0        # power of two: A - A_new recovers the summed gradient to fp32 rounding
+
+    A64 = [a.astype(np.float64) for a in A]
+    B64 = [b.astype(np.float64) for b in B]
+    gA = [fd_grad(lambda: loss_A(A64, B64, idx, vals, pos, lam_A), A64, n) for n in range(N)]
+    gB = [fd_grad(lambda: loss_B(A64, B64, idx, vals, pos, lam_B), B64, n) for n in range(N)]
+
+    A1 = [a.copy() for a in A]
+    B1 = [b.copy() for b in B]
+    oracle.sgd_step_sync(dims, idx, vals, A1, B1, pos, lr_A, lr_B, lam_A, lam_B)
+    for n in range(N):
+        dA = (A[n].astype(np.float64) - A1[n].astype(np.float64)) / lr_A
+        dB = (B[n].astype(np.float64) - B1[n].astype(np.float64)) / lr_B
+        tolA = 1e-6 * (1 + np.abs(A1[n]).max())
+        tolB = 1e-6 * (1 + np.abs(B1[n]).max())
+        np.testing.assert_allclose(dA, gA[n], rtol=2e-6, atol=tolA)
+        np.testing.assert_allclose(dB, gB[n], rtol=2e-6, atol=tolB)
+        # rows no sample touches do not move (no decay of untouched rows)
+        touched = np.zeros(dims[n], dtype=bool)
+        touched[idx[n][pos]] = True
+        assert np.array_equal(A1[n][~touched], A[n][~touched])
+        assert touched.sum() == 0 or not np.array_equal(A1[n][touched], A[n][touched])
+
+
+def test_step_scales_linearly_with_learning_rate():
+    dims, J, R = (5, 4, 6), (3, 2, 4), 3
+    idx, vals, A, B = random_problem(7, dims, J, R, 20, scale=0.5)
+    pos = oracle.sample_positions(1, 16, 20)
+    out = []
+    for lr in (0.25, 0.5):
+        A1 = [a.copy() for a in A]
+        B1 = [b.copy() for b in B]
+        oracle.sgd_step_sync(dims, idx, vals, A1, B1, pos, lr, lr, 0.01, 0.01)
+        out.append((A1, B1))
+    for n in range(3):
+        d1 = out[0][0][n].astype(np.float64) - A[n]
+        d2 = out[1][0][n].astype(np.float64) - A[n]
+        np.testing.assert_allclose(2 * d1, d2, rtol=0, atol=1e-6)
+        e1 = out[0][1][n].astype(np.float64) - B[n]
+        e2 = out[1][1][n].astype(np.float64) - B[n]
+        np.testing.assert_allclose(2 * e1, e2, rtol=0, atol=1e-6)
+
+
+def test_zero_learning_rate_changes_nothing():
+    dims, J, R = (5, 4, 6), (3, 2, 4), 3
+    idx, vals, A, B = random_problem(8, dims, J, R, 20)
+    A1 = [a.copy() for a in A]
+    B1 = [b.copy() for b in B]
+    oracle.sgd_step_sync(dims, idx, vals, A1, B1, np.arange(20), 0.0, 0.0, 0.5, 0.5)
+    assert all(np.array_equal(x, y) for x, y in zip(A + B, A1 + B1))
+
+
+def test_exact_model_gives_pure_decay_with_hit_counts():
+    """If every value equals the model's prediction (e = 0) the step is only the L2 terms:
+    a <- a (1 - lr_A lam_A hits(row)),  B <- B (1 - lr_B lam_B)."""
+    dims, J, R = (4, 3, 5), (2, 3, 2), 3
+    idx, vals, A, B = random_problem(9, dims, J, R, 15, scale=0.8)
+    G = dense_core(B)
+    # make the values exactly representable predictions: evaluate in double, store, then
+    # measure the decay against the (tiny) residual left by rounding the value to fp32
+    vals = np.array([tucker_entry_fast(G, [A[n][idx[n][p]] for n in range(3)]) for p in range(15)],
+                    dtype=np.float32)
+    pos = np.array([1, 1, 4, 8, 8, 8, 14], dtype=np.int64)
+    lr_A, lr_B, lam_A, lam_B = 0.125, 0.25, 0.5, 0.5
+    A1 = [a.copy() for a in A]
+    B1 = [b.copy() for b in B]
+    oracle.sgd_step_sync(dims, idx, vals, A1, B1, pos, lr_A, lr_B, lam_A, lam_B)
+    for n in range(3):
+        hits = np.bincount(idx[n][pos], minlength=dims[n]).astype(np.float64)
+        np.testing.assert_allclose(A1[n], A[n] * (1 - lr_A * lam_A * hits)[:, None], rtol=0, atol=2e-6)
+        np.testing.assert_allclose(B1[n], B[n] * (1 - lr_B * lam_B), rtol=0, atol=2e-6)
+
+
+def test_sample_order_does_not_matter_in_sync_mode():
+    dims, J, R = (6, 5, 4), (3, 3, 2), 4
+    idx, vals, A, B = random_problem(10, dims, J, R, 30, scale=0.6)
+    pos = oracle.sample_positions(3, 40, 30)
+    perm = np.random.default_rng(0).permutation(40)
+    res = []
+    for p in (pos, pos[perm]):
+        A1 = [a.copy() for a in A]
+        B1 = [b.copy() for b in B]
+        oracle.sgd_step_sync(dims, idx, vals, A1, B1, p, 0.01, 0.01, 0.01, 0.01)
+        res.append(A1 + B1)
+    for x, y in zip(*res):
+        np.testing.assert_allclose(x, y, rtol=0, atol=1e-7)
+
+
+def test_euler_homogeneity_of_core_gradient():
+    """xhat is linear in each B^(n): <B^(n), dF/dB^(n)> (data term) is the same for all n and equals
+    -(1/M) sum_k e_k xhat_k.  Measured through a step with lam_B = 0."""
+    dims, J, R = (5, 5, 5), (2, 3, 4), 3
+    idx, vals, A, B = random_problem(11, dims, J, R, 25, scale=0.7)
+    pos = np.arange(25, dtype=np.int64)
+    G = dense_core(B)
+    target = 0.0
+    for p in pos:
+        xh = tucker_entry_fast(G, [A[n][idx[n][p]] for n in range(3)])
+        target += -(float(vals[p]) - xh) * xh
+    target /= len(pos)
+    A1 = [a.copy() for a in A]
+    B1 = [b.copy() for b in B]
+    oracle.sgd_step_sync(dims, idx, vals, A1, B1, pos, 0.0, 1.0, 0.0, 0.0)
+    for n in range(3):
+        gB = B[n].astype(np.float64) - B1[n].astype(np.float64)
+        assert float((gB * B[n]).sum()) == pytest.approx(target, rel=1e-5, abs=1e-6)
+
+
+# ----------------------------------------------------------------------------
+# RMSE / MAE
+# ----------------------------------------------------------------------------
+def test_rmse_and_mae_against_dense_model():
+    dims, J, R = (4, 5, 3), (2, 3, 4), 2
+    idx, vals, A, B = random_problem(12, dims, J, R, 40)
+    G = dense_core(B)
+    err = np.array([float(vals[p]) - tucker_entry_fast(G, [A[n][idx[n][p]] for n in range(3)]) for p in range(40)])
+    rmse, mae = oracle.errors(dims, idx, vals, A, B)
+    assert rmse == pytest.approx(float(np.sqrt((err ** 2).mean())), rel=1e-12)
+    assert mae == pytest.approx(float(np.abs(err).mean()), rel=1e-12)
+    sub = np.array([3, 3, 17, 39], dtype=np.int64)
+    rmse_s, mae_s = oracle.errors(dims, idx, vals, A, B, positions=sub)
+    assert rmse_s == pytest.approx(float(np.sqrt((err[sub] ** 2).mean())), rel=1e-12)
+    assert mae_s == pytest.approx(float(np.abs(err[sub]).mean()), rel=1e-12)
+
+
+def test_ten_steps_reduce_rmse_on_scaled_c1():
+    """C1 recipe at a tenth of its size: RMSE starts near sqrt(E[(x-1)^2]) = sqrt(6) for values
+    uniform on 1..5 and a starting prediction of R (J/16)^N = 1, and falls with every step."""
+    w = synth.WORKLOADS["C1"].scaled(nnz=10_000, n_samples=1_000, dims=(100, 80, 60))
+    idx, vals = synth.make_tensor(w)
+    A, B = oracle.init_factors(w.init_seed, w.dims, w.J, w.R)
+    prev = oracle.rmse(w.dims, idx, vals, A, B)
+    assert 2.2 < prev < 2.7
+    for t in range(10):
+        pos = oracle.sample_positions(w.sample_seed0 + t, w.n_samples, w.nnz)
+        oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+        cur = oracle.rmse(w.dims, idx, vals, A, B)
+        assert cur < prev
+        prev = cur
