@@ -1,0 +1,171 @@
+/*
+ * ftk -- sampled stochastic-gradient step of sparse Tucker decomposition with a
+ * Kruskal-approximated core (FastTucker), for one AMD MI355X (gfx950).
+ *
+ * Problem (Definition "Sparse Tucker Decomposition", Eq. tucker): given an N-order
+ * sparse tensor X with stored entries Omega and ranks J_1..J_N, find factor matrices
+ * A^(n) in R^{I_n x J_n} and a core G with X ~ G x_1 A^(1) ... x_N A^(N).  The core is
+ * held as N small matrices B^(n) in R^{J_n x R} with G ~ sum_r b^(1)_r o ... o b^(N)_r
+ * (Eq. kruskal_approximation, R = R_core).  For a stored entry x at (i_1..i_N):
+ *
+ *   c^(n)_r = sum_j A^(n)[i_n,j] B^(n)[j,r]          (under-braces of the GS and Q derivations)
+ *   xhat    = sum_r prod_n c^(n)_r                    (Theorem 1)
+ *   w^(n)_r = prod_{k != n} c^(k)_r
+ *   GS^(n)_j = sum_r B^(n)[j,r] w^(n)_r               (Section 3.1, after Theorem 1)
+ *   Q^(n),r_j = A^(n)[i_n,j] w^(n)_r                  (Section 3.2, after Theorem 2)
+ *   e = x - xhat
+ *
+ * One step (Algorithm 1) over a sample set Psi of M stored entries, all gradients taken
+ * at the parameters the step starts from (synchronous mode):
+ *
+ *   A^(n)[i,:] <- A^(n)[i,:] - lr_A * sum_{k in Psi, i_n(k) = i} ( -e_k GS^(n)_k + lambda_A A^(n)[i,:] )
+ *   B^(n)      <- B^(n)      - lr_B * ( (1/M) sum_{k in Psi} -e_k Q^(n)_k  + lambda_B B^(n) )
+ *
+ * (Eq. Gradient_low_rank with parts (1)+(3) merged, Eq. Gradient_low_rank_core with parts
+ * (1)+(3)+(4) merged; "M = 1 for factor matrices, M = |Psi| for core tensor" is the input line
+ * of Algorithm 1.  The mean-over-Psi reading of Eq. SGD for the factor rows is the same step
+ * with lr_A / M.)  Rows no sample touches do not change.
+ *
+ * Conventions
+ *  - Plain C ABI.  Every call returns an int status (FTK_OK = 0, negative = error), never
+ *    throws and never aborts.  ftk_last_error() gives a message for the last failure.
+ *  - Indices are 0-based int32; sample positions are int64 at this boundary.
+ *  - All matrices are dense row-major fp32: A^(n) is I_n x J_n, B^(n) is J_n x R.
+ *  - "host" / "device" is stated for every pointer.  Device pointers must belong to the HIP
+ *    device that was current when ftk_create() ran; that device must be current in later calls.
+ *  - The library owns copies of the tensor, the parameters and Psi.  Caller buffers can be
+ *    released as soon as the call they were passed to returns.
+ *  - ftk_sample / ftk_sgd_step only enqueue work on the context's stream (the null stream
+ *    unless ftk_set_stream() was called).  ftk_rmse, ftk_mae, ftk_get_*, ftk_set_factors
+ *    wait for that stream.
+ *  - A context is not thread-safe; different contexts are independent.
+ */
+#ifndef FTK_H
+#define FTK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ftk_ctx ftk_ctx;
+
+enum {
+    FTK_OK = 0,
+    FTK_EINVAL = -1,       /* bad argument (null pointer, size out of range, index out of range) */
+    FTK_ENOMEM = -2,       /* a host or device allocation failed */
+    FTK_EDEVICE = -3,      /* a HIP call failed, or no usable gfx950 device */
+    FTK_ESTATE = -4,       /* call order: e.g. ftk_sgd_step before ftk_sample */
+    FTK_EUNSUPPORTED = -5  /* valid but outside what the kernels are built for */
+};
+
+/* ftk_create flags */
+enum {
+    FTK_PTRS_HOST = 0u,    /* idx[n] and vals point to host memory (default) */
+    FTK_PTRS_DEVICE = 1u   /* idx[n] and vals point to device memory (the idx array itself is host) */
+};
+
+/* ftk_set_mode */
+enum {
+    FTK_SYNC = 0,          /* all gradients at the step's starting parameters, then one update */
+    FTK_HOGWILD = 1        /* Algorithm 1 as printed: factor rows updated in place, sample by sample */
+};
+
+#define FTK_MAX_ORDER 8
+
+/*
+ * Create a context for one tensor and initialise the parameters.
+ *   out        host; receives the context (NULL on failure)
+ *   order      N, 1..FTK_MAX_ORDER
+ *   dims       host int64[order]; 1 <= I_n < 2^31
+ *   nnz        number of stored entries |Omega|, 1 <= nnz < 2^32; repeated coordinates are allowed
+ *   idx        host array of `order` pointers; idx[n] -> int32[nnz] (struct of arrays), host or
+ *              device per `flags`; every value must satisfy 0 <= idx[n][p] < dims[n] (checked)
+ *   vals       fp32[nnz], host or device per `flags`
+ *   J          host int32[order], J_n >= 1;   R >= 1.   R <= J_n is NOT required.
+ *   init_seed  A^(n), B^(n) ~ U[0, 0.5): element q (row-major flat index) of parameter array t
+ *              (t = n for A^(n), t = N + n for B^(n)) is
+ *              0.5 * 2^-24 * (w0 >> 8),  w0 = word 0 of Philox4x32-10(counter = (lo32 q, hi32 q, t, 1),
+ *              key = (lo32 init_seed, hi32 init_seed)).      ("Initializing A, B", Algorithm 1)
+ * Errors: FTK_EINVAL, FTK_ENOMEM, FTK_EDEVICE, FTK_EUNSUPPORTED (N*R or J_n beyond kernel limits).
+ */
+int ftk_create(ftk_ctx** out, int32_t order, const int64_t* dims, int64_t nnz,
+               const int32_t* const* idx, const float* vals, const int32_t* J, int32_t R,
+               uint64_t init_seed, uint32_t flags);
+
+/* Release everything the context owns.  NULL is allowed. */
+void ftk_destroy(ftk_ctx* ctx);
+
+/*
+ * Draw the sample set Psi for the next step(s) (Definition "SGD": "an M entries set Psi is
+ * randomly selected from Omega"; the paper fixes neither generator nor replacement rule).
+ * Psi is n_samples i.i.d. uniform positions WITH replacement:
+ *   (w0,w1,w2,w3) = Philox4x32-10(counter = (lo32(k/2), hi32(k/2), 0, 0), key = (lo32 seed, hi32 seed))
+ *   u = w0 | w1 << 32  for even k,   w2 | w3 << 32  for odd k
+ *   p_k = floor(u * nnz / 2^64)
+ * Psi stays valid until the next ftk_sample.  1 <= n_samples < 2^31.
+ */
+int ftk_sample(ftk_ctx* ctx, uint64_t seed, int64_t n_samples);
+
+/* Copy Psi to host int64[n_samples] (waits for the stream).  FTK_ESTATE if nothing was sampled. */
+int ftk_get_samples(ftk_ctx* ctx, int64_t* pos_out);
+
+/*
+ * One SGD step over the current Psi (formulas at the top of this file).  FTK_ESTATE if no Psi.
+ * In FTK_SYNC mode the result is independent of the order in which samples are processed up to
+ * fp32 summation order.  In FTK_HOGWILD mode factor rows are read and written in place while
+ * other samples are in flight (Algorithm 1 lines 1-16 as printed); results are not reproducible.
+ */
+int ftk_sgd_step(ftk_ctx* ctx, float lr_A, float lr_B, float lambda_A, float lambda_B);
+
+/*
+ * RMSE = sqrt( sum_{Omega} (x - xhat)^2 / |Omega| ) and MAE = sum_{Omega} |x - xhat| / |Omega|
+ * over ALL stored entries (Section 5.1 defines both over a test set Gamma; this library's
+ * Gamma is Omega).  Squared errors are summed in double.  out: host.  Waits for the stream.
+ */
+int ftk_rmse(ftk_ctx* ctx, double* out);
+int ftk_mae(ftk_ctx* ctx, double* out);
+
+/*
+ * Copy parameters out / in.  A[n]: host fp32[I_n * J_n] row-major; B[n]: host fp32[J_n * R]
+ * row-major.  Either array of pointers may be NULL (skipped), as may single entries.
+ */
+int ftk_get_factors(ftk_ctx* ctx, float* const* A_out, float* const* B_out);
+int ftk_set_factors(ftk_ctx* ctx, const float* const* A_in, const float* const* B_in);
+
+/* FTK_SYNC (default) or FTK_HOGWILD. */
+int ftk_set_mode(ftk_ctx* ctx, int mode);
+
+/* Use this hipStream_t (passed as void*) for all later work; NULL = the null stream.
+ * The caller keeps ownership of the stream and must keep it alive. */
+int ftk_set_stream(ftk_ctx* ctx, void* hip_stream);
+
+/*
+ * Per-kernel timing with HIP events on the context's stream, for benchmarks.
+ * ftk_set_timing(ctx, 1) makes every later ftk_sample / ftk_sgd_step bracket each kernel it
+ * launches with events; ftk_get_timing waits for the stream and returns, for kernel slot
+ * `which` (FTK_K_*), the summed milliseconds and the number of launches since timing was
+ * switched on (or last read with reset != 0).
+ */
+enum { FTK_K_SAMPLE = 0, FTK_K_GRAD = 1, FTK_K_APPLY_A = 2, FTK_K_APPLY_B = 3, FTK_K_COUNT = 4 };
+int ftk_set_timing(ftk_ctx* ctx, int enabled);
+int ftk_get_timing(ftk_ctx* ctx, int which, double* total_ms, int64_t* launches, int reset);
+
+/*
+ * Gradient-kernel variant.  ftk_create picks the fastest variant built for (N, J_n, R)
+ * ("auto").  ftk_set_kernel forces one by name: "generic" (any shape within the limits, one
+ * lane per sample) or one of the specialised names ftk_kernel_name can return; "auto" restores
+ * the default.  FTK_EUNSUPPORTED if the named variant is not built for this shape.
+ * ftk_kernel_name: the variant in use (static string, never NULL).
+ */
+int ftk_set_kernel(ftk_ctx* ctx, const char* name);
+const char* ftk_kernel_name(const ftk_ctx* ctx);
+
+/* Message for the most recent failure on this context (ctx == NULL: of ftk_create on this thread). */
+const char* ftk_last_error(const ftk_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FTK_H */

@@ -1,0 +1,239 @@
+"""Thin ctypes binding over the C ABI of libftk.so (declared in include/ftk.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+Function names and argument order follow the header.  numpy arrays are passed as host
+pointers; torch CUDA tensors (optional) as device pointers.  There is no CPU fallback: if
+the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libftk.so")
+
+FTK_OK, FTK_EINVAL, FTK_ENOMEM, FTK_EDEVICE, FTK_ESTATE, FTK_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+FTK_PTRS_HOST, FTK_PTRS_DEVICE = 0, 1
+FTK_SYNC, FTK_HOGWILD = 0, 1
+FTK_K_SAMPLE, FTK_K_GRAD, FTK_K_APPLY_A, FTK_K_APPLY_B, FTK_K_COUNT = 0, 1, 2, 3, 4
+FTK_MAX_ORDER = 8
+
+# every symbol include/ftk.h declares
+SYMBOLS = [
+    "ftk_create", "ftk_destroy", "ftk_sample", "ftk_get_samples", "ftk_sgd_step", "ftk_rmse", "ftk_mae",
+    "ftk_get_factors", "ftk_set_factors", "ftk_set_mode", "ftk_set_stream", "ftk_set_timing",
+    "ftk_get_timing", "ftk_set_kernel", "ftk_kernel_name", "ftk_last_error",
+]
+
+
+class FtkError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("ftk error %d: %s" % (code, message))
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Load libftk.so (built by `python -m paper_2204_07104_amd.build`).  Raises if missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build it with `python -m paper_2204_07104_amd.build` (there is no CPU fallback)" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp = C.c_void_p
+    L.ftk_create.argtypes = [C.POINTER(vp), C.c_int32, vp, C.c_int64, vp, vp, vp, C.c_int32, C.c_uint64, C.c_uint32]
+    L.ftk_create.restype = C.c_int
+    L.ftk_destroy.argtypes = [vp]
+    L.ftk_destroy.restype = None
+    L.ftk_sample.argtypes = [vp, C.c_uint64, C.c_int64]
+    L.ftk_sample.restype = C.c_int
+    L.ftk_get_samples.argtypes = [vp, vp]
+    L.ftk_get_samples.restype = C.c_int
+    L.ftk_sgd_step.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float]
+    L.ftk_sgd_step.restype = C.c_int
+    L.ftk_rmse.argtypes = [vp, C.POINTER(C.c_double)]
+    L.ftk_rmse.restype = C.c_int
+    L.ftk_mae.argtypes = [vp, C.POINTER(C.c_double)]
+    L.ftk_mae.restype = C.c_int
+    L.ftk_get_factors.argtypes = [vp, vp, vp]
+    L.ftk_get_factors.restype = C.c_int
+    L.ftk_set_factors.argtypes = [vp, vp, vp]
+    L.ftk_set_factors.restype = C.c_int
+    L.ftk_set_mode.argtypes = [vp, C.c_int]
+    L.ftk_set_mode.restype = C.c_int
+    L.ftk_set_stream.argtypes = [vp, vp]
+    L.ftk_set_stream.restype = C.c_int
+    L.ftk_set_timing.argtypes = [vp, C.c_int]
+    L.ftk_set_timing.restype = C.c_int
+    L.ftk_get_timing.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+    L.ftk_get_timing.restype = C.c_int
+    L.ftk_set_kernel.argtypes = [vp, C.c_char_p]
+    L.ftk_set_kernel.restype = C.c_int
+    L.ftk_kernel_name.argtypes = [vp]
+    L.ftk_kernel_name.restype = C.c_char_p
+    L.ftk_last_error.argtypes = [vp]
+    L.ftk_last_error.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def _is_torch_cuda(x) -> bool:
+    return hasattr(x, "is_cuda") and bool(x.is_cuda)
+
+
+def _ptr_list(ptrs: Sequence[Optional[int]]):
+    arr = (C.c_void_p * len(ptrs))()
+    for k, p in enumerate(ptrs):
+        arr[k] = p
+    return arr
+
+
+class FastTucker:
+    """One tensor + its parameters + the current sample set (an ftk_ctx)."""
+
+    def __init__(self, dims: Sequence[int], idx: Sequence, vals, J: Sequence[int], R: int, init_seed: int = 1):
+        L = load()
+        self._L = L
+        self._ctx = C.c_void_p(None)
+        N = len(dims)
+        if len(idx) != N or len(J) != N:
+            raise ValueError("dims, idx and J must have one entry per mode")
+        self.dims = tuple(int(d) for d in dims)
+        self.J = tuple(int(j) for j in J)
+        self.R = int(R)
+        self.order = N
+        on_device = _is_torch_cuda(vals)
+        if on_device:
+            import torch
+            for a in idx:
+                if not _is_torch_cuda(a) or a.dtype != torch.int32 or not a.is_contiguous():
+                    raise ValueError("idx[n] must be contiguous int32 CUDA tensors when vals is one")
+            if vals.dtype != torch.float32 or not vals.is_contiguous():
+                raise ValueError("vals must be a contiguous float32 tensor")
+            nnz = int(vals.numel())
+            ptrs = [int(a.data_ptr()) for a in idx]
+            vptr = int(vals.data_ptr())
+            flags = FTK_PTRS_DEVICE
+        else:
+            idx = [np.ascontiguousarray(a, dtype=np.int32) for a in idx]
+            vals = np.ascontiguousarray(vals, dtype=np.float32)
+            nnz = int(vals.shape[0])
+            ptrs = [a.ctypes.data for a in idx]
+            vptr = vals.ctypes.data
+            flags = FTK_PTRS_HOST
+        for a in idx:
+            if int(a.shape[0]) != nnz:
+                raise ValueError("idx[n] and vals must all have nnz entries")
+        self.nnz = nnz
+        dims_a = np.asarray(self.dims, dtype=np.int64)
+        J_a = np.asarray(self.J, dtype=np.int32)
+        idx_ptrs = _ptr_list(ptrs)
+        rc = L.ftk_create(C.byref(self._ctx), N, dims_a.ctypes.data, nnz, C.cast(idx_ptrs, C.c_void_p),
+                          vptr, J_a.ctypes.data, self.R, int(init_seed), flags)
+        if rc != FTK_OK:
+            msg = L.ftk_last_error(None)
+            self._ctx = C.c_void_p(None)
+            raise FtkError(rc, msg.decode() if msg else "")
+
+    # -- helpers -------------------------------------------------------------------------------
+    def _check(self, rc: int):
+        if rc != FTK_OK:
+            msg = self._L.ftk_last_error(self._ctx)
+            raise FtkError(rc, msg.decode() if msg else "")
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self._L.ftk_destroy(self._ctx)
+            self._ctx = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    # -- the ABI, one method per entry point ----------------------------------------------------
+    def ftk_sample(self, seed: int, n_samples: int) -> None:
+        self._check(self._L.ftk_sample(self._ctx, int(seed), int(n_samples)))
+        self._n_samples = int(n_samples)
+
+    def ftk_get_samples(self) -> np.ndarray:
+        out = np.empty(getattr(self, "_n_samples", 0) or 1, dtype=np.int64)
+        self._check(self._L.ftk_get_samples(self._ctx, out.ctypes.data))
+        return out
+
+    def ftk_sgd_step(self, lr_A: float, lr_B: float, lambda_A: float, lambda_B: float) -> None:
+        self._check(self._L.ftk_sgd_step(self._ctx, lr_A, lr_B, lambda_A, lambda_B))
+
+    def ftk_rmse(self) -> float:
+        out = C.c_double(0.0)
+        self._check(self._L.ftk_rmse(self._ctx, C.byref(out)))
+        return out.value
+
+    def ftk_mae(self) -> float:
+        out = C.c_double(0.0)
+        self._check(self._L.ftk_mae(self._ctx, C.byref(out)))
+        return out.value
+
+    def ftk_get_factors(self) -> Tuple[List[np.ndarray], List[np.ndarray]]:
+        A = [np.empty((self.dims[n], self.J[n]), dtype=np.float32) for n in range(self.order)]
+        B = [np.empty((self.J[n], self.R), dtype=np.float32) for n in range(self.order)]
+        pa = _ptr_list([a.ctypes.data for a in A])
+        pb = _ptr_list([b.ctypes.data for b in B])
+        self._check(self._L.ftk_get_factors(self._ctx, C.cast(pa, C.c_void_p), C.cast(pb, C.c_void_p)))
+        return A, B
+
+    def ftk_set_factors(self, A: Optional[Sequence[np.ndarray]], B: Optional[Sequence[np.ndarray]]) -> None:
+        keep = []
+        pa = pb = None
+        if A is not None:
+            A = [np.ascontiguousarray(a, dtype=np.float32) for a in A]
+            for n, a in enumerate(A):
+                if a.shape != (self.dims[n], self.J[n]):
+                    raise ValueError("A[%d] must have shape %r" % (n, (self.dims[n], self.J[n])))
+            pa = _ptr_list([a.ctypes.data for a in A])
+            keep.append(A)
+        if B is not None:
+            B = [np.ascontiguousarray(b, dtype=np.float32) for b in B]
+            for n, b in enumerate(B):
+                if b.shape != (self.J[n], self.R):
+                    raise ValueError("B[%d] must have shape %r" % (n, (self.J[n], self.R)))
+            pb = _ptr_list([b.ctypes.data for b in B])
+            keep.append(B)
+        self._check(self._L.ftk_set_factors(self._ctx, C.cast(pa, C.c_void_p) if pa is not None else None,
+                                            C.cast(pb, C.c_void_p) if pb is not None else None))
+
+    def ftk_set_mode(self, mode: int) -> None:
+        self._check(self._L.ftk_set_mode(self._ctx, int(mode)))
+
+    def ftk_set_stream(self, hip_stream: Optional[int]) -> None:
+        self._check(self._L.ftk_set_stream(self._ctx, hip_stream))
+
+    def ftk_set_timing(self, enabled: bool) -> None:
+        self._check(self._L.ftk_set_timing(self._ctx, 1 if enabled else 0))
+
+    def ftk_get_timing(self, which: int, reset: bool = False) -> Tuple[float, int]:
+        ms = C.c_double(0.0)
+        cnt = C.c_int64(0)
+        self._check(self._L.ftk_get_timing(self._ctx, int(which), C.byref(ms), C.byref(cnt), 1 if reset else 0))
+        return ms.value, cnt.value
+
+    def ftk_set_kernel(self, name: str) -> None:
+        self._check(self._L.ftk_set_kernel(self._ctx, name.encode()))
+
+    def ftk_kernel_name(self) -> str:
+        return self._L.ftk_kernel_name(self._ctx).decode()

@@ -1,0 +1,514 @@
+// C ABI of the ftk library (see include/ftk.h for the contract of every entry point).
+// Host side only: argument checks, ownership, the call-order state machine, kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "../../include/ftk.h"
+#include "ftk_kernels_generic.hpp"
+
+using namespace ftk;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+enum Variant { V_GENERIC = 0 };
+
+struct TimingSlot {
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pending;
+    double total_ms = 0.0;
+    int64_t launches = 0;
+};
+
+}  // namespace
+
+struct ftk_ctx {
+    int order = 0;
+    int64_t dims[kMaxOrder] = {};
+    int64_t nnz = 0;
+    Layout L = {};
+    long long A_total = 0;   // floats in the packed A (and dA) allocation, multiple of 64
+
+    int32_t* d_idx[kMaxOrder] = {};
+    float* d_val = nullptr;
+    float* d_A = nullptr;
+    float* d_dA = nullptr;
+    float* d_B = nullptr;
+    float* d_GB = nullptr;
+    double* d_sums = nullptr;
+    unsigned int* d_flag = nullptr;
+
+    uint32_t* d_pos = nullptr;
+    int32_t* d_bidx = nullptr;
+    float* d_bval = nullptr;
+    long long cap = 0;
+    long long n_samples = 0;
+
+    hipStream_t stream = nullptr;
+    int device = 0;
+    int num_cu = 1;
+    int max_lds = 65536;
+    int mode = FTK_SYNC;
+
+    int variant = V_GENERIC;
+    bool variant_forced = false;
+    int gen_threads = 0;     // block size of grad_generic for this shape (0: does not fit)
+    int gen_b_in_lds = 0;
+    size_t gen_lds_bytes = 0;
+
+    bool timing = false;
+    TimingSlot slots[FTK_K_COUNT];
+
+    std::string err;
+};
+
+namespace {
+
+int fail(ftk_ctx* c, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c)
+        c->err = buf;
+    else
+        g_create_error = buf;
+    return code;
+}
+
+#define FTK_HIP(c, call)                                                                         \
+    do {                                                                                         \
+        hipError_t e_ = (call);                                                                  \
+        if (e_ != hipSuccess)                                                                    \
+            return fail((c), e_ == hipErrorOutOfMemory ? FTK_ENOMEM : FTK_EDEVICE, "%s: %s", #call, \
+                        hipGetErrorString(e_));                                                  \
+    } while (0)
+
+inline int blocks_for(long long work, int threads, int cap_blocks) {
+    long long b = (work + threads - 1) / threads;
+    if (b < 1) b = 1;
+    if (b > cap_blocks) b = cap_blocks;
+    return (int)b;
+}
+
+// event bracket around one kernel launch when timing is on
+struct Bracket {
+    ftk_ctx* c;
+    int slot;
+    hipEvent_t a = nullptr, b = nullptr;
+    bool on = false;
+    Bracket(ftk_ctx* ctx, int s) : c(ctx), slot(s) {
+        if (!c->timing) return;
+        if (hipEventCreate(&a) != hipSuccess) return;
+        if (hipEventCreate(&b) != hipSuccess) {
+            hipEventDestroy(a);
+            return;
+        }
+        on = hipEventRecord(a, c->stream) == hipSuccess;
+        if (!on) {
+            hipEventDestroy(a);
+            hipEventDestroy(b);
+        }
+    }
+    ~Bracket() {
+        if (!on) return;
+        if (hipEventRecord(b, c->stream) == hipSuccess)
+            c->slots[slot].pending.emplace_back(a, b);
+        else {
+            hipEventDestroy(a);
+            hipEventDestroy(b);
+        }
+    }
+};
+
+void drop_pending(ftk_ctx* c) {
+    for (auto& s : c->slots) {
+        for (auto& p : s.pending) {
+            hipEventDestroy(p.first);
+            hipEventDestroy(p.second);
+        }
+        s.pending.clear();
+    }
+}
+
+void pick_generic_config(ftk_ctx* c) {
+    const long long NR = (long long)c->order * c->L.R, BT = c->L.B_total;
+    c->gen_threads = 0;
+    for (int T : {256, 128, 64})
+        for (int b : {1, 0}) {
+            const long long bytes = 4LL * (2 * NR * T + (T / 64) * BT + (b ? BT : 0));
+            if (bytes <= c->max_lds) {
+                c->gen_threads = T;
+                c->gen_b_in_lds = b;
+                c->gen_lds_bytes = (size_t)bytes;
+                return;
+            }
+        }
+}
+
+int launch_grad(ftk_ctx* c, float lambda_A) {
+    GradArgs g;
+    g.L = c->L;
+    g.batch = Batch{c->d_bidx, c->d_bval, c->n_samples, c->cap};
+    g.A = c->d_A;
+    g.B = c->d_B;
+    g.dA = c->d_dA;
+    g.GB = c->d_GB;
+    g.lambda_A = lambda_A;
+    g.b_in_lds = c->gen_b_in_lds;
+    if (c->gen_threads == 0)
+        return fail(c, FTK_EUNSUPPORTED, "generic gradient kernel: N*R = %d and sum J_n R = %d exceed the LDS budget",
+                    c->order * c->L.R, c->L.B_total);
+    const int T = c->gen_threads;
+    const int grid = blocks_for(c->n_samples, T, c->num_cu * 4);
+    if (c->gen_lds_bytes > 65536)
+        FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_generic_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->gen_lds_bytes));
+    Bracket t(c, FTK_K_GRAD);
+    hipLaunchKernelGGL(grad_generic_kernel, dim3(grid), dim3(T), c->gen_lds_bytes, c->stream, g);
+    FTK_HIP(c, hipGetLastError());
+    return FTK_OK;
+}
+
+int launch_errors(ftk_ctx* c, double* host_sums) {
+    CooSoA coo;
+    for (int n = 0; n < kMaxOrder; ++n) coo.idx[n] = c->d_idx[n];
+    coo.val = c->d_val;
+    FTK_HIP(c, hipMemsetAsync(c->d_sums, 0, 2 * sizeof(double), c->stream));
+    const int b_in_lds = (size_t)c->L.B_total * 4 <= 65536 - 256;
+    const size_t lds = b_in_lds ? (size_t)c->L.B_total * 4 : 0;
+    const int grid = blocks_for(c->nnz, 256, c->num_cu * 8);
+    hipLaunchKernelGGL(errors_generic_kernel, dim3(grid), dim3(256), lds, c->stream, coo, c->L, (uint64_t)c->nnz,
+                       (const float*)c->d_A, (const float*)c->d_B, b_in_lds, c->d_sums);
+    FTK_HIP(c, hipGetLastError());
+    FTK_HIP(c, hipMemcpyAsync(host_sums, c->d_sums, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    return FTK_OK;
+}
+
+void release(ftk_ctx* c) {
+    if (!c) return;
+    hipStreamSynchronize(c->stream);
+    drop_pending(c);
+    for (int n = 0; n < kMaxOrder; ++n)
+        if (c->d_idx[n]) hipFree(c->d_idx[n]);
+    void* ptrs[] = {c->d_val, c->d_A, c->d_dA, c->d_B, c->d_GB, c->d_sums, c->d_flag, c->d_pos, c->d_bidx, c->d_bval};
+    for (void* p : ptrs)
+        if (p) hipFree(p);
+    delete c;
+}
+
+int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, const float* vals, uint64_t init_seed,
+                uint32_t flags) {
+    const int N = c->order;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(c, FTK_EDEVICE, "no HIP device available");
+    FTK_HIP(c, hipGetDevice(&c->device));
+    FTK_HIP(c, hipDeviceGetAttribute(&c->num_cu, hipDeviceAttributeMultiprocessorCount, c->device));
+    FTK_HIP(c, hipDeviceGetAttribute(&c->max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, c->device));
+    if (c->num_cu < 1) c->num_cu = 1;
+    if (c->max_lds < 65536) c->max_lds = 65536;
+
+    // packed parameter layout: every mode starts on a 256-byte boundary
+    long long a_off = 0;
+    int b_off = 0;
+    for (int n = 0; n < N; ++n) {
+        c->L.A_off[n] = a_off;
+        c->L.B_off[n] = b_off;
+        a_off += ((dims[n] * c->L.J[n] + 63) / 64) * 64;
+        b_off += c->L.J[n] * c->L.R;
+    }
+    c->A_total = a_off;
+    c->L.B_total = b_off;
+    pick_generic_config(c);
+    if (c->gen_threads == 0)
+        return fail(c, FTK_EUNSUPPORTED, "N*R = %d with sum J_n R = %d exceeds the kernels' LDS budget", N * c->L.R,
+                    c->L.B_total);
+
+    const hipMemcpyKind kind = (flags & FTK_PTRS_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    FTK_HIP(c, hipMalloc(&c->d_flag, sizeof(unsigned int)));
+    FTK_HIP(c, hipMemset(c->d_flag, 0, sizeof(unsigned int)));
+    for (int n = 0; n < N; ++n) {
+        FTK_HIP(c, hipMalloc(&c->d_idx[n], (size_t)c->nnz * sizeof(int32_t)));
+        FTK_HIP(c, hipMemcpy(c->d_idx[n], idx[n], (size_t)c->nnz * sizeof(int32_t), kind));
+        hipLaunchKernelGGL(check_range_kernel, dim3(blocks_for(c->nnz, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
+                           (const int32_t*)c->d_idx[n], (uint64_t)c->nnz, (int32_t)dims[n], c->d_flag);
+        FTK_HIP(c, hipGetLastError());
+        unsigned int bad = 0;
+        FTK_HIP(c, hipMemcpy(&bad, c->d_flag, sizeof bad, hipMemcpyDeviceToHost));
+        if (bad) return fail(c, FTK_EINVAL, "idx[%d] holds %u entries outside [0, %lld)", n, bad, (long long)dims[n]);
+    }
+    FTK_HIP(c, hipMalloc(&c->d_val, (size_t)c->nnz * sizeof(float)));
+    FTK_HIP(c, hipMemcpy(c->d_val, vals, (size_t)c->nnz * sizeof(float), kind));
+
+    FTK_HIP(c, hipMalloc(&c->d_A, (size_t)c->A_total * sizeof(float)));
+    FTK_HIP(c, hipMalloc(&c->d_dA, (size_t)c->A_total * sizeof(float)));
+    FTK_HIP(c, hipMalloc(&c->d_B, (size_t)c->L.B_total * sizeof(float)));
+    FTK_HIP(c, hipMalloc(&c->d_GB, (size_t)c->L.B_total * sizeof(float)));
+    FTK_HIP(c, hipMalloc(&c->d_sums, 2 * sizeof(double)));
+    FTK_HIP(c, hipMemset(c->d_A, 0, (size_t)c->A_total * sizeof(float)));
+    FTK_HIP(c, hipMemset(c->d_dA, 0, (size_t)c->A_total * sizeof(float)));
+    FTK_HIP(c, hipMemset(c->d_GB, 0, (size_t)c->L.B_total * sizeof(float)));
+    for (int n = 0; n < N; ++n) {
+        const long long na = dims[n] * c->L.J[n], nb = (long long)c->L.J[n] * c->L.R;
+        hipLaunchKernelGGL(init_uniform_kernel, dim3(blocks_for(na, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
+                           c->d_A + c->L.A_off[n], na, init_seed, (uint32_t)n);
+        hipLaunchKernelGGL(init_uniform_kernel, dim3(blocks_for(nb, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
+                           c->d_B + c->L.B_off[n], nb, init_seed, (uint32_t)(N + n));
+    }
+    FTK_HIP(c, hipGetLastError());
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    return FTK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ftk_create(ftk_ctx** out, int32_t order, const int64_t* dims, int64_t nnz, const int32_t* const* idx,
+               const float* vals, const int32_t* J, int32_t R, uint64_t init_seed, uint32_t flags) {
+    if (!out) return fail(nullptr, FTK_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (order < 1 || order > FTK_MAX_ORDER) return fail(nullptr, FTK_EINVAL, "order %d outside 1..%d", order, FTK_MAX_ORDER);
+    if (!dims || !idx || !vals || !J) return fail(nullptr, FTK_EINVAL, "NULL argument");
+    if (nnz < 1 || nnz >= (1LL << 32)) return fail(nullptr, FTK_EINVAL, "nnz %lld outside 1..2^32-1", (long long)nnz);
+    if (R < 1 || R > 1024) return fail(nullptr, FTK_EINVAL, "R %d outside 1..1024", R);
+    if (flags & ~(uint32_t)FTK_PTRS_DEVICE) return fail(nullptr, FTK_EINVAL, "unknown flag bits 0x%x", flags);
+    for (int n = 0; n < order; ++n) {
+        if (dims[n] < 1 || dims[n] >= (1LL << 31))
+            return fail(nullptr, FTK_EINVAL, "dims[%d] = %lld outside 1..2^31-1", n, (long long)dims[n]);
+        if (J[n] < 1 || J[n] > 1024) return fail(nullptr, FTK_EINVAL, "J[%d] = %d outside 1..1024", n, J[n]);
+        if (!idx[n]) return fail(nullptr, FTK_EINVAL, "idx[%d] is NULL", n);
+    }
+    ftk_ctx* c = new (std::nothrow) ftk_ctx();
+    if (!c) return fail(nullptr, FTK_ENOMEM, "host allocation failed");
+    c->order = order;
+    c->nnz = nnz;
+    c->L.order = order;
+    c->L.R = R;
+    for (int n = 0; n < order; ++n) {
+        c->dims[n] = dims[n];
+        c->L.J[n] = J[n];
+    }
+    int rc;
+    try {
+        rc = create_impl(c, dims, idx, vals, init_seed, flags);
+    } catch (...) {
+        rc = fail(c, FTK_ENOMEM, "host allocation failed");
+    }
+    if (rc != FTK_OK) {
+        g_create_error = c->err;
+        release(c);
+        return rc;
+    }
+    *out = c;
+    return FTK_OK;
+}
+
+void ftk_destroy(ftk_ctx* ctx) { release(ctx); }
+
+int ftk_sample(ftk_ctx* c, uint64_t seed, int64_t n_samples) {
+    if (!c) return FTK_EINVAL;
+    if (n_samples < 1 || n_samples >= (1LL << 31))
+        return fail(c, FTK_EINVAL, "n_samples %lld outside 1..2^31-1", (long long)n_samples);
+    if (n_samples > c->cap) {
+        FTK_HIP(c, hipStreamSynchronize(c->stream));
+        if (c->d_pos) hipFree(c->d_pos);
+        if (c->d_bidx) hipFree(c->d_bidx);
+        if (c->d_bval) hipFree(c->d_bval);
+        c->d_pos = nullptr;
+        c->d_bidx = nullptr;
+        c->d_bval = nullptr;
+        c->cap = 0;
+        c->n_samples = 0;
+        const long long cap = ((n_samples + 255) / 256) * 256;
+        FTK_HIP(c, hipMalloc(&c->d_pos, (size_t)cap * sizeof(uint32_t)));
+        FTK_HIP(c, hipMalloc(&c->d_bidx, (size_t)cap * c->order * sizeof(int32_t)));
+        FTK_HIP(c, hipMalloc(&c->d_bval, (size_t)cap * sizeof(float)));
+        c->cap = cap;
+    }
+    CooSoA coo;
+    for (int n = 0; n < kMaxOrder; ++n) coo.idx[n] = c->d_idx[n];
+    coo.val = c->d_val;
+    {
+        Bracket t(c, FTK_K_SAMPLE);
+        hipLaunchKernelGGL(sample_gather_kernel, dim3((unsigned)((n_samples + 255) / 256)), dim3(256), 0, c->stream, coo,
+                           c->order, (uint64_t)c->nnz, seed, (long long)n_samples, c->cap, c->d_pos, c->d_bidx,
+                           c->d_bval);
+    }
+    FTK_HIP(c, hipGetLastError());
+    c->n_samples = n_samples;
+    return FTK_OK;
+}
+
+int ftk_get_samples(ftk_ctx* c, int64_t* pos_out) {
+    if (!c) return FTK_EINVAL;
+    if (!pos_out) return fail(c, FTK_EINVAL, "pos_out is NULL");
+    if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_get_samples before ftk_sample");
+    try {
+        std::vector<uint32_t> tmp((size_t)c->n_samples);
+        FTK_HIP(c, hipMemcpyAsync(tmp.data(), c->d_pos, tmp.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream));
+        FTK_HIP(c, hipStreamSynchronize(c->stream));
+        for (size_t k = 0; k < tmp.size(); ++k) pos_out[k] = (int64_t)tmp[k];
+    } catch (...) {
+        return fail(c, FTK_ENOMEM, "host allocation failed");
+    }
+    return FTK_OK;
+}
+
+int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
+    if (!c) return FTK_EINVAL;
+    if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step before ftk_sample");
+    if (c->mode != FTK_SYNC) return fail(c, FTK_EUNSUPPORTED, "only FTK_SYNC is built");
+    int rc = launch_grad(c, lambda_A);
+    if (rc != FTK_OK) return rc;
+    {
+        Bracket t(c, FTK_K_APPLY_A);
+        const long long n4 = c->A_total / 4;
+        hipLaunchKernelGGL(apply_A_kernel, dim3(blocks_for(n4, 256, c->num_cu * 16)), dim3(256), 0, c->stream, c->d_A,
+                           c->d_dA, n4, lr_A);
+    }
+    FTK_HIP(c, hipGetLastError());
+    {
+        Bracket t(c, FTK_K_APPLY_B);
+        hipLaunchKernelGGL(apply_B_kernel, dim3((c->L.B_total + 255) / 256), dim3(256), 0, c->stream, c->d_B, c->d_GB,
+                           c->L.B_total, lr_B, lambda_B, 1.0f / (float)c->n_samples);
+    }
+    FTK_HIP(c, hipGetLastError());
+    return FTK_OK;
+}
+
+int ftk_rmse(ftk_ctx* c, double* out) {
+    if (!c) return FTK_EINVAL;
+    if (!out) return fail(c, FTK_EINVAL, "out is NULL");
+    double s[2] = {0.0, 0.0};
+    int rc = launch_errors(c, s);
+    if (rc != FTK_OK) return rc;
+    *out = sqrt(s[0] / (double)c->nnz);
+    return FTK_OK;
+}
+
+int ftk_mae(ftk_ctx* c, double* out) {
+    if (!c) return FTK_EINVAL;
+    if (!out) return fail(c, FTK_EINVAL, "out is NULL");
+    double s[2] = {0.0, 0.0};
+    int rc = launch_errors(c, s);
+    if (rc != FTK_OK) return rc;
+    *out = s[1] / (double)c->nnz;
+    return FTK_OK;
+}
+
+int ftk_get_factors(ftk_ctx* c, float* const* A_out, float* const* B_out) {
+    if (!c) return FTK_EINVAL;
+    for (int n = 0; n < c->order; ++n) {
+        if (A_out && A_out[n])
+            FTK_HIP(c, hipMemcpyAsync(A_out[n], c->d_A + c->L.A_off[n], (size_t)c->dims[n] * c->L.J[n] * sizeof(float),
+                                      hipMemcpyDeviceToHost, c->stream));
+        if (B_out && B_out[n])
+            FTK_HIP(c, hipMemcpyAsync(B_out[n], c->d_B + c->L.B_off[n], (size_t)c->L.J[n] * c->L.R * sizeof(float),
+                                      hipMemcpyDeviceToHost, c->stream));
+    }
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    return FTK_OK;
+}
+
+int ftk_set_factors(ftk_ctx* c, const float* const* A_in, const float* const* B_in) {
+    if (!c) return FTK_EINVAL;
+    for (int n = 0; n < c->order; ++n) {
+        if (A_in && A_in[n])
+            FTK_HIP(c, hipMemcpyAsync(c->d_A + c->L.A_off[n], A_in[n], (size_t)c->dims[n] * c->L.J[n] * sizeof(float),
+                                      hipMemcpyHostToDevice, c->stream));
+        if (B_in && B_in[n])
+            FTK_HIP(c, hipMemcpyAsync(c->d_B + c->L.B_off[n], B_in[n], (size_t)c->L.J[n] * c->L.R * sizeof(float),
+                                      hipMemcpyHostToDevice, c->stream));
+    }
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    return FTK_OK;
+}
+
+int ftk_set_mode(ftk_ctx* c, int mode) {
+    if (!c) return FTK_EINVAL;
+    if (mode != FTK_SYNC && mode != FTK_HOGWILD) return fail(c, FTK_EINVAL, "unknown mode %d", mode);
+    if (mode == FTK_HOGWILD) return fail(c, FTK_EUNSUPPORTED, "FTK_HOGWILD is not built");
+    c->mode = mode;
+    return FTK_OK;
+}
+
+int ftk_set_stream(ftk_ctx* c, void* hip_stream) {
+    if (!c) return FTK_EINVAL;
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    drop_pending(c);
+    c->stream = (hipStream_t)hip_stream;
+    return FTK_OK;
+}
+
+int ftk_set_timing(ftk_ctx* c, int enabled) {
+    if (!c) return FTK_EINVAL;
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    drop_pending(c);
+    for (auto& s : c->slots) {
+        s.total_ms = 0.0;
+        s.launches = 0;
+    }
+    c->timing = enabled != 0;
+    return FTK_OK;
+}
+
+int ftk_get_timing(ftk_ctx* c, int which, double* total_ms, int64_t* launches, int reset) {
+    if (!c) return FTK_EINVAL;
+    if (which < 0 || which >= FTK_K_COUNT) return fail(c, FTK_EINVAL, "unknown kernel slot %d", which);
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    for (auto& s : c->slots) {
+        for (auto& p : s.pending) {
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, p.first, p.second) == hipSuccess) {
+                s.total_ms += (double)ms;
+                s.launches += 1;
+            }
+            hipEventDestroy(p.first);
+            hipEventDestroy(p.second);
+        }
+        s.pending.clear();
+    }
+    if (total_ms) *total_ms = c->slots[which].total_ms;
+    if (launches) *launches = c->slots[which].launches;
+    if (reset) {
+        c->slots[which].total_ms = 0.0;
+        c->slots[which].launches = 0;
+    }
+    return FTK_OK;
+}
+
+int ftk_set_kernel(ftk_ctx* c, const char* name) {
+    if (!c) return FTK_EINVAL;
+    if (!name) return fail(c, FTK_EINVAL, "name is NULL");
+    if (!strcmp(name, "auto")) {
+        c->variant_forced = false;
+        c->variant = V_GENERIC;
+        return FTK_OK;
+    }
+    if (!strcmp(name, "generic")) {
+        c->variant_forced = true;
+        c->variant = V_GENERIC;
+        return FTK_OK;
+    }
+    return fail(c, FTK_EUNSUPPORTED, "no kernel variant named '%s' for this shape", name);
+}
+
+const char* ftk_kernel_name(const ftk_ctx* c) {
+    (void)c;
+    return "generic";
+}
+
+const char* ftk_last_error(const ftk_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,280 @@
+// Shape-generic kernels: any order N <= 8, any J_n, any R within the LDS budget.
+// One lane owns one sampled nonzero.  These are the reference-speed path; shapes with a
+// specialised kernel never run grad_generic in the default configuration.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ftk_philox.hpp"
+
+namespace ftk {
+
+constexpr int kMaxOrder = 8;
+
+// Everything a kernel needs to find the parameters.  A^(n) for all modes share one allocation
+// (mode n starts at float offset A_off[n]); so do dA^(n) (same offsets), B^(n) and GB^(n)
+// (float offset B_off[n], row-major J_n x R).
+struct Layout {
+    int order;
+    int R;
+    int J[kMaxOrder];
+    int B_off[kMaxOrder];
+    long long A_off[kMaxOrder];
+    int B_total;   // sum_n J_n * R
+};
+
+struct Batch {
+    const int32_t* idx;   // [order][cap]: idx[n * cap + k] = i_n of sample k
+    const float* val;     // [cap]
+    long long count;      // M = |Psi|
+    long long cap;
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Psi: positions from Philox, and the sampled nonzeros gathered into a dense batch
+// (step a1 + a2: the only place the COO arrays are read with random access).
+// ---------------------------------------------------------------------------------------------
+struct CooSoA {
+    const int32_t* idx[kMaxOrder];
+    const float* val;
+};
+
+__global__ void __launch_bounds__(256) sample_gather_kernel(CooSoA coo, int order, uint64_t nnz, uint64_t seed,
+                                                            long long M, long long cap, uint32_t* __restrict__ pos,
+                                                            int32_t* __restrict__ bidx, float* __restrict__ bval) {
+    const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= M) return;
+    const uint32_t p = sample_position(seed, (uint64_t)k, nnz);
+    pos[k] = p;
+    for (int n = 0; n < order; ++n) bidx[(long long)n * cap + k] = coo.idx[n][p];
+    bval[k] = coo.val[p];
+}
+
+// ---------------------------------------------------------------------------------------------
+// gradient pass, one lane per sample
+//   LDS: c[N*R][T] | w[N*R][T] | per-wave GB partial sums [T/64][B_total] | (optional) B [B_total]
+// ---------------------------------------------------------------------------------------------
+struct GradArgs {
+    Layout L;
+    Batch batch;
+    const float* A;
+    const float* B;
+    float* dA;
+    float* GB;
+    float lambda_A;
+    int b_in_lds;
+};
+
+__global__ void grad_generic_kernel(GradArgs g) {
+    extern __shared__ float lds[];
+    const int N = g.L.order, R = g.L.R, T = blockDim.x, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, BT = g.L.B_total;
+    float* c_l = lds;
+    float* w_l = c_l + (size_t)N * R * T;
+    float* gb_w = w_l + (size_t)N * R * T + (size_t)wave * BT;
+    float* b_l = w_l + (size_t)N * R * T + (size_t)(T >> 6) * BT;
+
+    for (int q = lane; q < BT; q += 64) gb_w[q] = 0.0f;
+    if (g.b_in_lds)
+        for (int q = tid; q < BT; q += T) b_l[q] = g.B[q];
+    __syncthreads();
+    const float* Bm = g.b_in_lds ? b_l : g.B;
+
+    const long long M = g.batch.count, cap = g.batch.cap;
+    for (long long base = (long long)blockIdx.x * T; base < M; base += (long long)gridDim.x * T) {
+        const long long k = base + tid;
+        const bool act = k < M;
+        float e = 0.0f;
+        if (act) {
+            // c^(n)_r = a^(n) . B^(n)[:, r]
+            for (int n = 0; n < N; ++n) {
+                const int Jn = g.L.J[n];
+                const float* row = g.A + g.L.A_off[n] + (long long)g.batch.idx[(long long)n * cap + k] * Jn;
+                const float* Bn = Bm + g.L.B_off[n];
+                for (int r = 0; r < R; ++r) {
+                    float acc = 0.0f;
+                    for (int j = 0; j < Jn; ++j) acc = fmaf(row[j], Bn[j * R + r], acc);
+                    c_l[(size_t)(n * R + r) * T + tid] = acc;
+                }
+            }
+            // leave-one-out products by a prefix and a suffix sweep over the modes
+            float xhat = 0.0f;
+            for (int r = 0; r < R; ++r) {
+                float run = 1.0f;
+                for (int n = 0; n < N; ++n) {
+                    w_l[(size_t)(n * R + r) * T + tid] = run;
+                    run *= c_l[(size_t)(n * R + r) * T + tid];
+                }
+                xhat += run;
+                run = 1.0f;
+                for (int n = N - 1; n >= 0; --n) {
+                    w_l[(size_t)(n * R + r) * T + tid] *= run;
+                    run *= c_l[(size_t)(n * R + r) * T + tid];
+                }
+            }
+            e = g.batch.val[k] - xhat;
+            // factor-row gradient: -e GS^(n) + lambda_A a^(n), accumulated into dA
+            for (int n = 0; n < N; ++n) {
+                const int Jn = g.L.J[n];
+                const long long roff = g.L.A_off[n] + (long long)g.batch.idx[(long long)n * cap + k] * Jn;
+                const float* Bn = Bm + g.L.B_off[n];
+                for (int j = 0; j < Jn; ++j) {
+                    float gs = 0.0f;
+                    for (int r = 0; r < R; ++r) gs = fmaf(Bn[j * R + r], w_l[(size_t)(n * R + r) * T + tid], gs);
+                    atomicAdd(g.dA + roff + j, fmaf(-e, gs, g.lambda_A * g.A[roff + j]));
+                }
+            }
+        }
+        // core gradient: sum over the wave's samples of -e a_j w_r, kept per wave in LDS
+        for (int n = 0; n < N; ++n) {
+            const int Jn = g.L.J[n];
+            const float* row = g.A + g.L.A_off[n];
+            if (act) row += (long long)g.batch.idx[(long long)n * cap + k] * Jn;
+            for (int j = 0; j < Jn; ++j) {
+                const float ea = act ? -e * row[j] : 0.0f;
+                for (int r = 0; r < R; ++r) {
+                    float v = act ? ea * w_l[(size_t)(n * R + r) * T + tid] : 0.0f;
+                    v = wave_sum(v);
+                    if (lane == 0) gb_w[g.L.B_off[n] + j * R + r] += v;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int q = lane; q < BT; q += 64) {
+        const float v = gb_w[q];
+        if (v != 0.0f) atomicAdd(g.GB + q, v);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// update passes
+// ---------------------------------------------------------------------------------------------
+// A <- A - lr_A dA wherever dA != 0, and dA <- 0 (dA == 0 means: untouched, or a zero gradient).
+__global__ void __launch_bounds__(256) apply_A_kernel(float* __restrict__ A, float* __restrict__ dA,
+                                                      long long n4, float lr_A) {
+    float4* A4 = reinterpret_cast<float4*>(A);
+    float4* D4 = reinterpret_cast<float4*>(dA);
+    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < n4;
+         q += (long long)gridDim.x * blockDim.x) {
+        const float4 d = D4[q];
+        if (d.x != 0.0f || d.y != 0.0f || d.z != 0.0f || d.w != 0.0f) {
+            float4 a = A4[q];
+            a.x = fmaf(-lr_A, d.x, a.x);
+            a.y = fmaf(-lr_A, d.y, a.y);
+            a.z = fmaf(-lr_A, d.z, a.z);
+            a.w = fmaf(-lr_A, d.w, a.w);
+            A4[q] = a;
+            D4[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+    }
+}
+
+// B <- B - lr_B (GB / M + lambda_B B), GB <- 0
+__global__ void __launch_bounds__(256) apply_B_kernel(float* __restrict__ B, float* __restrict__ GB, int count,
+                                                      float lr_B, float lambda_B, float inv_M) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= count) return;
+    const float b = B[q];
+    B[q] = b - lr_B * fmaf(GB[q], inv_M, lambda_B * b);
+    GB[q] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// whole-tensor error sums (RMSE / MAE): one lane per stored nonzero, streaming over Omega
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) errors_generic_kernel(CooSoA coo, Layout L, uint64_t nnz,
+                                                             const float* __restrict__ A,
+                                                             const float* __restrict__ B, int b_in_lds,
+                                                             double* __restrict__ sums /* [2]: sse, sae */) {
+    extern __shared__ float lds[];
+    __shared__ double red[2][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (b_in_lds) {
+        for (int q = tid; q < L.B_total; q += blockDim.x) lds[q] = B[q];
+        __syncthreads();
+    }
+    const float* Bm = b_in_lds ? lds : B;
+    double sse = 0.0, sae = 0.0;
+    for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + tid; p < nnz; p += (uint64_t)gridDim.x * blockDim.x) {
+        float xhat = 0.0f;
+        for (int r = 0; r < L.R; ++r) {
+            float prod = 1.0f;
+            for (int n = 0; n < L.order; ++n) {
+                const int Jn = L.J[n];
+                const float* row = A + L.A_off[n] + (long long)coo.idx[n][p] * Jn;
+                const float* Bn = Bm + L.B_off[n];
+                float acc = 0.0f;
+                for (int j = 0; j < Jn; ++j) acc = fmaf(row[j], Bn[j * L.R + r], acc);
+                prod *= acc;
+            }
+            xhat += prod;
+        }
+        const double e = (double)coo.val[p] - (double)xhat;
+        sse += e * e;
+        sae += fabs(e);
+    }
+    sse = wave_sum(sse);
+    sae = wave_sum(sae);
+    if (lane == 0) {
+        red[0][wave] = sse;
+        red[1][wave] = sae;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double a = 0.0, b = 0.0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) {
+            a += red[0][w];
+            b += red[1][w];
+        }
+        atomicAdd(sums + 0, a);
+        atomicAdd(sums + 1, b);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// set-up kernels
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) init_uniform_kernel(float* __restrict__ out, long long count,
+                                                           uint64_t init_seed, uint32_t array_id) {
+    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < count;
+         q += (long long)gridDim.x * blockDim.x)
+        out[q] = init_value(init_seed, array_id, (uint64_t)q);
+}
+
+// counts entries outside [0, dim)
+__global__ void __launch_bounds__(256) check_range_kernel(const int32_t* __restrict__ idx, uint64_t nnz, int32_t dim,
+                                                          unsigned int* __restrict__ bad) {
+    unsigned int mine = 0;
+    for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (uint64_t)gridDim.x * blockDim.x) {
+        const int32_t v = idx[p];
+        mine += (v < 0 || v >= dim) ? 1u : 0u;
+    }
+    if (mine) atomicAdd(bad, mine);
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(float* __restrict__ out, long long count) {
+    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < count;
+         q += (long long)gridDim.x * blockDim.x)
+        out[q] = 0.0f;
+}
+
+__global__ void __launch_bounds__(256) widen_positions_kernel(const uint32_t* __restrict__ pos, long long count,
+                                                              long long* __restrict__ out) {
+    const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < count) out[k] = (long long)pos[k];
+}
+
+}  // namespace ftk

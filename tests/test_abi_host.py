@@ -1,0 +1,84 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2204_07104_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ftk.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ftk_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_list_the_same_symbols():
+    assert declared_functions() == sorted(binding.SYMBOLS)
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.load()
+    for name in declared_functions():
+        assert getattr(L, name) is not None
+
+
+def _create(order, dims, nnz, idx_ptrs, vals_ptr, J, R, flags=0):
+    L = binding.load()
+    ctx = C.c_void_p(None)
+    dims_a = np.asarray(dims, dtype=np.int64)
+    J_a = np.asarray(J, dtype=np.int32)
+    arr = (C.c_void_p * max(1, len(idx_ptrs)))(*idx_ptrs)
+    rc = L.ftk_create(C.byref(ctx), order, dims_a.ctypes.data, nnz, C.cast(arr, C.c_void_p), vals_ptr,
+                      J_a.ctypes.data, R, 1, flags)
+    return rc, ctx, L.ftk_last_error(None).decode()
+
+
+def test_create_rejects_bad_arguments_without_a_device():
+    i0 = np.zeros(4, dtype=np.int32)
+    v = np.ones(4, dtype=np.float32)
+    good = dict(order=2, dims=(3, 3), nnz=4, idx_ptrs=[i0.ctypes.data, i0.ctypes.data], vals_ptr=v.ctypes.data,
+                J=(2, 2), R=2)
+    cases = [
+        dict(good, order=0), dict(good, order=9), dict(good, nnz=0), dict(good, nnz=1 << 32),
+        dict(good, dims=(0, 3)), dict(good, dims=(3, 1 << 31)), dict(good, J=(0, 2)), dict(good, R=0),
+        dict(good, idx_ptrs=[i0.ctypes.data, None]), dict(good, vals_ptr=None), dict(good, flags=8),
+    ]
+    for kw in cases:
+        rc, ctx, msg = _create(**kw)
+        assert rc == binding.FTK_EINVAL, (kw, rc, msg)
+        assert not ctx.value
+        assert msg
+
+
+def test_null_context_is_rejected_everywhere():
+    L = binding.load()
+    d = C.c_double(0.0)
+    assert L.ftk_sample(None, 1, 1) == binding.FTK_EINVAL
+    assert L.ftk_sgd_step(None, 0.0, 0.0, 0.0, 0.0) == binding.FTK_EINVAL
+    assert L.ftk_rmse(None, C.byref(d)) == binding.FTK_EINVAL
+    assert L.ftk_mae(None, C.byref(d)) == binding.FTK_EINVAL
+    assert L.ftk_get_factors(None, None, None) == binding.FTK_EINVAL
+    assert L.ftk_set_factors(None, None, None) == binding.FTK_EINVAL
+    assert L.ftk_get_samples(None, None) == binding.FTK_EINVAL
+    assert L.ftk_set_mode(None, 0) == binding.FTK_EINVAL
+    assert L.ftk_set_stream(None, None) == binding.FTK_EINVAL
+    assert L.ftk_set_timing(None, 1) == binding.FTK_EINVAL
+    assert L.ftk_set_kernel(None, b"auto") == binding.FTK_EINVAL
+    L.ftk_destroy(None)
+    assert L.ftk_kernel_name(None) is not None
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2204_07104_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "ftk_oracle" not in text, f

@@ -1,0 +1,280 @@
+"""Parity of the HIP path against the CPU oracle (needs an MI355X: run with -m gpu).
+
+Bars (from the benchmark spec): sampled index sets bit-exact; after one synchronous step every
+parameter within 1e-4 relative / 1e-6 absolute of the oracle; RMSE over 10 steps within 1e-3
+relative.  Everything goes through the C ABI (binding.FastTucker); every input is seeded.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2204_07104_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-4, 1e-6
+
+
+def announce(msg):
+    print("[case] " + msg, flush=True)
+
+
+def assert_params_close(got, want, what):
+    for n, (g, w) in enumerate(zip(got, want)):
+        err = np.abs(g.astype(np.float64) - w.astype(np.float64))
+        bound = ATOL + RTOL * np.abs(w.astype(np.float64))
+        worst = float((err - bound).max())
+        assert worst <= 0.0, "%s[%d]: max excess over tolerance %.3e (max abs err %.3e)" % (what, n, worst, float(err.max()))
+
+
+def oracle_state(w):
+    return oracle.init_factors(w.init_seed, w.dims, w.J, w.R)
+
+
+def one_step_case(w, idx, vals, A0=None, B0=None, seed=None, kernel=None):
+    seed = w.sample_seed0 if seed is None else seed
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
+        if kernel:
+            ft.ftk_set_kernel(kernel)
+        if A0 is not None:
+            ft.ftk_set_factors(A0, B0)
+            A, B = [a.copy() for a in A0], [b.copy() for b in B0]
+        else:
+            A, B = oracle_state(w)
+            gA, gB = ft.ftk_get_factors()
+            for x, y in zip(gA + gB, A + B):
+                assert np.array_equal(x, y), "initial parameters differ from the oracle's"
+        ft.ftk_sample(seed, w.n_samples)
+        pos = ft.ftk_get_samples()
+        want = oracle.sample_positions(seed, w.n_samples, w.nnz)
+        assert np.array_equal(pos, want), "sample set differs from the oracle's"
+        ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+        gA, gB = ft.ftk_get_factors()
+    oracle.sgd_step_sync(w.dims, idx, vals, A, B, want, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+    assert_params_close(gA, A, "A")
+    assert_params_close(gB, B, "B")
+    return gA, gB, A, B
+
+
+# ------------------------------------------------------------------------------------------------
+# sampling and initialisation: bit-exact
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("nnz,M,seed", [(1, 5, 0), (3, 64, 7), (100_000, 1, 1000), (100_000, 63, 1001),
+                                        (100_000, 65, 1002), (100_000, 10_000, 1003),
+                                        (999_983, 262_145, 0xFEDCBA9876543210), (50_000_000, 100_003, 42)])
+def test_sample_set_bit_exact(nnz, M, seed):
+    announce("sample nnz=%d M=%d seed=%d" % (nnz, M, seed))
+    idx = [np.zeros(nnz, dtype=np.int32)]
+    vals = np.zeros(nnz, dtype=np.float32)
+    with binding.FastTucker((1,), idx, vals, (1,), 1) as ft:
+        ft.ftk_sample(seed, M)
+        got = ft.ftk_get_samples()
+        # a second draw with another seed replaces Psi; drawing fewer keeps the buffers
+        ft.ftk_sample(seed + 1, max(1, M // 2))
+        got2 = ft.ftk_get_samples()
+    assert np.array_equal(got, oracle.sample_positions(seed, M, nnz))
+    assert np.array_equal(got2, oracle.sample_positions(seed + 1, max(1, M // 2), nnz))
+
+
+def test_initial_parameters_bit_exact():
+    announce("init")
+    w = synth.tiny_workload(3, (1000, 37, 5), 50, (8, 5, 3), 6, 10)
+    idx, vals = synth.make_tensor(w)
+    for seed in (0, 1, 0xABCDEF0123456789):
+        with binding.FastTucker(w.dims, idx, vals, w.J, w.R, seed) as ft:
+            gA, gB = ft.ftk_get_factors()
+        A, B = oracle.init_factors(seed, w.dims, w.J, w.R)
+        for x, y in zip(gA + gB, A + B):
+            assert np.array_equal(x, y)
+
+
+# ------------------------------------------------------------------------------------------------
+# one synchronous step
+# ------------------------------------------------------------------------------------------------
+def test_c1_one_step_and_ten_step_rmse():
+    w = synth.WORKLOADS["C1"]
+    announce("C1 full size")
+    idx, vals = synth.make_tensor(w)
+    one_step_case(w, idx, vals)
+    A, B = oracle_state(w)
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
+        r0 = ft.ftk_rmse()
+        assert r0 == pytest.approx(oracle.rmse(w.dims, idx, vals, A, B), rel=1e-5)
+        prev = r0
+        for t in range(10):
+            ft.ftk_sample(w.sample_seed0 + t, w.n_samples)
+            ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+            pos = oracle.sample_positions(w.sample_seed0 + t, w.n_samples, w.nnz)
+            oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+            got, want = ft.ftk_rmse(), oracle.rmse(w.dims, idx, vals, A, B)
+            assert got == pytest.approx(want, rel=1e-3), "step %d" % t
+            assert got < prev
+            prev = got
+        assert ft.ftk_mae() == pytest.approx(oracle.errors(w.dims, idx, vals, A, B)[1], rel=1e-3)
+
+
+TINY = [
+    # order, dims, nnz, J, R, M
+    (1, (50,), 200, (4,), 3, 100),
+    (2, (40, 30), 500, (3, 5), 4, 333),
+    (3, (20, 30, 10), 2000, (2, 3, 4), 2, 1000),
+    (3, (64, 64, 64), 5000, (16, 16, 16), 16, 4097),
+    (3, (30, 30, 30), 3000, (8, 8, 8), 16, 64),
+    (4, (9, 8, 7, 6), 1500, (2, 2, 2, 2), 3, 777),
+    (5, (6, 5, 4, 3, 7), 800, (2, 1, 3, 2, 2), 5, 129),
+    (6, (50,) * 6, 4000, (8,) * 6, 16, 2049),
+    (8, (5,) * 8, 600, (2,) * 8, 2, 65),
+    (3, (10, 10, 10), 100, (5, 7, 3), 11, 1),
+    (3, (300, 200, 100), 3000, (32, 32, 32), 32, 513),
+    (3, (3, 2, 2), 1, (4, 4, 4), 4, 200),          # one stored entry, every sample a duplicate
+]
+
+
+@pytest.mark.parametrize("order,dims,nnz,J,R,M", TINY)
+def test_one_step_small_shapes(order, dims, nnz, J, R, M):
+    announce("tiny order=%d dims=%r J=%r R=%d M=%d" % (order, dims, J, R, M))
+    w = synth.tiny_workload(order, dims, nnz, J, R, M, seed=11 + order, values="normal")
+    w = synth.replace(w, lr_A=1e-2, lr_B=1e-2)
+    idx, vals = synth.make_tensor(w)
+    one_step_case(w, idx, vals)
+
+
+@pytest.mark.parametrize("name,nnz,M,dims", [
+    ("C2", 200_000, 20_000, (4_800, 1_777, 220)),
+    ("C3", 100_000, 5_000, (10_000, 6_250, 300)),
+    ("C4", 200_000, 20_000, (1_000,) * 6),
+    ("C5", 50_000, 2_000, (4_800, 1_777, 220)),
+])
+def test_one_step_scaled_workloads(name, nnz, M, dims):
+    announce("scaled %s" % name)
+    w = synth.WORKLOADS[name].scaled(nnz=nnz, n_samples=M, dims=dims)
+    idx, vals = synth.make_tensor(w)
+    one_step_case(w, idx, vals)
+
+
+def test_signed_parameters_and_hot_rows():
+    """Parameters of both signs (cancellation in the sums) and a mode with 2 rows (every sample
+    collides on it)."""
+    announce("signed parameters, 2-row mode")
+    w = synth.tiny_workload(3, (500, 2, 40), 20_000, (8, 8, 8), 8, 30_000, seed=5, values="normal")
+    w = synth.replace(w, lr_A=1e-4, lr_B=1e-3)
+    idx, vals = synth.make_tensor(w)
+    rng = np.random.default_rng(3)
+    A0 = [rng.uniform(-0.6, 0.6, size=(w.dims[n], w.J[n])).astype(np.float32) for n in range(3)]
+    B0 = [rng.uniform(-0.6, 0.6, size=(w.J[n], w.R)).astype(np.float32) for n in range(3)]
+    one_step_case(w, idx, vals, A0, B0)
+
+
+# ------------------------------------------------------------------------------------------------
+# invariants and error paths through the ABI
+# ------------------------------------------------------------------------------------------------
+def test_zero_learning_rate_leaves_parameters_bit_identical():
+    announce("lr = 0")
+    w = synth.tiny_workload(3, (50, 40, 30), 2000, (8, 8, 8), 8, 1500)
+    idx, vals = synth.make_tensor(w)
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, 3) as ft:
+        A0, B0 = ft.ftk_get_factors()
+        ft.ftk_sample(1, w.n_samples)
+        ft.ftk_sgd_step(0.0, 0.0, 0.5, 0.5)
+        A1, B1 = ft.ftk_get_factors()
+    for x, y in zip(A0 + B0, A1 + B1):
+        assert np.array_equal(x, y)
+
+
+def test_repeating_a_step_reuses_psi_and_accumulators_are_clean():
+    """Two steps on the same Psi equal two oracle steps on it: nothing is left over in the
+    gradient accumulators between steps."""
+    announce("two steps on one Psi")
+    w = synth.tiny_workload(3, (60, 50, 40), 3000, (4, 4, 4), 4, 2500)
+    idx, vals = synth.make_tensor(w)
+    A, B = oracle.init_factors(9, w.dims, w.J, w.R)
+    pos = oracle.sample_positions(77, w.n_samples, w.nnz)
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, 9) as ft:
+        ft.ftk_sample(77, w.n_samples)
+        for _ in range(2):
+            ft.ftk_sgd_step(1e-2, 1e-2, 1e-2, 1e-2)
+            oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, 1e-2, 1e-2, 1e-2, 1e-2)
+        gA, gB = ft.ftk_get_factors()
+    assert_params_close(gA, A, "A")
+    assert_params_close(gB, B, "B")
+
+
+def test_rmse_and_mae_match_oracle():
+    announce("rmse / mae")
+    for order, dims, J, R in [(3, (100, 90, 80), (8, 8, 8), 8), (2, (50, 60), (3, 7), 5), (6, (20,) * 6, (8,) * 6, 16)]:
+        w = synth.tiny_workload(order, dims, 20_011, J, R, 10, seed=21)
+        idx, vals = synth.make_tensor(w)
+        A, B = oracle.init_factors(4, w.dims, w.J, w.R)
+        with binding.FastTucker(w.dims, idx, vals, w.J, w.R, 4) as ft:
+            rm, ma = ft.ftk_rmse(), ft.ftk_mae()
+        want_rm, want_ma = oracle.errors(w.dims, idx, vals, A, B)
+        assert rm == pytest.approx(want_rm, rel=1e-5)
+        assert ma == pytest.approx(want_ma, rel=1e-5)
+
+
+def test_call_order_and_bad_input_errors():
+    announce("error paths")
+    w = synth.tiny_workload(3, (10, 10, 10), 100, (2, 2, 2), 2, 10)
+    idx, vals = synth.make_tensor(w)
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R) as ft:
+        with pytest.raises(binding.FtkError) as ei:
+            ft.ftk_sgd_step(0.1, 0.1, 0.0, 0.0)
+        assert ei.value.code == binding.FTK_ESTATE
+        with pytest.raises(binding.FtkError) as ei:
+            ft.ftk_get_samples()
+        assert ei.value.code == binding.FTK_ESTATE
+        with pytest.raises(binding.FtkError) as ei:
+            ft.ftk_sample(1, 0)
+        assert ei.value.code == binding.FTK_EINVAL
+        with pytest.raises(binding.FtkError) as ei:
+            ft.ftk_set_kernel("no-such-kernel")
+        assert ei.value.code == binding.FTK_EUNSUPPORTED
+        ft.ftk_sample(1, 10)
+        ft.ftk_sgd_step(0.1, 0.1, 0.0, 0.0)      # and now it works
+    bad = [a.copy() for a in idx]
+    bad[1][17] = 10                               # == dims[1]: out of range
+    with pytest.raises(binding.FtkError) as ei:
+        binding.FastTucker(w.dims, bad, vals, w.J, w.R)
+    assert ei.value.code == binding.FTK_EINVAL
+    bad[1][17] = -1
+    with pytest.raises(binding.FtkError) as ei:
+        binding.FastTucker(w.dims, bad, vals, w.J, w.R)
+    assert ei.value.code == binding.FTK_EINVAL
+
+
+def test_device_pointers_and_caller_stream():
+    """COO handed over as torch device tensors, work enqueued on torch's current stream."""
+    import torch
+    announce("device pointers + stream")
+    w = synth.tiny_workload(3, (80, 70, 60), 5000, (8, 8, 8), 8, 3000)
+    idx, vals = synth.make_tensor(w)
+    d_idx = [torch.from_numpy(a).cuda() for a in idx]
+    d_vals = torch.from_numpy(vals).cuda()
+    A, B = oracle.init_factors(2, w.dims, w.J, w.R)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        with binding.FastTucker(w.dims, d_idx, d_vals, w.J, w.R, 2) as ft:
+            del d_idx, d_vals                      # the library keeps its own copy
+            ft.ftk_set_stream(torch.cuda.current_stream().cuda_stream)
+            ft.ftk_sample(5, w.n_samples)
+            ft.ftk_sgd_step(1e-2, 1e-2, 1e-2, 1e-2)
+            gA, gB = ft.ftk_get_factors()
+    pos = oracle.sample_positions(5, w.n_samples, w.nnz)
+    oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, 1e-2, 1e-2, 1e-2, 1e-2)
+    assert_params_close(gA, A, "A")
+    assert_params_close(gB, B, "B")
+
+
+def test_timing_slots_count_launches():
+    announce("timing")
+    w = synth.tiny_workload(3, (80, 70, 60), 5000, (8, 8, 8), 8, 3000)
+    idx, vals = synth.make_tensor(w)
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R) as ft:
+        ft.ftk_set_timing(True)
+        for t in range(3):
+            ft.ftk_sample(t, w.n_samples)
+            ft.ftk_sgd_step(1e-3, 1e-3, 1e-2, 1e-2)
+        for slot in (binding.FTK_K_SAMPLE, binding.FTK_K_GRAD, binding.FTK_K_APPLY_A, binding.FTK_K_APPLY_B):
+            ms, cnt = ft.ftk_get_timing(slot)
+            assert cnt == 3 and ms > 0.0
+        ft.ftk_set_timing(False)
