@@ -8,6 +8,7 @@ the library has not been built, loading raises.
 from __future__ import annotations
 
 import ctypes as C
+import importlib.util
 import os
 from typing import List, Optional, Sequence, Tuple
 
@@ -39,6 +40,24 @@ class FtkError(RuntimeError):
 _lib = None
 
 
+def hip_runtime_path() -> str:
+    """The one HIP runtime this process should use.  libftk.so is built without a link-time
+    dependency on it, because two copies of the runtime in one process cannot both reach the
+    GPU: PyTorch bundles its own, so that one wins whenever PyTorch is installed."""
+    override = os.environ.get("FTK_HIP_RUNTIME")
+    if override:
+        return override
+    try:
+        spec = importlib.util.find_spec("torch")
+    except (ImportError, ValueError):
+        spec = None
+    if spec is not None and spec.origin:
+        bundled = os.path.join(os.path.dirname(spec.origin), "lib", "libamdhip64.so")
+        if os.path.exists(bundled):
+            return bundled
+    return "/opt/rocm/lib/libamdhip64.so"
+
+
 def load():
     """Load libftk.so (built by `python -m paper_2204_07104_amd.build`).  Raises if missing."""
     global _lib
@@ -47,6 +66,7 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(
             "%s is missing: build it with `python -m paper_2204_07104_amd.build` (there is no CPU fallback)" % LIB_PATH)
+    C.CDLL(hip_runtime_path(), mode=C.RTLD_GLOBAL)
     L = C.CDLL(LIB_PATH)
     vp = C.c_void_p
     L.ftk_create.argtypes = [C.POINTER(vp), C.c_int32, vp, C.c_int64, vp, vp, vp, C.c_int32, C.c_uint64, C.c_uint32]

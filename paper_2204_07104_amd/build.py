@@ -16,6 +16,10 @@ SOURCES = ["ftk_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-munsafe-fp-atomics",
+    # The HIP runtime is NOT linked in: a process must hold exactly one copy of it, and PyTorch
+    # ships its own.  The binding loads the right one (RTLD_GLOBAL) before this library; a C
+    # program links libamdhip64 itself.
+    "-no-hip-rt",
     # packed fp32 VALU ops are kept off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-unused-value", "-Wno-unused-result",

@@ -60,7 +60,7 @@ WORKLOADS = {
                    (None, None, None), "int1to5", distinct=True,
                    lr_A=1e-3, lr_B=1e-3, data_seed=101),
     "C2": Workload("C2", (480_000, 17_770, 2_200), 100_000_000, (16, 16, 16), 16, 1_000_000,
-                   (1.1, 1.1, None), "int1to5", lr_A=2e-9, lr_B=2e-6, data_seed=102),
+                   (1.1, 1.1, None), "int1to5", lr_A=2e-10, lr_B=1e-4, data_seed=102),
     "C3": Workload("C3", (1_000_000, 625_000, 3_000), 250_000_000, (32, 32, 32), 32, 4_000_000,
                    (1.2, 1.2, None), "int0to100_scaled", lr_A=1e-13, lr_B=1e-10, data_seed=103),
     "C4": Workload("C4", (100_000,) * 6, 200_000_000, (8,) * 6, 16, 2_000_000,

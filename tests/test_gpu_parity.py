@@ -278,3 +278,23 @@ def test_timing_slots_count_launches():
             ms, cnt = ft.ftk_get_timing(slot)
             assert cnt == 3 and ms > 0.0
         ft.ftk_set_timing(False)
+
+
+# ------------------------------------------------------------------------------------------------
+# the benchmark workload at full size, in the configuration bench.py times
+# ------------------------------------------------------------------------------------------------
+def test_c2_full_size_one_step():
+    """C2 (order-3, 1e8 stored entries, J = R = 16, |Psi| = 1e6): the sample set bit-exact and every
+    parameter after one step against the oracle (which needs a few seconds for 1e6 samples)."""
+    # step sizes large enough that the most-hit rows and the core factors move by a few percent:
+    # the comparison has to see the gradients, not just the unchanged parameters
+    w = synth.replace(synth.WORKLOADS["C2"], lr_A=1e-8, lr_B=1e-2)
+    announce("C2 full size: generating")
+    idx, vals = synth.make_tensor(w)
+    announce("C2 full size: step")
+    gA, gB, A, B = one_step_case(w, idx, vals)
+    A0, B0 = oracle_state(w)
+    moved_A = max(float(np.abs(a.astype(np.float64) - a0).max()) for a, a0 in zip(A, A0))
+    moved_B = max(float(np.abs(b.astype(np.float64) - b0).max()) for b, b0 in zip(B, B0))
+    assert moved_A > 1e-2, moved_A
+    assert moved_B > 1e-2, moved_B
