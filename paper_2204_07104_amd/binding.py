@@ -15,7 +15,8 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libftk.so")
+# FTK_LIB points the binding at another build of the library (kernel experiments)
+LIB_PATH = os.environ.get("FTK_LIB") or os.path.join(HERE, "libftk.so")
 
 FTK_OK, FTK_EINVAL, FTK_ENOMEM, FTK_EDEVICE, FTK_ESTATE, FTK_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 FTK_PTRS_HOST, FTK_PTRS_DEVICE = 0, 1

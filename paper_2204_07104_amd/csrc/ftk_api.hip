@@ -13,6 +13,7 @@
 
 #include "../../include/ftk.h"
 #include "ftk_kernels_generic.hpp"
+#include "ftk_kernels_mfma16.hpp"
 
 using namespace ftk;
 
@@ -20,7 +21,8 @@ namespace {
 
 thread_local std::string g_create_error;
 
-enum Variant { V_GENERIC = 0 };
+enum Variant { V_GENERIC = 0, V_MFMA16 = 1 };
+const char* const kVariantNames[] = {"generic", "mfma16"};
 
 struct TimingSlot {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pending;
@@ -37,8 +39,10 @@ struct ftk_ctx {
     Layout L = {};
     long long A_total = 0;   // floats in the packed A (and dA) allocation, multiple of 64
 
-    int32_t* d_idx[kMaxOrder] = {};
-    float* d_val = nullptr;
+    uint32_t* d_rec = nullptr;               // the tensor: one record per stored entry (see struct Coo)
+    int rec_words = 4;
+    int32_t* d_new_of_old[kMaxOrder] = {};   // internal row number of every caller row
+    float* d_stage = nullptr;                // staging for ftk_get/set_factors (largest I_n * J_n floats)
     float* d_A = nullptr;
     float* d_dA = nullptr;
     float* d_B = nullptr;
@@ -59,10 +63,19 @@ struct ftk_ctx {
     int mode = FTK_SYNC;
 
     int variant = V_GENERIC;
-    bool variant_forced = false;
     int gen_threads = 0;     // block size of grad_generic for this shape (0: does not fit)
     int gen_b_in_lds = 0;
     size_t gen_lds_bytes = 0;
+
+    // frequently hit rows: rows [0, hot_K[n]) of mode n (internal numbering) are accumulated in LDS
+    bool mfma16_ok = false;
+    int hot_K[kMaxOrder] = {};
+    int hot_off[kMaxOrder] = {};
+    int hot_H = 0;
+    int mfma_grid = 0;
+    size_t mfma_lds_bytes = 0;
+    float* d_hot_partial = nullptr;   // [mfma_grid][hot_H][16]
+    float* d_gb_partial = nullptr;    // [mfma_grid][B_total]
 
     bool timing = false;
     TimingSlot slots[FTK_K_COUNT];
@@ -155,7 +168,7 @@ void pick_generic_config(ftk_ctx* c) {
         }
 }
 
-int launch_grad(ftk_ctx* c, float lambda_A) {
+int launch_grad_generic(ftk_ctx* c, float lambda_A) {
     GradArgs g;
     g.L = c->L;
     g.batch = Batch{c->d_bidx, c->d_bval, c->n_samples, c->cap};
@@ -179,10 +192,49 @@ int launch_grad(ftk_ctx* c, float lambda_A) {
     return FTK_OK;
 }
 
+template <int N>
+int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
+    FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_mfma16_kernel<N>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->mfma_lds_bytes));
+    Bracket t(c, FTK_K_GRAD);
+    hipLaunchKernelGGL(grad_mfma16_kernel<N>, dim3(c->mfma_grid), dim3(kMfmaThreads), c->mfma_lds_bytes, c->stream, g);
+    FTK_HIP(c, hipGetLastError());
+    return FTK_OK;
+}
+
+int launch_grad_mfma16(ftk_ctx* c, float lambda_A) {
+    Mfma16Args g;
+    g.batch = Batch{c->d_bidx, c->d_bval, c->n_samples, c->cap};
+    g.A = c->d_A;
+    g.B = c->d_B;
+    g.dA = c->d_dA;
+    for (int n = 0; n < kMaxOrder; ++n) {
+        g.A_off[n] = c->L.A_off[n];
+        g.B_off[n] = c->L.B_off[n];
+        g.K[n] = c->hot_K[n];
+        g.hot_off[n] = c->hot_off[n];
+    }
+    g.H = c->hot_H;
+    g.hot_partial = c->d_hot_partial;
+    g.gb_partial = c->d_gb_partial;
+    g.lambda_A = lambda_A;
+    g.n_tiles = (c->n_samples + 15) / 16;
+    // what the kernel assumes: 16-float rows, a batch padded to whole tiles, tables sized for the grid
+    if (!c->mfma16_ok || c->cap < g.n_tiles * 16 || !c->d_hot_partial || !c->d_gb_partial)
+        return fail(c, FTK_EUNSUPPORTED, "mfma16 kernel is not available for this shape");
+    switch (c->order) {
+        case 1: return launch_mfma16_n<1>(c, g);
+        case 2: return launch_mfma16_n<2>(c, g);
+        case 3: return launch_mfma16_n<3>(c, g);
+        case 4: return launch_mfma16_n<4>(c, g);
+        case 5: return launch_mfma16_n<5>(c, g);
+        case 6: return launch_mfma16_n<6>(c, g);
+        default: return fail(c, FTK_EUNSUPPORTED, "mfma16 kernel is built for order <= 6");
+    }
+}
+
 int launch_errors(ftk_ctx* c, double* host_sums) {
-    CooSoA coo;
-    for (int n = 0; n < kMaxOrder; ++n) coo.idx[n] = c->d_idx[n];
-    coo.val = c->d_val;
+    Coo coo{c->d_rec, c->rec_words};
     FTK_HIP(c, hipMemsetAsync(c->d_sums, 0, 2 * sizeof(double), c->stream));
     const int b_in_lds = (size_t)c->L.B_total * 4 <= 65536 - 256;
     const size_t lds = b_in_lds ? (size_t)c->L.B_total * 4 : 0;
@@ -200,11 +252,46 @@ void release(ftk_ctx* c) {
     hipStreamSynchronize(c->stream);
     drop_pending(c);
     for (int n = 0; n < kMaxOrder; ++n)
-        if (c->d_idx[n]) hipFree(c->d_idx[n]);
-    void* ptrs[] = {c->d_val, c->d_A, c->d_dA, c->d_B, c->d_GB, c->d_sums, c->d_flag, c->d_pos, c->d_bidx, c->d_bval};
+        if (c->d_new_of_old[n]) hipFree(c->d_new_of_old[n]);
+    void* ptrs[] = {c->d_rec, c->d_stage, c->d_A, c->d_dA, c->d_B, c->d_GB, c->d_sums, c->d_flag,
+                    c->d_pos, c->d_bidx, c->d_bval, c->d_hot_partial, c->d_gb_partial};
     for (void* p : ptrs)
         if (p) hipFree(p);
     delete c;
+}
+
+// Choose which rows are accumulated in LDS: the H rows with the largest occurrence counts over
+// all modes (rows are already sorted by count within a mode, so this is a merge of sorted lists).
+void pick_hot_rows(ftk_ctx* c, const std::vector<std::vector<unsigned int>>& sorted_counts) {
+    const int N = c->order;
+    const long long budget = (long long)c->max_lds - 4LL * (kMfmaWaves * kWaveScratch + N * 256) - 1024;
+    int H = (int)std::max(0LL, budget / 64);
+    long long rows_total = 0;
+    for (int n = 0; n < N; ++n) rows_total += c->dims[n];
+    if (H > rows_total) H = (int)rows_total;
+    int taken[kMaxOrder] = {};
+    for (int t = 0; t < H; ++t) {
+        int best = -1;
+        unsigned int best_count = 0;
+        for (int n = 0; n < N; ++n)
+            if (taken[n] < c->dims[n]) {
+                const unsigned int cnt = sorted_counts[n][taken[n]];
+                if (best < 0 || cnt > best_count) {
+                    best = n;
+                    best_count = cnt;
+                }
+            }
+        if (best < 0) break;
+        taken[best] += 1;
+    }
+    int off = 0;
+    for (int n = 0; n < N; ++n) {
+        c->hot_K[n] = taken[n];
+        c->hot_off[n] = off;
+        off += taken[n];
+    }
+    c->hot_H = std::max(off, 1);
+    c->mfma_lds_bytes = 4 * ((size_t)c->hot_H * 16 + kMfmaWaves * kWaveScratch + N * 256);
 }
 
 int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, const float* vals, uint64_t init_seed,
@@ -219,53 +306,120 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     if (c->max_lds < 65536) c->max_lds = 65536;
 
     // packed parameter layout: every mode starts on a 256-byte boundary
-    long long a_off = 0;
+    long long a_off = 0, stage = 0;
     int b_off = 0;
     for (int n = 0; n < N; ++n) {
         c->L.A_off[n] = a_off;
         c->L.B_off[n] = b_off;
         a_off += ((dims[n] * c->L.J[n] + 63) / 64) * 64;
         b_off += c->L.J[n] * c->L.R;
+        stage = std::max(stage, (long long)dims[n] * c->L.J[n]);
     }
     c->A_total = a_off;
     c->L.B_total = b_off;
     pick_generic_config(c);
-    if (c->gen_threads == 0)
+    c->mfma16_ok = c->L.R == 16 && N <= 6 && c->max_lds >= 131072;
+    for (int n = 0; n < N; ++n) c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16;
+    if (c->gen_threads == 0 && !c->mfma16_ok)
         return fail(c, FTK_EUNSUPPORTED, "N*R = %d with sum J_n R = %d exceeds the kernels' LDS budget", N * c->L.R,
                     c->L.B_total);
 
+    // ---- the tensor: range check, per-mode row frequencies, renumbering, record packing ----
     const hipMemcpyKind kind = (flags & FTK_PTRS_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    const int scan_blocks = blocks_for(c->nnz, 256, c->num_cu * 8);
+    c->rec_words = record_words(N);
     FTK_HIP(c, hipMalloc(&c->d_flag, sizeof(unsigned int)));
-    FTK_HIP(c, hipMemset(c->d_flag, 0, sizeof(unsigned int)));
+    FTK_HIP(c, hipMalloc(&c->d_rec, (size_t)c->nnz * c->rec_words * sizeof(uint32_t)));
+    if (c->rec_words != N + 1) FTK_HIP(c, hipMemset(c->d_rec, 0, (size_t)c->nnz * c->rec_words * sizeof(uint32_t)));
+    uint32_t* d_col = nullptr;        // one caller column at a time
+    unsigned int* d_counts = nullptr;
+    struct Guard {
+        uint32_t*& a;
+        unsigned int*& b;
+        ~Guard() {
+            if (a) hipFree(a);
+            if (b) hipFree(b);
+        }
+    } guard{d_col, d_counts};
+    FTK_HIP(c, hipMalloc(&d_col, (size_t)c->nnz * sizeof(uint32_t)));
+    std::vector<std::vector<unsigned int>> sorted_counts(N);
     for (int n = 0; n < N; ++n) {
-        FTK_HIP(c, hipMalloc(&c->d_idx[n], (size_t)c->nnz * sizeof(int32_t)));
-        FTK_HIP(c, hipMemcpy(c->d_idx[n], idx[n], (size_t)c->nnz * sizeof(int32_t), kind));
-        hipLaunchKernelGGL(check_range_kernel, dim3(blocks_for(c->nnz, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
-                           (const int32_t*)c->d_idx[n], (uint64_t)c->nnz, (int32_t)dims[n], c->d_flag);
+        FTK_HIP(c, hipMemcpy(d_col, idx[n], (size_t)c->nnz * sizeof(int32_t), kind));
+        FTK_HIP(c, hipMemset(c->d_flag, 0, sizeof(unsigned int)));
+        hipLaunchKernelGGL(check_range_kernel, dim3(scan_blocks), dim3(256), 0, c->stream, (const int32_t*)d_col,
+                           (uint64_t)c->nnz, (int32_t)dims[n], c->d_flag);
         FTK_HIP(c, hipGetLastError());
         unsigned int bad = 0;
         FTK_HIP(c, hipMemcpy(&bad, c->d_flag, sizeof bad, hipMemcpyDeviceToHost));
         if (bad) return fail(c, FTK_EINVAL, "idx[%d] holds %u entries outside [0, %lld)", n, bad, (long long)dims[n]);
-    }
-    FTK_HIP(c, hipMalloc(&c->d_val, (size_t)c->nnz * sizeof(float)));
-    FTK_HIP(c, hipMemcpy(c->d_val, vals, (size_t)c->nnz * sizeof(float), kind));
 
+        FTK_HIP(c, hipMalloc(&d_counts, (size_t)dims[n] * sizeof(unsigned int)));
+        FTK_HIP(c, hipMemset(d_counts, 0, (size_t)dims[n] * sizeof(unsigned int)));
+        hipLaunchKernelGGL(histogram_kernel, dim3(scan_blocks), dim3(256), 0, c->stream, (const int32_t*)d_col,
+                           (uint64_t)c->nnz, d_counts);
+        FTK_HIP(c, hipGetLastError());
+        std::vector<unsigned int> counts((size_t)dims[n]);
+        FTK_HIP(c, hipMemcpy(counts.data(), d_counts, counts.size() * sizeof(unsigned int), hipMemcpyDeviceToHost));
+        FTK_HIP(c, hipFree(d_counts));
+        d_counts = nullptr;
+
+        // internal row number = rank by descending count (ties: ascending caller row number)
+        std::vector<int32_t> order_rows((size_t)dims[n]);
+        for (size_t i = 0; i < order_rows.size(); ++i) order_rows[i] = (int32_t)i;
+        std::stable_sort(order_rows.begin(), order_rows.end(),
+                         [&](int32_t x, int32_t y) { return counts[(size_t)x] > counts[(size_t)y]; });
+        std::vector<int32_t> new_of_old((size_t)dims[n]);
+        sorted_counts[n].resize((size_t)dims[n]);
+        for (size_t r = 0; r < order_rows.size(); ++r) {
+            new_of_old[(size_t)order_rows[r]] = (int32_t)r;
+            sorted_counts[n][r] = counts[(size_t)order_rows[r]];
+        }
+        FTK_HIP(c, hipMalloc(&c->d_new_of_old[n], (size_t)dims[n] * sizeof(int32_t)));
+        FTK_HIP(c, hipMemcpy(c->d_new_of_old[n], new_of_old.data(), new_of_old.size() * sizeof(int32_t),
+                             hipMemcpyHostToDevice));
+        hipLaunchKernelGGL(pack_records_kernel, dim3(scan_blocks), dim3(256), 0, c->stream, (const uint32_t*)d_col,
+                           (uint64_t)c->nnz, (const int32_t*)c->d_new_of_old[n], c->d_rec, c->rec_words, n);
+        FTK_HIP(c, hipGetLastError());
+        FTK_HIP(c, hipStreamSynchronize(c->stream));
+    }
+    FTK_HIP(c, hipMemcpy(d_col, vals, (size_t)c->nnz * sizeof(float), kind));
+    hipLaunchKernelGGL(pack_records_kernel, dim3(scan_blocks), dim3(256), 0, c->stream, (const uint32_t*)d_col,
+                       (uint64_t)c->nnz, (const int32_t*)nullptr, c->d_rec, c->rec_words, N);
+    FTK_HIP(c, hipGetLastError());
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    FTK_HIP(c, hipFree(d_col));
+    d_col = nullptr;
+
+    // ---- parameters ----
     FTK_HIP(c, hipMalloc(&c->d_A, (size_t)c->A_total * sizeof(float)));
     FTK_HIP(c, hipMalloc(&c->d_dA, (size_t)c->A_total * sizeof(float)));
     FTK_HIP(c, hipMalloc(&c->d_B, (size_t)c->L.B_total * sizeof(float)));
     FTK_HIP(c, hipMalloc(&c->d_GB, (size_t)c->L.B_total * sizeof(float)));
+    FTK_HIP(c, hipMalloc(&c->d_stage, (size_t)stage * sizeof(float)));
     FTK_HIP(c, hipMalloc(&c->d_sums, 2 * sizeof(double)));
     FTK_HIP(c, hipMemset(c->d_A, 0, (size_t)c->A_total * sizeof(float)));
     FTK_HIP(c, hipMemset(c->d_dA, 0, (size_t)c->A_total * sizeof(float)));
     FTK_HIP(c, hipMemset(c->d_GB, 0, (size_t)c->L.B_total * sizeof(float)));
     for (int n = 0; n < N; ++n) {
         const long long na = dims[n] * c->L.J[n], nb = (long long)c->L.J[n] * c->L.R;
-        hipLaunchKernelGGL(init_uniform_kernel, dim3(blocks_for(na, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
-                           c->d_A + c->L.A_off[n], na, init_seed, (uint32_t)n);
+        hipLaunchKernelGGL(init_factor_kernel, dim3(blocks_for(na, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
+                           c->d_A + c->L.A_off[n], (long long)dims[n], c->L.J[n], (const int32_t*)c->d_new_of_old[n],
+                           init_seed, (uint32_t)n);
         hipLaunchKernelGGL(init_uniform_kernel, dim3(blocks_for(nb, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
                            c->d_B + c->L.B_off[n], nb, init_seed, (uint32_t)(N + n));
     }
     FTK_HIP(c, hipGetLastError());
+
+    // ---- kernel variant ----
+    if (c->mfma16_ok) {
+        pick_hot_rows(c, sorted_counts);
+        c->mfma_grid = c->num_cu;
+        FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid * c->hot_H * 16 * sizeof(float)));
+        FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid * c->L.B_total * sizeof(float)));
+        c->variant = V_MFMA16;
+    } else {
+        c->variant = V_GENERIC;
+    }
     FTK_HIP(c, hipStreamSynchronize(c->stream));
     return FTK_OK;
 }
@@ -336,9 +490,7 @@ int ftk_sample(ftk_ctx* c, uint64_t seed, int64_t n_samples) {
         FTK_HIP(c, hipMalloc(&c->d_bval, (size_t)cap * sizeof(float)));
         c->cap = cap;
     }
-    CooSoA coo;
-    for (int n = 0; n < kMaxOrder; ++n) coo.idx[n] = c->d_idx[n];
-    coo.val = c->d_val;
+    Coo coo{c->d_rec, c->rec_words};
     {
         Bracket t(c, FTK_K_SAMPLE);
         hipLaunchKernelGGL(sample_gather_kernel, dim3((unsigned)((n_samples + 255) / 256)), dim3(256), 0, c->stream, coo,
@@ -369,19 +521,37 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
     if (!c) return FTK_EINVAL;
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step before ftk_sample");
     if (c->mode != FTK_SYNC) return fail(c, FTK_EUNSUPPORTED, "only FTK_SYNC is built");
-    int rc = launch_grad(c, lambda_A);
+    const bool mfma = c->variant == V_MFMA16;
+    int rc = mfma ? launch_grad_mfma16(c, lambda_A) : launch_grad_generic(c, lambda_A);
     if (rc != FTK_OK) return rc;
     {
-        Bracket t(c, FTK_K_APPLY_A);
+        ApplyHotArgs h = {};
+        int hot_blocks = 0;
+        if (mfma) {
+            h.hot_partial = c->d_hot_partial;
+            h.parts = c->mfma_grid;
+            h.H = c->hot_H;
+            h.J = 16;
+            h.order = c->order;
+            for (int n = 0; n < kMaxOrder; ++n) {
+                h.K[n] = c->hot_K[n];
+                h.hot_off[n] = c->hot_off[n];
+                h.A_off[n] = c->L.A_off[n];
+            }
+            hot_blocks = (c->hot_H * 16 + 255) / 256;
+        }
         const long long n4 = c->A_total / 4;
-        hipLaunchKernelGGL(apply_A_kernel, dim3(blocks_for(n4, 256, c->num_cu * 16)), dim3(256), 0, c->stream, c->d_A,
-                           c->d_dA, n4, lr_A);
+        const int dense_blocks = blocks_for(n4, 256, c->num_cu * 16);
+        Bracket t(c, FTK_K_APPLY_A);
+        hipLaunchKernelGGL(apply_A_hot_kernel, dim3(dense_blocks + hot_blocks), dim3(256), 0, c->stream, c->d_A, c->d_dA,
+                           n4, lr_A, dense_blocks, h);
     }
     FTK_HIP(c, hipGetLastError());
     {
         Bracket t(c, FTK_K_APPLY_B);
-        hipLaunchKernelGGL(apply_B_kernel, dim3((c->L.B_total + 255) / 256), dim3(256), 0, c->stream, c->d_B, c->d_GB,
-                           c->L.B_total, lr_B, lambda_B, 1.0f / (float)c->n_samples);
+        hipLaunchKernelGGL(apply_B_kernel, dim3((c->L.B_total * 16 + 255) / 256), dim3(256), 0, c->stream, c->d_B,
+                           mfma ? c->d_gb_partial : c->d_GB, c->L.B_total, mfma ? c->mfma_grid : 1, mfma ? 0 : 1, lr_B,
+                           lambda_B, 1.0f / (float)c->n_samples);
     }
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;
@@ -410,9 +580,15 @@ int ftk_mae(ftk_ctx* c, double* out) {
 int ftk_get_factors(ftk_ctx* c, float* const* A_out, float* const* B_out) {
     if (!c) return FTK_EINVAL;
     for (int n = 0; n < c->order; ++n) {
-        if (A_out && A_out[n])
-            FTK_HIP(c, hipMemcpyAsync(A_out[n], c->d_A + c->L.A_off[n], (size_t)c->dims[n] * c->L.J[n] * sizeof(float),
-                                      hipMemcpyDeviceToHost, c->stream));
+        if (A_out && A_out[n]) {
+            const long long na = c->dims[n] * c->L.J[n];
+            hipLaunchKernelGGL(permute_rows_kernel, dim3(blocks_for(na, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
+                               (const float*)(c->d_A + c->L.A_off[n]), c->d_stage, (const int32_t*)c->d_new_of_old[n],
+                               (long long)c->dims[n], c->L.J[n], 0);
+            FTK_HIP(c, hipGetLastError());
+            FTK_HIP(c, hipMemcpyAsync(A_out[n], c->d_stage, (size_t)na * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+            FTK_HIP(c, hipStreamSynchronize(c->stream));
+        }
         if (B_out && B_out[n])
             FTK_HIP(c, hipMemcpyAsync(B_out[n], c->d_B + c->L.B_off[n], (size_t)c->L.J[n] * c->L.R * sizeof(float),
                                       hipMemcpyDeviceToHost, c->stream));
@@ -424,9 +600,15 @@ int ftk_get_factors(ftk_ctx* c, float* const* A_out, float* const* B_out) {
 int ftk_set_factors(ftk_ctx* c, const float* const* A_in, const float* const* B_in) {
     if (!c) return FTK_EINVAL;
     for (int n = 0; n < c->order; ++n) {
-        if (A_in && A_in[n])
-            FTK_HIP(c, hipMemcpyAsync(c->d_A + c->L.A_off[n], A_in[n], (size_t)c->dims[n] * c->L.J[n] * sizeof(float),
-                                      hipMemcpyHostToDevice, c->stream));
+        if (A_in && A_in[n]) {
+            const long long na = c->dims[n] * c->L.J[n];
+            FTK_HIP(c, hipMemcpyAsync(c->d_stage, A_in[n], (size_t)na * sizeof(float), hipMemcpyHostToDevice, c->stream));
+            hipLaunchKernelGGL(permute_rows_kernel, dim3(blocks_for(na, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
+                               (const float*)c->d_stage, c->d_A + c->L.A_off[n], (const int32_t*)c->d_new_of_old[n],
+                               (long long)c->dims[n], c->L.J[n], 1);
+            FTK_HIP(c, hipGetLastError());
+            FTK_HIP(c, hipStreamSynchronize(c->stream));
+        }
         if (B_in && B_in[n])
             FTK_HIP(c, hipMemcpyAsync(c->d_B + c->L.B_off[n], B_in[n], (size_t)c->L.J[n] * c->L.R * sizeof(float),
                                       hipMemcpyHostToDevice, c->stream));
@@ -491,23 +673,25 @@ int ftk_get_timing(ftk_ctx* c, int which, double* total_ms, int64_t* launches, i
 int ftk_set_kernel(ftk_ctx* c, const char* name) {
     if (!c) return FTK_EINVAL;
     if (!name) return fail(c, FTK_EINVAL, "name is NULL");
+    // the accumulators of both variants are clean between steps, so switching is always safe
     if (!strcmp(name, "auto")) {
-        c->variant_forced = false;
-        c->variant = V_GENERIC;
+        c->variant = c->mfma16_ok ? V_MFMA16 : V_GENERIC;
         return FTK_OK;
     }
     if (!strcmp(name, "generic")) {
-        c->variant_forced = true;
+        if (c->gen_threads == 0) return fail(c, FTK_EUNSUPPORTED, "the generic kernel does not fit this shape");
         c->variant = V_GENERIC;
         return FTK_OK;
     }
-    return fail(c, FTK_EUNSUPPORTED, "no kernel variant named '%s' for this shape", name);
+    if (!strcmp(name, "mfma16")) {
+        if (!c->mfma16_ok) return fail(c, FTK_EUNSUPPORTED, "mfma16 needs J_n = R = 16 and order <= 6");
+        c->variant = V_MFMA16;
+        return FTK_OK;
+    }
+    return fail(c, FTK_EUNSUPPORTED, "no kernel variant named '%s'", name);
 }
 
-const char* ftk_kernel_name(const ftk_ctx* c) {
-    (void)c;
-    return "generic";
-}
+const char* ftk_kernel_name(const ftk_ctx* c) { return c ? kVariantNames[c->variant] : "none"; }
 
 const char* ftk_last_error(const ftk_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
 

@@ -43,23 +43,40 @@ __device__ __forceinline__ double wave_sum(double v) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Psi: positions from Philox, and the sampled nonzeros gathered into a dense batch
-// (step a1 + a2: the only place the COO arrays are read with random access).
+// The tensor in device memory: one record per stored entry, `words` 32-bit words each
+// (N mode indices, then the value's bits, padded to a multiple of 4 words), so that a random
+// position costs one 16-byte-aligned access instead of N + 1 scattered ones.  Mode indices
+// are the library's internal row numbers (rows renumbered by descending frequency).
 // ---------------------------------------------------------------------------------------------
-struct CooSoA {
-    const int32_t* idx[kMaxOrder];
-    const float* val;
+struct Coo {
+    const uint32_t* rec;
+    int words;
 };
 
-__global__ void __launch_bounds__(256) sample_gather_kernel(CooSoA coo, int order, uint64_t nnz, uint64_t seed,
+__host__ __device__ inline int record_words(int order) { return ((order + 1 + 3) / 4) * 4; }
+
+// ---------------------------------------------------------------------------------------------
+// Psi: positions from Philox, and the sampled entries gathered into a dense batch
+// (step a1 + a2: the only place the tensor is read with random access).
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) sample_gather_kernel(Coo coo, int order, uint64_t nnz, uint64_t seed,
                                                             long long M, long long cap, uint32_t* __restrict__ pos,
                                                             int32_t* __restrict__ bidx, float* __restrict__ bval) {
     const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= M) return;
     const uint32_t p = sample_position(seed, (uint64_t)k, nnz);
     pos[k] = p;
-    for (int n = 0; n < order; ++n) bidx[(long long)n * cap + k] = coo.idx[n][p];
-    bval[k] = coo.val[p];
+    const uint4* r4 = reinterpret_cast<const uint4*>(coo.rec + (size_t)p * coo.words);
+    uint32_t w[kMaxOrder + 4];
+    for (int q = 0; q < coo.words / 4; ++q) {
+        const uint4 t = r4[q];
+        w[4 * q + 0] = t.x;
+        w[4 * q + 1] = t.y;
+        w[4 * q + 2] = t.z;
+        w[4 * q + 3] = t.w;
+    }
+    for (int n = 0; n < order; ++n) bidx[(long long)n * cap + k] = (int32_t)w[n];
+    bval[k] = __uint_as_float(w[order]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -182,20 +199,29 @@ __global__ void __launch_bounds__(256) apply_A_kernel(float* __restrict__ A, flo
     }
 }
 
-// B <- B - lr_B (GB / M + lambda_B B), GB <- 0
+// B <- B - lr_B (GB / M + lambda_B B).  GB is the sum of `parts` partial tables of `count` floats
+// each; with clear != 0 the (single, atomically accumulated) table is zeroed for the next step.
+// One 64-lane wave per group of 4 entries: 16 lanes stride over the partial tables of an entry.
 __global__ void __launch_bounds__(256) apply_B_kernel(float* __restrict__ B, float* __restrict__ GB, int count,
-                                                      float lr_B, float lambda_B, float inv_M) {
-    const int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q >= count) return;
-    const float b = B[q];
-    B[q] = b - lr_B * fmaf(GB[q], inv_M, lambda_B * b);
-    GB[q] = 0.0f;
+                                                      int parts, int clear, float lr_B, float lambda_B, float inv_M) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    const int q = t >> 4, sub = t & 15;
+    float gsum = 0.0f;
+    if (q < count)
+        for (int b = sub; b < parts; b += 16) gsum += GB[(size_t)b * count + q];
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) gsum += __shfl_xor(gsum, o);
+    if (q < count && sub == 0) {
+        const float b0 = B[q];
+        B[q] = b0 - lr_B * fmaf(gsum, inv_M, lambda_B * b0);
+        if (clear) GB[q] = 0.0f;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
 // whole-tensor error sums (RMSE / MAE): one lane per stored nonzero, streaming over Omega
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) errors_generic_kernel(CooSoA coo, Layout L, uint64_t nnz,
+__global__ void __launch_bounds__(256) errors_generic_kernel(Coo coo, Layout L, uint64_t nnz,
                                                              const float* __restrict__ A,
                                                              const float* __restrict__ B, int b_in_lds,
                                                              double* __restrict__ sums /* [2]: sse, sae */) {
@@ -209,12 +235,13 @@ __global__ void __launch_bounds__(256) errors_generic_kernel(CooSoA coo, Layout 
     const float* Bm = b_in_lds ? lds : B;
     double sse = 0.0, sae = 0.0;
     for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + tid; p < nnz; p += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t* rec = coo.rec + (size_t)p * coo.words;
         float xhat = 0.0f;
         for (int r = 0; r < L.R; ++r) {
             float prod = 1.0f;
             for (int n = 0; n < L.order; ++n) {
                 const int Jn = L.J[n];
-                const float* row = A + L.A_off[n] + (long long)coo.idx[n][p] * Jn;
+                const float* row = A + L.A_off[n] + (long long)rec[n] * Jn;
                 const float* Bn = Bm + L.B_off[n];
                 float acc = 0.0f;
                 for (int j = 0; j < Jn; ++j) acc = fmaf(row[j], Bn[j * L.R + r], acc);
@@ -222,7 +249,7 @@ __global__ void __launch_bounds__(256) errors_generic_kernel(CooSoA coo, Layout 
             }
             xhat += prod;
         }
-        const double e = (double)coo.val[p] - (double)xhat;
+        const double e = (double)__uint_as_float(rec[L.order]) - (double)xhat;
         sse += e * e;
         sae += fabs(e);
     }
@@ -263,6 +290,54 @@ __global__ void __launch_bounds__(256) check_range_kernel(const int32_t* __restr
         mine += (v < 0 || v >= dim) ? 1u : 0u;
     }
     if (mine) atomicAdd(bad, mine);
+}
+
+// per-row occurrence counts of one mode over all stored entries
+__global__ void __launch_bounds__(256) histogram_kernel(const int32_t* __restrict__ idx, uint64_t nnz,
+                                                        unsigned int* __restrict__ counts) {
+    for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (uint64_t)gridDim.x * blockDim.x)
+        atomicAdd(counts + idx[p], 1u);
+}
+
+// word `slot` of every record <- new_of_old[idx[p]]  (or the value's bits when new_of_old == nullptr)
+__global__ void __launch_bounds__(256) pack_records_kernel(const uint32_t* __restrict__ src, uint64_t nnz,
+                                                           const int32_t* __restrict__ new_of_old,
+                                                           uint32_t* __restrict__ rec, int words, int slot) {
+    for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t v = src[p];
+        rec[p * words + slot] = new_of_old ? (uint32_t)new_of_old[v] : v;
+    }
+}
+
+// Parameter rows between the caller's numbering and the internal one:
+// to_internal:  dst[new_of_old[i]][:] = src[i][:]      from_internal:  dst[i][:] = src[new_of_old[i]][:]
+__global__ void __launch_bounds__(256) permute_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                           const int32_t* __restrict__ new_of_old, long long rows,
+                                                           int J, int to_internal) {
+    const long long total = rows * J;
+    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < total;
+         q += (long long)gridDim.x * blockDim.x) {
+        const long long i = q / J;
+        const int j = (int)(q - i * J);
+        const long long m = new_of_old[i];
+        if (to_internal)
+            dst[m * J + j] = src[q];
+        else
+            dst[q] = src[m * J + j];
+    }
+}
+
+// A^(n) initial values, written at the internal row of every caller-numbered row
+__global__ void __launch_bounds__(256) init_factor_kernel(float* __restrict__ out, long long rows, int J,
+                                                          const int32_t* __restrict__ new_of_old, uint64_t init_seed,
+                                                          uint32_t array_id) {
+    const long long total = rows * J;
+    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < total;
+         q += (long long)gridDim.x * blockDim.x) {
+        const long long i = q / J;
+        const int j = (int)(q - i * J);
+        out[(long long)new_of_old[i] * J + j] = init_value(init_seed, array_id, (uint64_t)q);
+    }
 }
 
 __global__ void __launch_bounds__(256) fill_zero_kernel(float* __restrict__ out, long long count) {
