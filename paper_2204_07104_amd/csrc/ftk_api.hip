@@ -54,7 +54,9 @@ struct ftk_ctx {
     int32_t* d_bidx = nullptr;
     float* d_bval = nullptr;
     long long cap = 0;
-    long long n_samples = 0;
+    long long n_samples = 0;      // |Psi| of the current sample set (0: none drawn yet)
+    uint64_t sample_seed = 0;
+    bool batch_valid = false;     // d_pos / d_bidx / d_bval hold the current Psi
 
     hipStream_t stream = nullptr;
     int device = 0;
@@ -204,7 +206,10 @@ int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
 
 int launch_grad_mfma16(ftk_ctx* c, float lambda_A) {
     Mfma16Args g;
-    g.batch = Batch{c->d_bidx, c->d_bval, c->n_samples, c->cap};
+    g.coo = Coo{c->d_rec, c->rec_words};
+    g.nnz = (uint64_t)c->nnz;
+    g.seed = c->sample_seed;
+    g.M = c->n_samples;
     g.A = c->d_A;
     g.B = c->d_B;
     g.dA = c->d_dA;
@@ -218,9 +223,9 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A) {
     g.hot_partial = c->d_hot_partial;
     g.gb_partial = c->d_gb_partial;
     g.lambda_A = lambda_A;
-    g.n_tiles = (c->n_samples + 15) / 16;
-    // what the kernel assumes: 16-float rows, a batch padded to whole tiles, tables sized for the grid
-    if (!c->mfma16_ok || c->cap < g.n_tiles * 16 || !c->d_hot_partial || !c->d_gb_partial)
+    // what the kernel assumes: 16-float rows, records of 4 * ceil((N + 1) / 4) words, partial
+    // tables sized for the grid, an LDS table of hot_H rows
+    if (!c->mfma16_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->d_hot_partial || !c->d_gb_partial)
         return fail(c, FTK_EUNSUPPORTED, "mfma16 kernel is not available for this shape");
     switch (c->order) {
         case 1: return launch_mfma16_n<1>(c, g);
@@ -231,6 +236,37 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A) {
         case 6: return launch_mfma16_n<6>(c, g);
         default: return fail(c, FTK_EUNSUPPORTED, "mfma16 kernel is built for order <= 6");
     }
+}
+
+// Psi as arrays (positions, row numbers, values): needed by the generic kernel and ftk_get_samples
+int ensure_batch(ftk_ctx* c) {
+    if (c->batch_valid) return FTK_OK;
+    const long long n_samples = c->n_samples;
+    if (n_samples > c->cap) {
+        FTK_HIP(c, hipStreamSynchronize(c->stream));
+        if (c->d_pos) hipFree(c->d_pos);
+        if (c->d_bidx) hipFree(c->d_bidx);
+        if (c->d_bval) hipFree(c->d_bval);
+        c->d_pos = nullptr;
+        c->d_bidx = nullptr;
+        c->d_bval = nullptr;
+        c->cap = 0;
+        const long long cap = ((n_samples + 255) / 256) * 256;
+        FTK_HIP(c, hipMalloc(&c->d_pos, (size_t)cap * sizeof(uint32_t)));
+        FTK_HIP(c, hipMalloc(&c->d_bidx, (size_t)cap * c->order * sizeof(int32_t)));
+        FTK_HIP(c, hipMalloc(&c->d_bval, (size_t)cap * sizeof(float)));
+        c->cap = cap;
+    }
+    Coo coo{c->d_rec, c->rec_words};
+    {
+        Bracket t(c, FTK_K_SAMPLE);
+        hipLaunchKernelGGL(sample_gather_kernel, dim3((unsigned)((n_samples + 255) / 256)), dim3(256), 0, c->stream, coo,
+                           c->order, (uint64_t)c->nnz, c->sample_seed, (long long)n_samples, c->cap, c->d_pos,
+                           c->d_bidx, c->d_bval);
+    }
+    FTK_HIP(c, hipGetLastError());
+    c->batch_valid = true;
+    return FTK_OK;
 }
 
 int launch_errors(ftk_ctx* c, double* host_sums) {
@@ -264,7 +300,7 @@ void release(ftk_ctx* c) {
 // all modes (rows are already sorted by count within a mode, so this is a merge of sorted lists).
 void pick_hot_rows(ftk_ctx* c, const std::vector<std::vector<unsigned int>>& sorted_counts) {
     const int N = c->order;
-    const long long budget = (long long)c->max_lds - 4LL * (kMfmaWaves * kWaveScratch + N * 256) - 1024;
+    const long long budget = (long long)c->max_lds - 4LL * (kMfmaWaves * mfma16_wave_scratch(N) + N * 256) - 1024;
     int H = (int)std::max(0LL, budget / 64);
     long long rows_total = 0;
     for (int n = 0; n < N; ++n) rows_total += c->dims[n];
@@ -291,7 +327,7 @@ void pick_hot_rows(ftk_ctx* c, const std::vector<std::vector<unsigned int>>& sor
         off += taken[n];
     }
     c->hot_H = std::max(off, 1);
-    c->mfma_lds_bytes = 4 * ((size_t)c->hot_H * 16 + kMfmaWaves * kWaveScratch + N * 256);
+    c->mfma_lds_bytes = 4 * ((size_t)c->hot_H * 16 + kMfmaWaves * mfma16_wave_scratch(N) + N * 256);
 }
 
 int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, const float* vals, uint64_t init_seed,
@@ -474,31 +510,11 @@ int ftk_sample(ftk_ctx* c, uint64_t seed, int64_t n_samples) {
     if (!c) return FTK_EINVAL;
     if (n_samples < 1 || n_samples >= (1LL << 31))
         return fail(c, FTK_EINVAL, "n_samples %lld outside 1..2^31-1", (long long)n_samples);
-    if (n_samples > c->cap) {
-        FTK_HIP(c, hipStreamSynchronize(c->stream));
-        if (c->d_pos) hipFree(c->d_pos);
-        if (c->d_bidx) hipFree(c->d_bidx);
-        if (c->d_bval) hipFree(c->d_bval);
-        c->d_pos = nullptr;
-        c->d_bidx = nullptr;
-        c->d_bval = nullptr;
-        c->cap = 0;
-        c->n_samples = 0;
-        const long long cap = ((n_samples + 255) / 256) * 256;
-        FTK_HIP(c, hipMalloc(&c->d_pos, (size_t)cap * sizeof(uint32_t)));
-        FTK_HIP(c, hipMalloc(&c->d_bidx, (size_t)cap * c->order * sizeof(int32_t)));
-        FTK_HIP(c, hipMalloc(&c->d_bval, (size_t)cap * sizeof(float)));
-        c->cap = cap;
-    }
-    Coo coo{c->d_rec, c->rec_words};
-    {
-        Bracket t(c, FTK_K_SAMPLE);
-        hipLaunchKernelGGL(sample_gather_kernel, dim3((unsigned)((n_samples + 255) / 256)), dim3(256), 0, c->stream, coo,
-                           c->order, (uint64_t)c->nnz, seed, (long long)n_samples, c->cap, c->d_pos, c->d_bidx,
-                           c->d_bval);
-    }
-    FTK_HIP(c, hipGetLastError());
+    // Psi is a pure function of (seed, k): the fused kernel regenerates positions in registers,
+    // so nothing is launched here; the arrays are only materialised for callers that need them.
+    c->sample_seed = seed;
     c->n_samples = n_samples;
+    c->batch_valid = false;
     return FTK_OK;
 }
 
@@ -506,6 +522,10 @@ int ftk_get_samples(ftk_ctx* c, int64_t* pos_out) {
     if (!c) return FTK_EINVAL;
     if (!pos_out) return fail(c, FTK_EINVAL, "pos_out is NULL");
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_get_samples before ftk_sample");
+    {
+        const int rc = ensure_batch(c);
+        if (rc != FTK_OK) return rc;
+    }
     try {
         std::vector<uint32_t> tmp((size_t)c->n_samples);
         FTK_HIP(c, hipMemcpyAsync(tmp.data(), c->d_pos, tmp.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream));
@@ -522,7 +542,9 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step before ftk_sample");
     if (c->mode != FTK_SYNC) return fail(c, FTK_EUNSUPPORTED, "only FTK_SYNC is built");
     const bool mfma = c->variant == V_MFMA16;
-    int rc = mfma ? launch_grad_mfma16(c, lambda_A) : launch_grad_generic(c, lambda_A);
+    int rc = mfma ? FTK_OK : ensure_batch(c);
+    if (rc != FTK_OK) return rc;
+    rc = mfma ? launch_grad_mfma16(c, lambda_A) : launch_grad_generic(c, lambda_A);
     if (rc != FTK_OK) return rc;
     {
         ApplyHotArgs h = {};

@@ -1,29 +1,32 @@
-// Gradient pass for J_n = R = 16 (any order N), built on the fp32 matrix cores.
+// Fused sampling + gradient pass for J_n = R = 16 (order N <= 6), built on the fp32 matrix cores.
 //
-// One wavefront owns a tile of 16 sampled entries.  All three contractions of the method are
-// 16x16 matrix products per mode and run as v_mfma_f32_16x16x4_f32 (four K-steps each):
+// One wavefront draws 64 positions of Psi at a time (one Philox position and one random record
+// read per lane), parks the 64 records in a private LDS buffer, and then works through them as
+// four tiles of 16 sampled entries.  The three contractions of the method are 16x16 matrix
+// products per mode and run as v_mfma_f32_16x16x4_f32 (four K-steps each):
 //
 //   projections   C^T  [r x sample] = B^T [r x j]      . a^T [j x sample]      (contract j)
 //   A gradient    GS   [sample x j] = W   [sample x r] . B^T [r x j]           (contract r)
 //   core gradient GB   [j x r]     += a^T [j x sample] . (-e W) [sample x r]   (contract the tile's samples)
 //
 // Operand layout of the instruction (lane l, c = l % 16, g = l / 16):
-//   A operand holds M[c][4g' ... ] one K-slot per lane group:  Aop(l) = M[row c][k = g]
-//   B operand:                                                  Bop(l) = M[k = g][col c]
-//   accumulator register v:                                     D(l, v) = M[row 4g + v][col c]
-// A contracted index must sit in the (g, K-step) position of both operands, so the kernel keeps
-// two register layouts of the per-sample data:
-//   X: lane (c, g) holds sample c, components 4g..4g+3   (rows as gathered with one 16-byte load)
-//   Y: lane (c, g) holds component c of samples 4g..4g+3 (16 lanes cover one 64-byte row)
-// Rows are gathered in both layouts (the second read hits in cache); -e w moves from X to Y
-// through a small per-wave LDS buffer.  The A gradient comes out of the matrix core directly in
-// layout Y, which is the layout that lets a row be added with ONE 64-byte atomic request.
+//   A operand: Aop(l) = M[row c][k = g]      B operand: Bop(l) = M[k = g][col c]
+//   accumulator register v: D(l, v) = M[row 4g + v][col c]
+// A contracted index has to sit in the (g, K-step) position of both operands, so per-sample data
+// exists in two register layouts:
+//   X: lane (c, g) holds sample c, components 4g..4g+3
+//   Y: lane (c, g) holds component c of samples 4g..4g+3   (16 lanes cover one 64-byte row)
+// Rows are gathered in layout Y only (four full 64-byte rows per load instruction) and reach
+// layout X through a per-wave LDS buffer; -e w goes the other way.  The A gradient comes out of
+// the matrix core directly in layout Y, which lets a row be added with ONE 64-byte atomic request.
+// The row gather of the next tile is issued before the current tile is computed, and the record
+// reads of the next 64 samples are in flight during the whole current group of four tiles.
 //
 // Rows are numbered by descending frequency, so the rows most samples hit are rows [0, K_n) of
-// each mode: their gradient sums are kept in LDS (one table per workgroup, LDS float adds) and
-// written out once per workgroup; only the remaining rows use global float atomics.  The core
+// each mode: their gradient sums are kept in an LDS table (one per workgroup) and leave the
+// workgroup once, as plain stores; only the remaining rows use global float atomics.  The core
 // gradient is accumulated in matrix-core accumulators over all tiles of a wave, reduced across
-// the workgroup's waves in LDS, and leaves the workgroup as one table of plain stores.
+// the workgroup's waves in LDS, and also leaves the workgroup as one table of plain stores.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -34,12 +37,19 @@ namespace ftk {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kMfmaWaves = 16;                 // waves per workgroup (one workgroup per CU)
+constexpr int kMfmaWaves = 8;                  // waves per workgroup (one workgroup per CU)
 constexpr int kMfmaThreads = kMfmaWaves * 64;
-constexpr int kWaveScratch = 16 * 20 + 16;     // floats: padded 16x16 transpose buffer + 16 errors
+constexpr int kTransposeFloats = 16 * 20;      // 16x16 tile, rows padded to 20 floats
+__host__ __device__ constexpr int mfma16_wave_scratch(int order) {
+    // floats per wave: N index columns + values of 64 samples | transpose buffer | 16 errors
+    return (order + 1) * 64 + kTransposeFloats + 16;
+}
 
 struct Mfma16Args {
-    Batch batch;
+    Coo coo;
+    uint64_t nnz;
+    uint64_t seed;
+    long long M;              // |Psi|
     const float* A;
     const float* B;
     float* dA;
@@ -51,12 +61,11 @@ struct Mfma16Args {
     float* hot_partial;       // [gridDim.x][H][16]
     float* gb_partial;        // [gridDim.x][N * 256]
     float lambda_A;
-    long long n_tiles;
 };
 
 __device__ __forceinline__ void lds_wave_sync() {
-    // LDS requests of one wave complete in order; this only has to keep the compiler from
-    // moving the transposed reads above the writes (and waits for them).
+    // LDS requests of one wave complete in order; this keeps the compiler from moving LDS reads
+    // above the writes of other lanes they depend on, and waits for outstanding LDS traffic.
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
@@ -73,13 +82,25 @@ __device__ __forceinline__ void lds_float_add(float* p, float v) {
 }
 
 template <int N>
+struct TileRows {
+    float aY[N][4];   // layout Y: component c of the rows of samples 4g..4g+3
+    int iY[N][4];     // their row numbers
+    float x;          // value of sample c (layout X)
+};
+
+template <int N>
 __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g) {
     extern __shared__ float lds[];
+    constexpr int W4 = (N + 1 + 3) / 4;   // 16-byte words per record
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g4 = lane >> 4;
     float* hot = lds;
-    float* scratch = lds + (size_t)g.H * 16 + wave * kWaveScratch;
-    float* gbred = lds + (size_t)g.H * 16 + kMfmaWaves * kWaveScratch;
+    float* wave_lds = lds + (size_t)g.H * 16 + wave * mfma16_wave_scratch(N);
+    int* sidx = reinterpret_cast<int*>(wave_lds);           // [N][64]
+    float* sval = wave_lds + N * 64;                         // [64]
+    float* tbuf = wave_lds + (N + 1) * 64;                   // [16][20]
+    float* ebuf = tbuf + kTransposeFloats;                   // [16]
+    float* gbred = lds + (size_t)g.H * 16 + kMfmaWaves * mfma16_wave_scratch(N);
 
     for (int q = tid; q < g.H * 16; q += kMfmaThreads) hot[q] = 0.0f;
     for (int q = tid; q < N * 256; q += kMfmaThreads) gbred[q] = 0.0f;
@@ -100,112 +121,147 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     for (int n = 0; n < N; ++n) GBacc[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
     __syncthreads();
 
-    const long long M = g.batch.count, cap = g.batch.cap;
-    for (long long tile = (long long)blockIdx.x * kMfmaWaves + wave; tile < g.n_tiles;
-         tile += (long long)gridDim.x * kMfmaWaves) {
-        const long long base = tile * 16;
-        const bool actX = base + c < M;
-        bool actY[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) actY[v] = base + 4 * g4 + v < M;
+    const long long M = g.M;
+    const long long n_groups = (M + 63) / 64;
+    const long long group_stride = (long long)gridDim.x * kMfmaWaves;
+    const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
 
-        // row numbers: layout X (sample c) and layout Y (samples 4g..4g+3); rows of inactive samples
-        // are row 0 with all data forced to zero, so every contribution of theirs is exactly zero
-        int iX[N], iY[N][4];
+    // record of sample (group * 64 + lane): N row numbers and the value's bits
+    auto load_record = [&](long long group, uint4 (&rec)[W4]) {
+        const long long k = group * 64 + lane;
+        const uint32_t p = k < M ? sample_position(g.seed, (uint64_t)k, g.nnz) : 0u;
+#pragma unroll
+        for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
+    };
+    // rows of tile `sub` (0..3) of the group parked in LDS, gathered in layout Y
+    auto gather = [&](long long group, int sub, TileRows<N>& t) {
+        const long long base = group * 64 + sub * 16;
+        t.x = sval[sub * 16 + c];
 #pragma unroll
         for (int n = 0; n < N; ++n) {
-            const int32_t* col = g.batch.idx + (long long)n * cap + base;
-            iX[n] = actX ? col[c] : 0;
-            const int4 t = *reinterpret_cast<const int4*>(col + 4 * g4);
-            iY[n][0] = actY[0] ? t.x : 0;
-            iY[n][1] = actY[1] ? t.y : 0;
-            iY[n][2] = actY[2] ? t.z : 0;
-            iY[n][3] = actY[3] ? t.w : 0;
-        }
-        const float x = actX ? g.batch.val[base + c] : 0.0f;
-
-        floatx4 aX[N];
-        float aY[N][4];
-#pragma unroll
-        for (int n = 0; n < N; ++n) {
+            const int4 r = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
+            t.iY[n][0] = r.x;
+            t.iY[n][1] = r.y;
+            t.iY[n][2] = r.z;
+            t.iY[n][3] = r.w;
             const float* An = g.A + g.A_off[n];
-            const float4 t = *reinterpret_cast<const float4*>(An + (long long)iX[n] * 16 + 4 * g4);
-            aX[n] = actX ? floatx4{t.x, t.y, t.z, t.w} : floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float t1 = An[(long long)iY[n][v] * 16 + c];
-                aY[n][v] = actY[v] ? t1 : 0.0f;
+                // samples past the end of Psi were parked as row 0 with value 0; their rows are
+                // forced to zero so that every contribution of theirs is exactly zero
+                const float a = An[(long long)t.iY[n][v] * 16 + c];
+                t.aY[n][v] = (base + 4 * g4 + v < M) ? a : 0.0f;
             }
         }
+    };
 
-        // projections, layout X:  s[n][v] = c^(n)_{r = 4g+v} of sample c
-        floatx4 s[N];
-#pragma unroll
-        for (int n = 0; n < N; ++n) {
-            floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][k], aX[n][k], acc, 0, 0, 0);
-            s[n] = acc;
-        }
+    uint4 rec[W4];
+    long long group = (long long)blockIdx.x * kMfmaWaves + wave;
+    if (group < n_groups) load_record(group, rec);
 
-        // leave-one-out products (prefix sweep, then suffix sweep), prediction, error
-        floatx4 w[N];
-        floatx4 run = {1.0f, 1.0f, 1.0f, 1.0f};
+    for (; group < n_groups; group += group_stride) {
+        // park the 64 records (struct of arrays) for this wave
+        {
+            const bool act = group * 64 + lane < M;
+            uint32_t flat[4 * W4];
 #pragma unroll
-        for (int n = 0; n < N; ++n) {
-            w[n] = run;
-            run *= s[n];
-        }
-        float xhat = (run[0] + run[1]) + (run[2] + run[3]);
-        xhat += __shfl_xor(xhat, 16);
-        xhat += __shfl_xor(xhat, 32);
-        const float e = x - xhat;
-        run = floatx4{1.0f, 1.0f, 1.0f, 1.0f};
+            for (int q = 0; q < W4; ++q) {
+                flat[4 * q + 0] = rec[q].x;
+                flat[4 * q + 1] = rec[q].y;
+                flat[4 * q + 2] = rec[q].z;
+                flat[4 * q + 3] = rec[q].w;
+            }
 #pragma unroll
-        for (int n = N - 1; n >= 0; --n) {
-            w[n] *= run;
-            run *= s[n];
+            for (int n = 0; n < N; ++n) sidx[n * 64 + lane] = act ? (int)flat[n] : 0;
+            sval[lane] = act ? __uint_as_float(flat[N]) : 0.0f;
         }
-
-        // errors of samples 4g..4g+3 for layout Y
-        if (g4 == 0) scratch[320 + c] = e;
         lds_wave_sync();
-        const float4 eY4 = *reinterpret_cast<const float4*>(scratch + 320 + 4 * g4);
-        const float eY[4] = {eY4.x, eY4.y, eY4.z, eY4.w};
+        if (group + group_stride < n_groups) load_record(group + group_stride, rec);
 
+        TileRows<N> cur, nxt;
+        gather(group, 0, nxt);
 #pragma unroll
-        for (int n = 0; n < N; ++n) {
-            // GS^(n) in layout Y:  gs[v] = GS_{j = c} of sample 4g+v
-            floatx4 gs = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) gs = __builtin_amdgcn_mfma_f32_16x16x4f32(w[n][k], Br[n][k], gs, 0, 0, 0);
+        for (int sub = 0; sub < 4; ++sub) {
+            cur = nxt;
+            if (sub < 3) gather(group, sub + 1, nxt);
+            const long long base = group * 64 + sub * 16;
 
-            // -e w: layout X -> LDS -> layout Y
-            const floatx4 wp = w[n] * (-e);
-            *reinterpret_cast<float4*>(scratch + c * 20 + 4 * g4) = make_float4(wp[0], wp[1], wp[2], wp[3]);
-            lds_wave_sync();
-            float wY[4];
+            // rows: layout Y -> LDS -> layout X, then projections s[n][v] = c^(n)_{r = 4g+v} of sample c
+            floatx4 s[N];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) wY[v] = scratch[(4 * g4 + v) * 20 + c];
-            lds_wave_sync();
-
-            // factor-row gradient -e GS + lambda_A a, one 64-byte row per 16 lanes
+            for (int n = 0; n < N; ++n) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if (actY[v]) {
-                    const float grad = fmaf(-eY[v], gs[v], g.lambda_A * aY[n][v]);
-                    const int row = iY[n][v];
-                    if (row < g.K[n])
-                        lds_float_add(hot + (size_t)(g.hot_off[n] + row) * 16 + c, grad);
-                    else
-                        atomicAdd(g.dA + g.A_off[n] + (long long)row * 16 + c, grad);
-                }
+                for (int v = 0; v < 4; ++v) tbuf[(4 * g4 + v) * 20 + c] = cur.aY[n][v];
+                lds_wave_sync();
+                const float4 ax = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
+                lds_wave_sync();
+                floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][0], ax.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][1], ax.y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][2], ax.z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][3], ax.w, acc, 0, 0, 0);
+                s[n] = acc;
             }
 
-            // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
+            // leave-one-out products (prefix sweep, then suffix sweep), prediction, error
+            floatx4 w[N];
+            floatx4 run = {1.0f, 1.0f, 1.0f, 1.0f};
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[v], GBacc[n], 0, 0, 0);
+            for (int n = 0; n < N; ++n) {
+                w[n] = run;
+                run *= s[n];
+            }
+            float xhat = (run[0] + run[1]) + (run[2] + run[3]);
+            xhat += __shfl_xor(xhat, 16);
+            xhat += __shfl_xor(xhat, 32);
+            const float e = cur.x - xhat;
+            run = floatx4{1.0f, 1.0f, 1.0f, 1.0f};
+#pragma unroll
+            for (int n = N - 1; n >= 0; --n) {
+                w[n] *= run;
+                run *= s[n];
+            }
+
+            // errors of samples 4g..4g+3 for layout Y
+            if (g4 == 0) ebuf[c] = e;
+            lds_wave_sync();
+            const float4 eY4 = *reinterpret_cast<const float4*>(ebuf + 4 * g4);
+            const float eY[4] = {eY4.x, eY4.y, eY4.z, eY4.w};
+
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                // GS^(n) in layout Y:  gs[v] = GS_{j = c} of sample 4g+v
+                floatx4 gs = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) gs = __builtin_amdgcn_mfma_f32_16x16x4f32(w[n][k], Br[n][k], gs, 0, 0, 0);
+
+                // -e w: layout X -> LDS -> layout Y
+                const floatx4 wp = w[n] * (-e);
+                *reinterpret_cast<float4*>(tbuf + c * 20 + 4 * g4) = make_float4(wp[0], wp[1], wp[2], wp[3]);
+                lds_wave_sync();
+                float wY[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) wY[v] = tbuf[(4 * g4 + v) * 20 + c];
+                lds_wave_sync();
+
+                // factor-row gradient -e GS + lambda_A a, one 64-byte row per 16 lanes
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if (base + 4 * g4 + v < M) {
+                        const float grad = fmaf(-eY[v], gs[v], g.lambda_A * cur.aY[n][v]);
+                        const int row = cur.iY[n][v];
+                        if (row < g.K[n])
+                            lds_float_add(hot + (size_t)(g.hot_off[n] + row) * 16 + c, grad);
+                        else
+                            atomicAdd(g.dA + g.A_off[n] + (long long)row * 16 + c, grad);
+                    }
+                }
+
+                // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(cur.aY[n][v], wY[v], GBacc[n], 0, 0, 0);
+            }
         }
     }
 
