@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 FP32_VALU_PEAK_TFLOPS = 157.3    # MI355X fp32 vector, published
-KERNEL_SLOTS = ["sample_gather", "grad", "apply_A", "apply_B"]
+KERNEL_SLOTS = ["sample_gather", "grad", "apply"]
 
 
 def algorithmic_bytes_per_sample(w) -> int:

@@ -148,7 +148,12 @@ int ftk_set_stream(ftk_ctx* ctx, void* hip_stream);
  * `which` (FTK_K_*), the summed milliseconds and the number of launches since timing was
  * switched on (or last read with reset != 0).
  */
-enum { FTK_K_SAMPLE = 0, FTK_K_GRAD = 1, FTK_K_APPLY_A = 2, FTK_K_APPLY_B = 3, FTK_K_COUNT = 4 };
+enum {
+    FTK_K_SAMPLE = 0,   /* Psi materialised as arrays (only launched for the generic kernel / ftk_get_samples) */
+    FTK_K_GRAD = 1,     /* gradient pass (the specialised variants also draw Psi and fetch the entries in it) */
+    FTK_K_APPLY = 2,    /* update pass: A, B */
+    FTK_K_COUNT = 3
+};
 int ftk_set_timing(ftk_ctx* ctx, int enabled);
 int ftk_get_timing(ftk_ctx* ctx, int which, double* total_ms, int64_t* launches, int reset);
 

@@ -217,6 +217,7 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A) {
         g.A_off[n] = c->L.A_off[n];
         g.B_off[n] = c->L.B_off[n];
         g.K[n] = c->hot_K[n];
+        g.top[n] = c->hot_K[n] >= 16 ? 16 : 0;
         g.hot_off[n] = c->hot_off[n];
     }
     g.H = c->hot_H;
@@ -355,7 +356,8 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     c->L.B_total = b_off;
     pick_generic_config(c);
     c->mfma16_ok = c->L.R == 16 && N <= 6 && c->max_lds >= 131072;
-    for (int n = 0; n < N; ++n) c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16;
+    for (int n = 0; n < N; ++n)   // 16-float rows, addressed with 32-bit element offsets inside a mode
+        c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16 && dims[n] < (1LL << 26);
     if (c->gen_threads == 0 && !c->mfma16_ok)
         return fail(c, FTK_EUNSUPPORTED, "N*R = %d with sum J_n R = %d exceeds the kernels' LDS budget", N * c->L.R,
                     c->L.B_total);
@@ -547,33 +549,36 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
     rc = mfma ? launch_grad_mfma16(c, lambda_A) : launch_grad_generic(c, lambda_A);
     if (rc != FTK_OK) return rc;
     {
-        ApplyHotArgs h = {};
-        int hot_blocks = 0;
+        ApplyArgs p = {};
+        p.A = c->d_A;
+        p.dA = c->d_dA;
+        p.n4 = c->A_total / 4;
+        p.dense_blocks = blocks_for(p.n4, 256, c->num_cu * 16);
         if (mfma) {
-            h.hot_partial = c->d_hot_partial;
-            h.parts = c->mfma_grid;
-            h.H = c->hot_H;
-            h.J = 16;
-            h.order = c->order;
+            p.hot_partial = c->d_hot_partial;
+            p.hot_parts = c->mfma_grid;
+            p.H = c->hot_H;
+            p.J = 16;
+            p.hot_blocks = (c->hot_H * 16 + 15) / 16;
+            p.order = c->order;
             for (int n = 0; n < kMaxOrder; ++n) {
-                h.K[n] = c->hot_K[n];
-                h.hot_off[n] = c->hot_off[n];
-                h.A_off[n] = c->L.A_off[n];
+                p.K[n] = c->hot_K[n];
+                p.hot_off[n] = c->hot_off[n];
+                p.A_off[n] = c->L.A_off[n];
             }
-            hot_blocks = (c->hot_H * 16 + 255) / 256;
         }
-        const long long n4 = c->A_total / 4;
-        const int dense_blocks = blocks_for(n4, 256, c->num_cu * 16);
-        Bracket t(c, FTK_K_APPLY_A);
-        hipLaunchKernelGGL(apply_A_hot_kernel, dim3(dense_blocks + hot_blocks), dim3(256), 0, c->stream, c->d_A, c->d_dA,
-                           n4, lr_A, dense_blocks, h);
-    }
-    FTK_HIP(c, hipGetLastError());
-    {
-        Bracket t(c, FTK_K_APPLY_B);
-        hipLaunchKernelGGL(apply_B_kernel, dim3((c->L.B_total * 16 + 255) / 256), dim3(256), 0, c->stream, c->d_B,
-                           mfma ? c->d_gb_partial : c->d_GB, c->L.B_total, mfma ? c->mfma_grid : 1, mfma ? 0 : 1, lr_B,
-                           lambda_B, 1.0f / (float)c->n_samples);
+        p.B = c->d_B;
+        p.GB = mfma ? c->d_gb_partial : c->d_GB;
+        p.B_total = c->L.B_total;
+        p.gb_parts = mfma ? c->mfma_grid : 1;
+        p.gb_clear = mfma ? 0 : 1;
+        p.lr_A = lr_A;
+        p.lr_B = lr_B;
+        p.lambda_B = lambda_B;
+        p.inv_M = 1.0f / (float)c->n_samples;
+        const int b_blocks = (c->L.B_total + 15) / 16;
+        Bracket t(c, FTK_K_APPLY);
+        hipLaunchKernelGGL(apply_kernel, dim3(p.dense_blocks + p.hot_blocks + b_blocks), dim3(256), 0, c->stream, p);
     }
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;

@@ -177,48 +177,6 @@ __global__ void grad_generic_kernel(GradArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// update passes
-// ---------------------------------------------------------------------------------------------
-// A <- A - lr_A dA wherever dA != 0, and dA <- 0 (dA == 0 means: untouched, or a zero gradient).
-__global__ void __launch_bounds__(256) apply_A_kernel(float* __restrict__ A, float* __restrict__ dA,
-                                                      long long n4, float lr_A) {
-    float4* A4 = reinterpret_cast<float4*>(A);
-    float4* D4 = reinterpret_cast<float4*>(dA);
-    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < n4;
-         q += (long long)gridDim.x * blockDim.x) {
-        const float4 d = D4[q];
-        if (d.x != 0.0f || d.y != 0.0f || d.z != 0.0f || d.w != 0.0f) {
-            float4 a = A4[q];
-            a.x = fmaf(-lr_A, d.x, a.x);
-            a.y = fmaf(-lr_A, d.y, a.y);
-            a.z = fmaf(-lr_A, d.z, a.z);
-            a.w = fmaf(-lr_A, d.w, a.w);
-            A4[q] = a;
-            D4[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        }
-    }
-}
-
-// B <- B - lr_B (GB / M + lambda_B B).  GB is the sum of `parts` partial tables of `count` floats
-// each; with clear != 0 the (single, atomically accumulated) table is zeroed for the next step.
-// One 64-lane wave per group of 4 entries: 16 lanes stride over the partial tables of an entry.
-__global__ void __launch_bounds__(256) apply_B_kernel(float* __restrict__ B, float* __restrict__ GB, int count,
-                                                      int parts, int clear, float lr_B, float lambda_B, float inv_M) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    const int q = t >> 4, sub = t & 15;
-    float gsum = 0.0f;
-    if (q < count)
-        for (int b = sub; b < parts; b += 16) gsum += GB[(size_t)b * count + q];
-#pragma unroll
-    for (int o = 8; o > 0; o >>= 1) gsum += __shfl_xor(gsum, o);
-    if (q < count && sub == 0) {
-        const float b0 = B[q];
-        B[q] = b0 - lr_B * fmaf(gsum, inv_M, lambda_B * b0);
-        if (clear) GB[q] = 0.0f;
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
 // whole-tensor error sums (RMSE / MAE): one lane per stored nonzero, streaming over Omega
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) errors_generic_kernel(Coo coo, Layout L, uint64_t nnz,

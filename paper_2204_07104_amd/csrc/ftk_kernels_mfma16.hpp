@@ -17,14 +17,18 @@
 //   X: lane (c, g) holds sample c, components 4g..4g+3
 //   Y: lane (c, g) holds component c of samples 4g..4g+3   (16 lanes cover one 64-byte row)
 // Rows are gathered in layout Y only (four full 64-byte rows per load instruction) and reach
-// layout X through a per-wave LDS buffer; -e w goes the other way.  The A gradient comes out of
-// the matrix core directly in layout Y, which lets a row be added with ONE 64-byte atomic request.
+// layout X through a per-wave LDS buffer; -e w goes the other way.  The A gradient (with the -e
+// factor already folded into w) comes out of the matrix core directly in layout Y, which lets a
+// row be added with ONE 64-byte atomic request.
 // The row gather of the next tile is issued before the current tile is computed, and the record
 // reads of the next 64 samples are in flight during the whole current group of four tiles.
 //
 // Rows are numbered by descending frequency, so the rows most samples hit are rows [0, K_n) of
 // each mode: their gradient sums are kept in an LDS table (one per workgroup) and leave the
-// workgroup once, as plain stores; only the remaining rows use global float atomics.  The core
+// workgroup once, as plain stores; only the remaining rows use global float atomics.  The 16
+// most frequent rows of a mode do not even touch LDS per sample: the tile's gradients are summed
+// per row by one more matrix product, ONEHOT [row x sample] . GRAD [sample x j], into
+// accumulators that live in registers for the whole kernel.  The core
 // gradient is accumulated in matrix-core accumulators over all tiles of a wave, reduced across
 // the workgroup's waves in LDS, and also leaves the workgroup as one table of plain stores.
 #pragma once
@@ -41,8 +45,8 @@ constexpr int kMfmaWaves = 8;                  // waves per workgroup (one workg
 constexpr int kMfmaThreads = kMfmaWaves * 64;
 constexpr int kTransposeFloats = 16 * 20;      // 16x16 tile, rows padded to 20 floats
 __host__ __device__ constexpr int mfma16_wave_scratch(int order) {
-    // floats per wave: N index columns + values of 64 samples | transpose buffer | 16 errors
-    return (order + 1) * 64 + kTransposeFloats + 16;
+    // floats per wave: N index columns + values of 64 samples | one transpose buffer per mode
+    return (order + 1) * 64 + order * kTransposeFloats;
 }
 
 struct Mfma16Args {
@@ -56,6 +60,7 @@ struct Mfma16Args {
     long long A_off[kMaxOrder];
     int B_off[kMaxOrder];
     int K[kMaxOrder];         // rows [0, K[n]) of mode n live in the LDS table
+    int top[kMaxOrder];       // 16 if K[n] >= 16 (rows 0..15 go through the one-hot matrix product), else 0
     int hot_off[kMaxOrder];   // first LDS table row of mode n
     int H;                    // rows in the LDS table (>= sum K[n])
     float* hot_partial;       // [gridDim.x][H][16]
@@ -88,54 +93,26 @@ struct TileRows {
     float x;          // value of sample c (layout X)
 };
 
+// Everything a wave keeps across tiles.
 template <int N>
-__global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g) {
-    extern __shared__ float lds[];
-    constexpr int W4 = (N + 1 + 3) / 4;   // 16-byte words per record
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 15, g4 = lane >> 4;
-    float* hot = lds;
-    float* wave_lds = lds + (size_t)g.H * 16 + wave * mfma16_wave_scratch(N);
-    int* sidx = reinterpret_cast<int*>(wave_lds);           // [N][64]
-    float* sval = wave_lds + N * 64;                         // [64]
-    float* tbuf = wave_lds + (N + 1) * 64;                   // [16][20]
-    float* ebuf = tbuf + kTransposeFloats;                   // [16]
-    float* gbred = lds + (size_t)g.H * 16 + kMfmaWaves * mfma16_wave_scratch(N);
+struct WaveState {
+    float Bq[N][4], Br[N][4];   // B^(n) in the two operand layouts: Bq[n][k] = B[4g+k][c], Br[n][k] = B[c][4g+k]
+    floatx4 GBacc[N];           // core gradient, D layout: GB[j = 4g+v][r = c]
+    floatx4 Top[N];             // gradient sums of rows 0..15 of each mode, D layout: [row 4g+v][j = c]
+};
 
-    for (int q = tid; q < g.H * 16; q += kMfmaThreads) hot[q] = 0.0f;
-    for (int q = tid; q < N * 256; q += kMfmaThreads) gbred[q] = 0.0f;
-
-    // B^(n) in the two operand layouts:  Bq[n][k] = B[4g+k][c],  Br[n][k] = B[c][4g+k]
-    float Bq[N][4], Br[N][4];
-#pragma unroll
-    for (int n = 0; n < N; ++n) {
-        const float* Bn = g.B + g.B_off[n];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            Bq[n][k] = Bn[(4 * g4 + k) * 16 + c];
-            Br[n][k] = Bn[c * 16 + 4 * g4 + k];
-        }
-    }
-    floatx4 GBacc[N];
-#pragma unroll
-    for (int n = 0; n < N; ++n) GBacc[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
-    __syncthreads();
-
+// One group of 64 samples whose records are parked in this wave's LDS buffer: four tiles of 16.
+// MASKED: the group reaches past the end of Psi (only the last group can); samples past the end
+// were parked as row 0 / value 0 and every contribution of theirs is forced to zero.
+template <int N, bool MASKED, class IssueNext>
+__device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, long long group, float* hot,
+                                              const int* sidx, const float* sval, float* tbuf, int c, int g4,
+                                              IssueNext&& issue_next_records) {
     const long long M = g.M;
-    const long long n_groups = (M + 63) / 64;
-    const long long group_stride = (long long)gridDim.x * kMfmaWaves;
-    const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
+    auto active = [&](int sub, int v) -> bool { return !MASKED || group * 64 + sub * 16 + 4 * g4 + v < M; };
 
-    // record of sample (group * 64 + lane): N row numbers and the value's bits
-    auto load_record = [&](long long group, uint4 (&rec)[W4]) {
-        const long long k = group * 64 + lane;
-        const uint32_t p = k < M ? sample_position(g.seed, (uint64_t)k, g.nnz) : 0u;
-#pragma unroll
-        for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
-    };
-    // rows of tile `sub` (0..3) of the group parked in LDS, gathered in layout Y
-    auto gather = [&](long long group, int sub, TileRows<N>& t) {
-        const long long base = group * 64 + sub * 16;
+    // rows of tile `sub` gathered in layout Y (four full 64-byte rows per load instruction)
+    auto gather = [&](int sub, TileRows<N>& t) {
         t.x = sval[sub * 16 + c];
 #pragma unroll
         for (int n = 0; n < N; ++n) {
@@ -147,12 +124,186 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
             const float* An = g.A + g.A_off[n];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                // samples past the end of Psi were parked as row 0 with value 0; their rows are
-                // forced to zero so that every contribution of theirs is exactly zero
-                const float a = An[(long long)t.iY[n][v] * 16 + c];
-                t.aY[n][v] = (base + 4 * g4 + v < M) ? a : 0.0f;
+                const float a = An[(uint32_t)(t.iY[n][v] * 16 + c)];
+                t.aY[n][v] = active(sub, v) ? a : 0.0f;
             }
         }
+    };
+
+    TileRows<N> cur, nxt;
+    gather(0, nxt);
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+        cur = nxt;
+        if (sub < 3) gather(sub + 1, nxt);
+        // Vector-memory results are waited for in issue order, so the long-latency random record
+        // reads of the next group go out only after this group's last row gather.
+        if (sub == 2) issue_next_records();
+
+        // rows of all modes: layout Y -> LDS -> layout X
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c] = cur.aY[n][v];
+        lds_wave_sync();
+        float4 aX[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+            aX[n] = *reinterpret_cast<const float4*>(tbuf + n * kTransposeFloats + c * 20 + 4 * g4);
+
+        // projections, layout X:  s[n][v] = c^(n)_{r = 4g+v} of sample c
+        floatx4 s[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n) s[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][0], aX[n].x, s[n], 0, 0, 0);
+#pragma unroll
+        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][1], aX[n].y, s[n], 0, 0, 0);
+#pragma unroll
+        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][2], aX[n].z, s[n], 0, 0, 0);
+#pragma unroll
+        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][3], aX[n].w, s[n], 0, 0, 0);
+
+        // leave-one-out products (prefix sweep, then suffix sweep), prediction, error
+        floatx4 w[N];
+        floatx4 run = {1.0f, 1.0f, 1.0f, 1.0f};
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            w[n] = run;
+            run *= s[n];
+        }
+        float xhat = (run[0] + run[1]) + (run[2] + run[3]);
+        xhat += __shfl_xor(xhat, 16);
+        xhat += __shfl_xor(xhat, 32);
+        const float neg_e = xhat - cur.x;
+        run = floatx4{1.0f, 1.0f, 1.0f, 1.0f};
+#pragma unroll
+        for (int n = N - 1; n >= 0; --n) {
+            w[n] *= run;
+            run *= s[n];
+        }
+
+        // -e w of all modes: layout X -> LDS -> layout Y.  (The a-reads of this buffer are
+        // complete: the projections above consumed them.)
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            w[n] *= neg_e;
+            *reinterpret_cast<float4*>(tbuf + n * kTransposeFloats + c * 20 + 4 * g4) =
+                make_float4(w[n][0], w[n][1], w[n][2], w[n][3]);
+        }
+        // -e GS^(n) straight into layout Y:  gs[n][v] = -e GS_{j = c} of sample 4g+v
+        floatx4 gs[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n) gs[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+                gs[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[n][k], st.Br[n][k], gs[n], 0, 0, 0);
+        lds_wave_sync();
+        float wY[N][4];
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) wY[n][v] = tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c];
+
+        // Factor-row gradients -e GS + lambda_A a, one 64-byte row per 16 lanes, three routes:
+        //   rows [0, top)   summed over the tile by the matrix core against a one-hot operand
+        //   rows [top, K)   added to the workgroup's LDS table (reads, then compare-and-swaps)
+        //   rows [K, I_n)   global float atomics
+        float grad[N][4];
+        unsigned int* cell[N][4];
+        unsigned int seen[N][4];
+        unsigned int pending = 0;
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            float* dAn = g.dA + g.A_off[n];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = cur.iY[n][v];
+                grad[n][v] = fmaf(g.lambda_A, cur.aY[n][v], gs[n][v]);
+                if (MASKED && !active(sub, v)) grad[n][v] = 0.0f;
+                cell[n][v] = reinterpret_cast<unsigned int*>(hot + (uint32_t)((g.hot_off[n] + row) * 16 + c));
+                if (row >= g.K[n]) {
+                    if (active(sub, v)) atomicAdd(dAn + (uint32_t)(row * 16 + c), grad[n][v]);
+                } else if (row >= g.top[n] && active(sub, v)) {
+                    seen[n][v] = *cell[n][v];
+                    pending |= 1u << (n * 4 + v);
+                }
+            }
+        }
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+            if (g.top[n] > 0) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float onehot = cur.iY[n][k] == c ? 1.0f : 0.0f;   // inactive samples carry grad = 0
+                    st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot, grad[n][k], st.Top[n], 0, 0, 0);
+                }
+            }
+        // one compare-and-swap per pending row element; lanes that lose a race go round again
+        while (pending) {
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (pending & (1u << (n * 4 + v))) {
+                        const unsigned int expect = seen[n][v];
+                        seen[n][v] = atomicCAS(cell[n][v], expect, __float_as_uint(__uint_as_float(expect) + grad[n][v]));
+                        if (seen[n][v] == expect) pending &= ~(1u << (n * 4 + v));
+                    }
+        }
+
+        // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+                st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(cur.aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
+    }
+}
+
+template <int N>
+__global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g) {
+    extern __shared__ float lds[];
+    constexpr int W4 = (N + 1 + 3) / 4;   // 16-byte words per record
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g4 = lane >> 4;
+    float* hot = lds;
+    float* wave_lds = lds + (size_t)g.H * 16 + wave * mfma16_wave_scratch(N);
+    int* sidx = reinterpret_cast<int*>(wave_lds);           // [N][64]
+    float* sval = wave_lds + N * 64;                         // [64]
+    float* tbuf = wave_lds + (N + 1) * 64;                   // [N][16][20]
+    float* gbred = lds + (size_t)g.H * 16 + kMfmaWaves * mfma16_wave_scratch(N);
+
+    for (int q = tid; q < g.H * 16; q += kMfmaThreads) hot[q] = 0.0f;
+    for (int q = tid; q < N * 256; q += kMfmaThreads) gbred[q] = 0.0f;
+
+    WaveState<N> st;
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+        const float* Bn = g.B + g.B_off[n];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            st.Bq[n][k] = Bn[(4 * g4 + k) * 16 + c];
+            st.Br[n][k] = Bn[c * 16 + 4 * g4 + k];
+        }
+        st.GBacc[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        st.Top[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+    __syncthreads();
+
+    const long long M = g.M;
+    const long long n_groups = (M + 63) / 64;
+    const long long group_stride = (long long)gridDim.x * kMfmaWaves;
+    const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
+
+    // record of sample (group * 64 + lane): N row numbers and the value's bits
+    auto load_record = [&](long long grp, uint4 (&rec)[W4]) {
+        const long long k = grp * 64 + lane;
+        const uint32_t p = k < M ? sample_position(g.seed, (uint64_t)k, g.nnz) : 0u;
+#pragma unroll
+        for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
 
     uint4 rec[W4];
@@ -161,8 +312,9 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
 
     for (; group < n_groups; group += group_stride) {
         // park the 64 records (struct of arrays) for this wave
+        const bool full = (group + 1) * 64 <= M;
         {
-            const bool act = group * 64 + lane < M;
+            const bool act = full || group * 64 + lane < M;
             uint32_t flat[4 * W4];
 #pragma unroll
             for (int q = 0; q < W4; ++q) {
@@ -176,100 +328,29 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
             sval[lane] = act ? __uint_as_float(flat[N]) : 0.0f;
         }
         lds_wave_sync();
-        if (group + group_stride < n_groups) load_record(group + group_stride, rec);
-
-        TileRows<N> cur, nxt;
-        gather(group, 0, nxt);
-#pragma unroll
-        for (int sub = 0; sub < 4; ++sub) {
-            cur = nxt;
-            if (sub < 3) gather(group, sub + 1, nxt);
-            const long long base = group * 64 + sub * 16;
-
-            // rows: layout Y -> LDS -> layout X, then projections s[n][v] = c^(n)_{r = 4g+v} of sample c
-            floatx4 s[N];
-#pragma unroll
-            for (int n = 0; n < N; ++n) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) tbuf[(4 * g4 + v) * 20 + c] = cur.aY[n][v];
-                lds_wave_sync();
-                const float4 ax = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
-                lds_wave_sync();
-                floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][0], ax.x, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][1], ax.y, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][2], ax.z, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][3], ax.w, acc, 0, 0, 0);
-                s[n] = acc;
-            }
-
-            // leave-one-out products (prefix sweep, then suffix sweep), prediction, error
-            floatx4 w[N];
-            floatx4 run = {1.0f, 1.0f, 1.0f, 1.0f};
-#pragma unroll
-            for (int n = 0; n < N; ++n) {
-                w[n] = run;
-                run *= s[n];
-            }
-            float xhat = (run[0] + run[1]) + (run[2] + run[3]);
-            xhat += __shfl_xor(xhat, 16);
-            xhat += __shfl_xor(xhat, 32);
-            const float e = cur.x - xhat;
-            run = floatx4{1.0f, 1.0f, 1.0f, 1.0f};
-#pragma unroll
-            for (int n = N - 1; n >= 0; --n) {
-                w[n] *= run;
-                run *= s[n];
-            }
-
-            // errors of samples 4g..4g+3 for layout Y
-            if (g4 == 0) ebuf[c] = e;
-            lds_wave_sync();
-            const float4 eY4 = *reinterpret_cast<const float4*>(ebuf + 4 * g4);
-            const float eY[4] = {eY4.x, eY4.y, eY4.z, eY4.w};
-
-#pragma unroll
-            for (int n = 0; n < N; ++n) {
-                // GS^(n) in layout Y:  gs[v] = GS_{j = c} of sample 4g+v
-                floatx4 gs = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) gs = __builtin_amdgcn_mfma_f32_16x16x4f32(w[n][k], Br[n][k], gs, 0, 0, 0);
-
-                // -e w: layout X -> LDS -> layout Y
-                const floatx4 wp = w[n] * (-e);
-                *reinterpret_cast<float4*>(tbuf + c * 20 + 4 * g4) = make_float4(wp[0], wp[1], wp[2], wp[3]);
-                lds_wave_sync();
-                float wY[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) wY[v] = tbuf[(4 * g4 + v) * 20 + c];
-                lds_wave_sync();
-
-                // factor-row gradient -e GS + lambda_A a, one 64-byte row per 16 lanes
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    if (base + 4 * g4 + v < M) {
-                        const float grad = fmaf(-eY[v], gs[v], g.lambda_A * cur.aY[n][v]);
-                        const int row = cur.iY[n][v];
-                        if (row < g.K[n])
-                            lds_float_add(hot + (size_t)(g.hot_off[n] + row) * 16 + c, grad);
-                        else
-                            atomicAdd(g.dA + g.A_off[n] + (long long)row * 16 + c, grad);
-                    }
-                }
-
-                // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(cur.aY[n][v], wY[v], GBacc[n], 0, 0, 0);
-            }
-        }
+        auto issue_next = [&]() {
+            if (group + group_stride < n_groups) load_record(group + group_stride, rec);
+        };
+        if (full)
+            process_group<N, false>(g, st, group, hot, sidx, sval, tbuf, c, g4, issue_next);
+        else
+            process_group<N, true>(g, st, group, hot, sidx, sval, tbuf, c, g4, issue_next);
     }
 
+    // rows 0..15 of each mode: from the wave's accumulators into the workgroup's LDS table
+    // (a mode whose table holds fewer than 16 rows never used its accumulator)
+#pragma unroll
+    for (int n = 0; n < N; ++n)
+        if (g.top[n] > 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                lds_float_add(hot + (size_t)(g.hot_off[n] + 4 * g4 + v) * 16 + c, st.Top[n][v]);
+        }
     // workgroup reduction of the core gradient, then one table of plain stores per workgroup
 #pragma unroll
     for (int n = 0; n < N; ++n)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) lds_float_add(gbred + n * 256 + (4 * g4 + v) * 16 + c, GBacc[n][v]);
+        for (int v = 0; v < 4; ++v) lds_float_add(gbred + n * 256 + (4 * g4 + v) * 16 + c, st.GBacc[n][v]);
     __syncthreads();
     float* gb_out = g.gb_partial + (size_t)blockIdx.x * (N * 256);
     for (int q = tid; q < N * 256; q += kMfmaThreads) gb_out[q] = gbred[q];
@@ -278,61 +359,89 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
 }
 
 // ---------------------------------------------------------------------------------------------
-// A <- A - lr_A dA.  Blocks [0, dense_blocks) scan the dense accumulator (rows updated with global
-// atomics); the remaining blocks sum the per-workgroup LDS tables of the frequently hit rows.
+// The update pass, one launch:
+//   blocks [0, dense_blocks)                 A <- A - lr_A dA over the dense accumulator (rows that
+//                                            were updated with global atomics), clearing it
+//   next hot_blocks blocks                   A <- A - lr_A sum_b hot_partial[b] for the rows kept in
+//                                            the workgroups' LDS tables (16 elements per block,
+//                                            16 threads striding over the partial tables of each)
+//   last B_blocks blocks                     B <- B - lr_B (sum_b GB[b] / M + lambda_B B)
 // ---------------------------------------------------------------------------------------------
-struct ApplyHotArgs {
-    const float* hot_partial;   // [parts][H][J]
-    int parts;
+struct ApplyArgs {
+    float* A;
+    float* dA;
+    long long n4;               // float4 elements of the packed A / dA allocation
+    int dense_blocks;
+    // frequently hit rows
+    const float* hot_partial;   // [hot_parts][H][J]
+    int hot_parts;
+    int hot_blocks;             // ceil(H * J / 16)
     int H;
     int J;
     int order;
     int K[kMaxOrder];
     int hot_off[kMaxOrder];
     long long A_off[kMaxOrder];
+    // core factors
+    float* B;
+    float* GB;                  // [gb_parts][B_total]
+    int B_total;
+    int gb_parts;
+    int gb_clear;               // zero GB[0] afterwards (single atomically accumulated table)
+    float lr_A, lr_B, lambda_B, inv_M;
 };
 
-__global__ void __launch_bounds__(256) apply_A_hot_kernel(float* __restrict__ A, float* __restrict__ dA, long long n4,
-                                                          float lr_A, int dense_blocks, ApplyHotArgs h) {
-    if ((int)blockIdx.x < dense_blocks) {
-        float4* A4 = reinterpret_cast<float4*>(A);
-        float4* D4 = reinterpret_cast<float4*>(dA);
-        for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < n4;
-             q += (long long)dense_blocks * blockDim.x) {
+__global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
+    __shared__ float red[16][17];
+    const int tid = threadIdx.x;
+    int blk = (int)blockIdx.x;
+    if (blk < p.dense_blocks) {
+        float4* A4 = reinterpret_cast<float4*>(p.A);
+        float4* D4 = reinterpret_cast<float4*>(p.dA);
+        for (long long q = (long long)blk * 256 + tid; q < p.n4; q += (long long)p.dense_blocks * 256) {
             const float4 d = D4[q];
             if (d.x != 0.0f || d.y != 0.0f || d.z != 0.0f || d.w != 0.0f) {
                 float4 a = A4[q];
-                a.x = fmaf(-lr_A, d.x, a.x);
-                a.y = fmaf(-lr_A, d.y, a.y);
-                a.z = fmaf(-lr_A, d.z, a.z);
-                a.w = fmaf(-lr_A, d.w, a.w);
+                a.x = fmaf(-p.lr_A, d.x, a.x);
+                a.y = fmaf(-p.lr_A, d.y, a.y);
+                a.z = fmaf(-p.lr_A, d.z, a.z);
+                a.w = fmaf(-p.lr_A, d.w, a.w);
                 A4[q] = a;
                 D4[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             }
         }
         return;
     }
-    const int q = ((int)blockIdx.x - dense_blocks) * blockDim.x + threadIdx.x;
-    const int table = h.H * h.J;
-    if (q >= table) return;
-    const int hrow = q / h.J, j = q - hrow * h.J;
-    int n = -1;
-    for (int m = 0; m < h.order; ++m)
-        if (hrow >= h.hot_off[m] && hrow < h.hot_off[m] + h.K[m]) n = m;
-    if (n < 0) return;
-    float d0 = 0.0f, d1 = 0.0f, d2 = 0.0f, d3 = 0.0f;
-    int b = 0;
-    for (; b + 4 <= h.parts; b += 4) {
-        d0 += h.hot_partial[(size_t)(b + 0) * table + q];
-        d1 += h.hot_partial[(size_t)(b + 1) * table + q];
-        d2 += h.hot_partial[(size_t)(b + 2) * table + q];
-        d3 += h.hot_partial[(size_t)(b + 3) * table + q];
-    }
-    for (; b < h.parts; ++b) d0 += h.hot_partial[(size_t)b * table + q];
-    const float d = (d0 + d1) + (d2 + d3);
-    if (d != 0.0f) {
-        float* a = A + h.A_off[n] + (long long)(hrow - h.hot_off[n]) * h.J + j;
-        *a = fmaf(-lr_A, d, *a);
+    blk -= p.dense_blocks;
+    const int ql = tid & 15, sub = tid >> 4;
+    const bool is_hot = blk < p.hot_blocks;
+    if (!is_hot) blk -= p.hot_blocks;
+    const int count = is_hot ? p.H * p.J : p.B_total;
+    const int parts = is_hot ? p.hot_parts : p.gb_parts;
+    const float* src = is_hot ? p.hot_partial : p.GB;
+    const int q = blk * 16 + ql;
+    float acc = 0.0f;
+    if (q < count)
+        for (int b = sub; b < parts; b += 16) acc += src[(size_t)b * count + q];
+    red[sub][ql] = acc;
+    __syncthreads();
+    if (tid >= 16 || q >= count) return;
+    float total = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) total += red[r][tid];
+    if (is_hot) {
+        const int hrow = q / p.J, j = q - hrow * p.J;
+        int n = -1;
+        for (int m = 0; m < p.order; ++m)
+            if (hrow >= p.hot_off[m] && hrow < p.hot_off[m] + p.K[m]) n = m;
+        if (n >= 0 && total != 0.0f) {
+            float* a = p.A + p.A_off[n] + (long long)(hrow - p.hot_off[n]) * p.J + j;
+            *a = fmaf(-p.lr_A, total, *a);
+        }
+    } else {
+        const float b0 = p.B[q];
+        p.B[q] = b0 - p.lr_B * fmaf(total, p.inv_M, p.lambda_B * b0);
+        if (p.gb_clear) p.GB[q] = 0.0f;
     }
 }
 

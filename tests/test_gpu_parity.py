@@ -274,9 +274,14 @@ def test_timing_slots_count_launches():
         for t in range(3):
             ft.ftk_sample(t, w.n_samples)
             ft.ftk_sgd_step(1e-3, 1e-3, 1e-2, 1e-2)
-        for slot in (binding.FTK_K_SAMPLE, binding.FTK_K_GRAD, binding.FTK_K_APPLY_A, binding.FTK_K_APPLY_B):
+        for slot in (binding.FTK_K_GRAD, binding.FTK_K_APPLY):
             ms, cnt = ft.ftk_get_timing(slot)
             assert cnt == 3 and ms > 0.0
+        # Psi is only materialised as arrays when something needs them
+        ms, cnt = ft.ftk_get_timing(binding.FTK_K_SAMPLE)
+        assert cnt == (3 if ft.ftk_kernel_name() == "generic" else 0)
+        ft.ftk_get_samples()
+        assert ft.ftk_get_timing(binding.FTK_K_SAMPLE)[1] == cnt + (0 if ft.ftk_kernel_name() == "generic" else 1)
         ft.ftk_set_timing(False)
 
 
