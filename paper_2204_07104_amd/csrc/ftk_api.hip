@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -73,7 +74,10 @@ struct ftk_ctx {
     bool mfma16_ok = false;
     int hot_K[kMaxOrder] = {};
     int hot_off[kMaxOrder] = {};
-    int hot_H = 0;
+    int hot_H = 0;            // rows in the LDS table for the current |Psi|
+    int hot_H_max = 0;        // rows the LDS budget allows (partial tables are sized for this)
+    long long hot_for_M = -1; // |Psi| the current choice was made for
+    std::vector<std::vector<unsigned int>> sorted_counts;   // per mode: occurrence counts, descending
     int mfma_grid = 0;
     size_t mfma_lds_bytes = 0;
     float* d_hot_partial = nullptr;   // [mfma_grid][hot_H][16]
@@ -218,6 +222,7 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A) {
         g.B_off[n] = c->L.B_off[n];
         g.K[n] = c->hot_K[n];
         g.top[n] = c->hot_K[n] >= 16 ? 16 : 0;
+        g.row_bytes[n] = (unsigned int)(c->dims[n] * 64);
         g.hot_off[n] = c->hot_off[n];
     }
     g.H = c->hot_H;
@@ -297,22 +302,24 @@ void release(ftk_ctx* c) {
     delete c;
 }
 
-// Choose which rows are accumulated in LDS: the H rows with the largest occurrence counts over
-// all modes (rows are already sorted by count within a mode, so this is a merge of sorted lists).
-void pick_hot_rows(ftk_ctx* c, const std::vector<std::vector<unsigned int>>& sorted_counts) {
+// Choose which rows are accumulated in LDS for a sample set of n_samples entries: rows expected to
+// be hit at least twice per workgroup per step (below that a private copy saves no atomics and
+// only costs table traffic), most frequent first, as many as the LDS budget allows.  Rows are
+// already sorted by count within a mode, so this is a merge of sorted lists.
+void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     const int N = c->order;
-    const long long budget = (long long)c->max_lds - 4LL * (kMfmaWaves * mfma16_wave_scratch(N) + N * 256) - 1024;
-    int H = (int)std::max(0LL, budget / 64);
     long long rows_total = 0;
     for (int n = 0; n < N; ++n) rows_total += c->dims[n];
-    if (H > rows_total) H = (int)rows_total;
+    const int H = (int)std::min<long long>(c->hot_H_max, rows_total);
+    double min_count = 2.0 * (double)c->mfma_grid * (double)c->nnz / (double)std::max<long long>(n_samples, 1);
+    if (const char* e = getenv("FTK_HOT_PMIN")) min_count = atof(e) * (double)c->nnz;   // tuning override
     int taken[kMaxOrder] = {};
     for (int t = 0; t < H; ++t) {
         int best = -1;
         unsigned int best_count = 0;
         for (int n = 0; n < N; ++n)
-            if (taken[n] < c->dims[n]) {
-                const unsigned int cnt = sorted_counts[n][taken[n]];
+            if (taken[n] < c->dims[n] && (double)c->sorted_counts[n][taken[n]] >= min_count) {
+                const unsigned int cnt = c->sorted_counts[n][taken[n]];
                 if (best < 0 || cnt > best_count) {
                     best = n;
                     best_count = cnt;
@@ -329,6 +336,7 @@ void pick_hot_rows(ftk_ctx* c, const std::vector<std::vector<unsigned int>>& sor
     }
     c->hot_H = std::max(off, 1);
     c->mfma_lds_bytes = 4 * ((size_t)c->hot_H * 16 + kMfmaWaves * mfma16_wave_scratch(N) + N * 256);
+    c->hot_for_M = n_samples;
 }
 
 int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, const float* vals, uint64_t init_seed,
@@ -348,7 +356,7 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     for (int n = 0; n < N; ++n) {
         c->L.A_off[n] = a_off;
         c->L.B_off[n] = b_off;
-        a_off += ((dims[n] * c->L.J[n] + 63) / 64) * 64;
+        a_off += ((dims[n] * c->L.J[n] + 16 + 63) / 64) * 64;   // >= 16 floats of slack after every mode
         b_off += c->L.J[n] * c->L.R;
         stage = std::max(stage, (long long)dims[n] * c->L.J[n]);
     }
@@ -357,7 +365,7 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     pick_generic_config(c);
     c->mfma16_ok = c->L.R == 16 && N <= 6 && c->max_lds >= 131072;
     for (int n = 0; n < N; ++n)   // 16-float rows, addressed with 32-bit element offsets inside a mode
-        c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16 && dims[n] < (1LL << 26);
+        c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16 && dims[n] < (1LL << 25);
     if (c->gen_threads == 0 && !c->mfma16_ok)
         return fail(c, FTK_EUNSUPPORTED, "N*R = %d with sum J_n R = %d exceeds the kernels' LDS budget", N * c->L.R,
                     c->L.B_total);
@@ -380,7 +388,8 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
         }
     } guard{d_col, d_counts};
     FTK_HIP(c, hipMalloc(&d_col, (size_t)c->nnz * sizeof(uint32_t)));
-    std::vector<std::vector<unsigned int>> sorted_counts(N);
+    std::vector<std::vector<unsigned int>>& sorted_counts = c->sorted_counts;
+    sorted_counts.assign(N, {});
     for (int n = 0; n < N; ++n) {
         FTK_HIP(c, hipMemcpy(d_col, idx[n], (size_t)c->nnz * sizeof(int32_t), kind));
         FTK_HIP(c, hipMemset(c->d_flag, 0, sizeof(unsigned int)));
@@ -450,9 +459,11 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
 
     // ---- kernel variant ----
     if (c->mfma16_ok) {
-        pick_hot_rows(c, sorted_counts);
         c->mfma_grid = c->num_cu;
-        FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid * c->hot_H * 16 * sizeof(float)));
+        const long long budget = (long long)c->max_lds - 4LL * (kMfmaWaves * mfma16_wave_scratch(N) + N * 256) - 1024;
+        c->hot_H_max = (int)std::max(1LL, budget / 64);
+        pick_hot_rows(c, 1LL << 20);
+        FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid * c->hot_H_max * 16 * sizeof(float)));
         FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid * c->L.B_total * sizeof(float)));
         c->variant = V_MFMA16;
     } else {
@@ -517,6 +528,7 @@ int ftk_sample(ftk_ctx* c, uint64_t seed, int64_t n_samples) {
     c->sample_seed = seed;
     c->n_samples = n_samples;
     c->batch_valid = false;
+    if (c->mfma16_ok && c->hot_for_M != n_samples) pick_hot_rows(c, n_samples);
     return FTK_OK;
 }
 

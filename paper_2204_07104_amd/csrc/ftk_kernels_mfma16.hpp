@@ -65,6 +65,7 @@ struct Mfma16Args {
     int H;                    // rows in the LDS table (>= sum K[n])
     float* hot_partial;       // [gridDim.x][H][16]
     float* gb_partial;        // [gridDim.x][N * 256]
+    unsigned int row_bytes[kMaxOrder];   // I_n * 64: size of mode n's rows in A and dA
     float lambda_A;
 };
 
@@ -104,12 +105,24 @@ struct WaveState {
 // One group of 64 samples whose records are parked in this wave's LDS buffer: four tiles of 16.
 // MASKED: the group reaches past the end of Psi (only the last group can); samples past the end
 // were parked as row 0 / value 0 and every contribution of theirs is forced to zero.
+// Buffer resource over `bytes` bytes at p (raw buffer, 32-bit data).  Accesses at offsets past
+// `bytes` are dropped by the hardware: loads return 0 and atomics do nothing.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned int bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+
 template <int N, bool MASKED, class IssueNext>
 __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, long long group, float* hot,
                                               const int* sidx, const float* sval, float* tbuf, int c, int g4,
                                               IssueNext&& issue_next_records) {
     const long long M = g.M;
     auto active = [&](int sub, int v) -> bool { return !MASKED || group * 64 + sub * 16 + 4 * g4 + v < M; };
+    __amdgpu_buffer_rsrc_t rsrc_A[N], rsrc_dA[N];
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+        rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
+        rsrc_dA[n] = make_rsrc(g.dA + g.A_off[n], g.row_bytes[n]);
+    }
 
     // rows of tile `sub` gathered in layout Y (four full 64-byte rows per load instruction)
     auto gather = [&](int sub, TileRows<N>& t) {
@@ -121,10 +134,9 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
             t.iY[n][1] = r.y;
             t.iY[n][2] = r.z;
             t.iY[n][3] = r.w;
-            const float* An = g.A + g.A_off[n];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float a = An[(uint32_t)(t.iY[n][v] * 16 + c)];
+                const float a = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_A[n], (t.iY[n][v] * 16 + c) * 4, 0, 0));
                 t.aY[n][v] = active(sub, v) ? a : 0.0f;
             }
         }
@@ -217,15 +229,20 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
         unsigned int pending = 0;
 #pragma unroll
         for (int n = 0; n < N; ++n) {
-            float* dAn = g.dA + g.A_off[n];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int row = cur.iY[n][v];
                 grad[n][v] = fmaf(g.lambda_A, cur.aY[n][v], gs[n][v]);
                 if (MASKED && !active(sub, v)) grad[n][v] = 0.0f;
                 cell[n][v] = reinterpret_cast<unsigned int*>(hot + (uint32_t)((g.hot_off[n] + row) * 16 + c));
+                // Every lane issues the atomic; lanes whose row lives in LDS (or is past the end of
+                // Psi) aim past the end of the buffer, where the hardware drops the request.  An
+                // unconditional instruction lets the compiler count outstanding memory operations
+                // exactly, so waiting for the prefetched rows never waits for these atomics.
+                const bool cold = row >= g.K[n] && active(sub, v);
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[n][v], rsrc_dA[n],
+                                                                cold ? (row * 16 + c) * 4 : (int)g.row_bytes[n] + c * 4, 0, 0);
                 if (row >= g.K[n]) {
-                    if (active(sub, v)) atomicAdd(dAn + (uint32_t)(row * 16 + c), grad[n][v]);
                 } else if (row >= g.top[n] && active(sub, v)) {
                     seen[n][v] = *cell[n][v];
                     pending |= 1u << (n * 4 + v);
