@@ -27,6 +27,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
+# what the same counters read for kernels of known size (profiles/grad_mfma16_C2.txt, section 2)
+MEASURED_TRAFFIC_BYTES = {("C2", "grad:mfma16"): 172.4e6 + 121.8e6}
 FP32_VALU_PEAK_TFLOPS = 157.3    # MI355X fp32 vector, published
 KERNEL_SLOTS = ["sample_gather", "grad", "apply"]
 
@@ -49,6 +52,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--kernel", default="auto")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the CPU-oracle leg (0: skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported."
@@ -109,7 +114,7 @@ def main() -> int:
     roofline = {
         "bound": "hbm", "kernel": dominant + ":" + ft.ftk_kernel_name(),
         "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant + ":" + ft.ftk_kernel_name())),
         "bytes_per_sample": algorithmic_bytes_per_sample(w), "avg_kernel_ms": dom_ms,
         "whole_step_gbs": bytes_per_launch / (ms_per_step * 1e-3) / 1e9,
         "whole_step_frac": bytes_per_launch / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -117,6 +122,13 @@ def main() -> int:
         "per_kernel_ms": {k: v["avg_ms"] for k, v in per_kernel.items()},
     }
     ft.close()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 26, dtype=torch.float32, device="cuda")     # 256 MiB read, 256 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu_baseline = None
     if args.cpu_seconds > 0:
