@@ -275,14 +275,33 @@ int ensure_batch(ftk_ctx* c) {
     return FTK_OK;
 }
 
+template <int N>
+void launch_errors_mfma16_n(ftk_ctx* c, const Coo& coo) {
+    const long long groups = (c->nnz + 63) / 64;
+    const int grid = blocks_for(groups, 4, c->num_cu * 8);
+    hipLaunchKernelGGL(errors_mfma16_kernel<N>, dim3(grid), dim3(256), 0, c->stream, coo, (uint64_t)c->nnz,
+                       (const float*)c->d_A, (const float*)c->d_B, c->L, c->d_sums);
+}
+
 int launch_errors(ftk_ctx* c, double* host_sums) {
     Coo coo{c->d_rec, c->rec_words};
     FTK_HIP(c, hipMemsetAsync(c->d_sums, 0, 2 * sizeof(double), c->stream));
-    const int b_in_lds = (size_t)c->L.B_total * 4 <= 65536 - 256;
-    const size_t lds = b_in_lds ? (size_t)c->L.B_total * 4 : 0;
-    const int grid = blocks_for(c->nnz, 256, c->num_cu * 8);
-    hipLaunchKernelGGL(errors_generic_kernel, dim3(grid), dim3(256), lds, c->stream, coo, c->L, (uint64_t)c->nnz,
-                       (const float*)c->d_A, (const float*)c->d_B, b_in_lds, c->d_sums);
+    if (c->variant == V_MFMA16 && c->rec_words == 4 * ((c->order + 1 + 3) / 4)) {
+        switch (c->order) {
+            case 1: launch_errors_mfma16_n<1>(c, coo); break;
+            case 2: launch_errors_mfma16_n<2>(c, coo); break;
+            case 3: launch_errors_mfma16_n<3>(c, coo); break;
+            case 4: launch_errors_mfma16_n<4>(c, coo); break;
+            case 5: launch_errors_mfma16_n<5>(c, coo); break;
+            default: launch_errors_mfma16_n<6>(c, coo); break;
+        }
+    } else {
+        const int b_in_lds = (size_t)c->L.B_total * 4 <= 65536 - 256;
+        const size_t lds = b_in_lds ? (size_t)c->L.B_total * 4 : 0;
+        const int grid = blocks_for(c->nnz, 256, c->num_cu * 8);
+        hipLaunchKernelGGL(errors_generic_kernel, dim3(grid), dim3(256), lds, c->stream, coo, c->L, (uint64_t)c->nnz,
+                           (const float*)c->d_A, (const float*)c->d_B, b_in_lds, c->d_sums);
+    }
     FTK_HIP(c, hipGetLastError());
     FTK_HIP(c, hipMemcpyAsync(host_sums, c->d_sums, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
     FTK_HIP(c, hipStreamSynchronize(c->stream));

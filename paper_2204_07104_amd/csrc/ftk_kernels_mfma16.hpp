@@ -376,6 +376,95 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Evaluation pass over ALL stored entries (RMSE / MAE, Section 5.1) for J_n = R = 16: a streaming
+// version of the forward half of the gradient kernel.  A wave reads 64 consecutive records
+// (coalesced), gathers their rows 16 lanes per row, transposes through LDS and runs the
+// projections on the matrix core; squared and absolute errors are summed in double.
+// ---------------------------------------------------------------------------------------------
+template <int N>
+__global__ void __launch_bounds__(256) errors_mfma16_kernel(Coo coo, uint64_t nnz, const float* __restrict__ A,
+                                                            const float* __restrict__ B, Layout L,
+                                                            double* __restrict__ sums /* [2]: sse, sae */) {
+    constexpr int W4 = (N + 1 + 3) / 4;
+    __shared__ int sidx_all[4][N][64];
+    __shared__ float tbuf_all[4][kTransposeFloats];
+    __shared__ double red[2][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g4 = lane >> 4;
+    int (*sidx)[64] = sidx_all[wave];
+    float* tbuf = tbuf_all[wave];
+    float Bq[N][4];
+#pragma unroll
+    for (int n = 0; n < N; ++n)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) Bq[n][k] = B[L.B_off[n] + (4 * g4 + k) * 16 + c];
+
+    const uint4* rec4 = reinterpret_cast<const uint4*>(coo.rec);
+    const uint64_t n_groups = (nnz + 63) / 64;
+    double sse = 0.0, sae = 0.0;
+    for (uint64_t group = (uint64_t)blockIdx.x * 4 + wave; group < n_groups; group += (uint64_t)gridDim.x * 4) {
+        const uint64_t p = group * 64 + lane;
+        const bool act = p < nnz;
+        uint32_t flat[4 * W4];
+#pragma unroll
+        for (int q = 0; q < W4; ++q) {
+            const uint4 r = rec4[(act ? p : 0) * W4 + q];
+            flat[4 * q + 0] = r.x;
+            flat[4 * q + 1] = r.y;
+            flat[4 * q + 2] = r.z;
+            flat[4 * q + 3] = r.w;
+        }
+#pragma unroll
+        for (int n = 0; n < N; ++n) sidx[n][lane] = act ? (int)flat[n] : 0;
+        const float xval = act ? __uint_as_float(flat[N]) : 0.0f;
+        lds_wave_sync();
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) {
+            floatx4 prod = {1.0f, 1.0f, 1.0f, 1.0f};
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const int4 r = *reinterpret_cast<const int4*>(&sidx[n][sub * 16 + 4 * g4]);
+                const int rows[4] = {r.x, r.y, r.z, r.w};
+                const float* An = A + L.A_off[n];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) tbuf[(4 * g4 + v) * 20 + c] = An[(uint32_t)(rows[v] * 16 + c)];
+                lds_wave_sync();
+                const float4 ax = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
+                lds_wave_sync();
+                floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][0], ax.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][1], ax.y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][2], ax.z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][3], ax.w, acc, 0, 0, 0);
+                prod *= acc;
+            }
+            // xhat of sample (sub * 16 + c): sum over the 16 r held by lanes (c, 0..3) x 4 registers
+            float xhat = (prod[0] + prod[1]) + (prod[2] + prod[3]);
+            xhat += __shfl_xor(xhat, 16);
+            xhat += __shfl_xor(xhat, 32);
+            // the value of sample sub * 16 + c sits in lane sub * 16 + c
+            const float x = __shfl(xval, sub * 16 + c);
+            if (g4 == 0 && group * 64 + sub * 16 + c < nnz) {
+                const double e = (double)x - (double)xhat;
+                sse += e * e;
+                sae += fabs(e);
+            }
+        }
+    }
+    sse = wave_sum(sse);
+    sae = wave_sum(sae);
+    if (lane == 0) {
+        red[0][wave] = sse;
+        red[1][wave] = sae;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        atomicAdd(sums + 0, (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]));
+        atomicAdd(sums + 1, (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // The update pass, one launch:
 //   blocks [0, dense_blocks)                 A <- A - lr_A dA over the dense accumulator (rows that
 //                                            were updated with global atomics), clearing it

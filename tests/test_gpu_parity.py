@@ -113,6 +113,35 @@ def test_c1_one_step_and_ten_step_rmse():
         assert ft.ftk_mae() == pytest.approx(oracle.errors(w.dims, idx, vals, A, B)[1], rel=1e-3)
 
 
+def test_ten_steps_rmse_scaled_c2_both_kernels():
+    """10 synchronous steps on the C2 recipe at reduced size (J = R = 16: the matrix-core kernels),
+    RMSE after every step within 1e-3 relative of the oracle's, for the specialised and the generic
+    gradient kernel."""
+    w = synth.WORKLOADS["C2"].scaled(nnz=300_000, n_samples=30_000, dims=(4_800, 1_777, 220))
+    w = synth.replace(w, lr_A=2e-7, lr_B=1e-4)
+    idx, vals = synth.make_tensor(w)
+    for kernel in ("auto", "generic"):
+        announce("10 steps scaled C2, kernel=%s" % kernel)
+        A, B = oracle_state(w)
+        with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
+            ft.ftk_set_kernel(kernel)
+            assert ft.ftk_kernel_name() == ("mfma16" if kernel == "auto" else "generic")
+            first = None
+            for t in range(10):
+                ft.ftk_sample(w.sample_seed0 + t, w.n_samples)
+                ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+                pos = oracle.sample_positions(w.sample_seed0 + t, w.n_samples, w.nnz)
+                oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+                got, want = ft.ftk_rmse(), oracle.rmse(w.dims, idx, vals, A, B)
+                assert got == pytest.approx(want, rel=1e-3), "step %d" % t
+                first = got if first is None else first
+            assert got < first          # it learns
+            gA, gB = ft.ftk_get_factors()
+        # after 10 steps the parameters themselves are still close (errors do not blow up)
+        for g, o in zip(gA + gB, A + B):
+            assert float(np.abs(g.astype(np.float64) - o).max()) <= 1e-3 * (1.0 + float(np.abs(o).max()))
+
+
 TINY = [
     # order, dims, nnz, J, R, M
     (1, (50,), 200, (4,), 3, 100),
@@ -201,7 +230,8 @@ def test_repeating_a_step_reuses_psi_and_accumulators_are_clean():
 
 def test_rmse_and_mae_match_oracle():
     announce("rmse / mae")
-    for order, dims, J, R in [(3, (100, 90, 80), (8, 8, 8), 8), (2, (50, 60), (3, 7), 5), (6, (20,) * 6, (8,) * 6, 16)]:
+    for order, dims, J, R in [(3, (100, 90, 80), (8, 8, 8), 8), (2, (50, 60), (3, 7), 5), (6, (20,) * 6, (8,) * 6, 16),
+                              (3, (300, 200, 100), (16, 16, 16), 16), (1, (500,), (16,), 16), (4, (30, 20, 10, 40), (16,) * 4, 16)]:
         w = synth.tiny_workload(order, dims, 20_011, J, R, 10, seed=21)
         idx, vals = synth.make_tensor(w)
         A, B = oracle.init_factors(4, w.dims, w.J, w.R)
