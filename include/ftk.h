@@ -69,7 +69,7 @@ enum {
 /* ftk_set_mode */
 enum {
     FTK_SYNC = 0,          /* all gradients at the step's starting parameters, then one update */
-    FTK_HOGWILD = 1        /* Algorithm 1 as printed: factor rows updated in place, sample by sample */
+    FTK_HOGWILD = 1        /* in-place factor rows (Algorithm 1's order, run concurrently): see ftk_sgd_step */
 };
 
 #define FTK_MAX_ORDER 8
@@ -114,8 +114,15 @@ int ftk_get_samples(ftk_ctx* ctx, int64_t* pos_out);
 /*
  * One SGD step over the current Psi (formulas at the top of this file).  FTK_ESTATE if no Psi.
  * In FTK_SYNC mode the result is independent of the order in which samples are processed up to
- * fp32 summation order.  In FTK_HOGWILD mode factor rows are read and written in place while
- * other samples are in flight (Algorithm 1 lines 1-16 as printed); results are not reproducible.
+ * fp32 summation order.
+ * In FTK_HOGWILD mode there is no accumulator and no separate factor update: every sample adds
+ * -lr_A (-e GS^(n) + lambda_A a^(n)) straight into A^(n) while other samples are reading it, as
+ * Algorithm 1 lines 1-16 do (M = 1).  Deviations from the printed order, both forced by running
+ * samples concurrently: the N gradients of one sample all use the rows as gathered (mode n does
+ * not see the row mode n-1 of the same sample just wrote), and the most frequently hit rows are
+ * accumulated per workgroup and added at the end of the step.  The core factors are updated once
+ * per step from the accumulated gradient, M = |Psi| (Section 4.2).  Results depend on scheduling;
+ * this mode is meant to be judged by its RMSE curve.
  */
 int ftk_sgd_step(ftk_ctx* ctx, float lr_A, float lr_B, float lambda_A, float lambda_B);
 

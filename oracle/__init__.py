@@ -59,6 +59,8 @@ def lib():
                                         C.c_void_p, C.c_int32, _pp_f, _pp_f, C.c_void_p,
                                         C.c_int64, C.c_float, C.c_float, C.c_float, C.c_float]
         L.fto_sgd_step_sync.restype = C.c_int
+        L.fto_sgd_step_hogwild.argtypes = L.fto_sgd_step_sync.argtypes
+        L.fto_sgd_step_hogwild.restype = C.c_int
         L.fto_errors.argtypes = [C.c_int32, C.c_void_p, C.c_int64, _pp_i, C.c_void_p, C.c_void_p,
                                  C.c_int32, _pp_f, _pp_f, C.c_void_p, C.c_int64, C.c_void_p,
                                  C.c_void_p]
@@ -159,6 +161,19 @@ def sgd_step_sync(dims, idx, vals, A, B, pos, lr_A, lr_B, lambda_A, lambda_B) ->
                                  lr_A, lr_B, lambda_A, lambda_B)
     if rc:
         raise ValueError("fto_sgd_step_sync failed: %d" % rc)
+
+
+def sgd_step_hogwild(dims, idx, vals, A, B, pos, lr_A, lr_B, lambda_A, lambda_B) -> None:
+    """One step in the order Algorithm 1 prints (rows overwritten sample by sample, mode by mode;
+    core factors from the accumulated gradient afterwards), run sequentially.  In place."""
+    N, dims_a, nnz, J, R, A, B = _tensor_args(dims, idx, vals, A, B)
+    pos = np.ascontiguousarray(pos, dtype=np.int64)
+    rc = lib().fto_sgd_step_hogwild(N, dims_a.ctypes.data, nnz, _ptr_array(idx, C.c_int32),
+                                    vals.ctypes.data, J.ctypes.data, R, _ptr_array(A, C.c_float),
+                                    _ptr_array(B, C.c_float), pos.ctypes.data, int(pos.shape[0]),
+                                    lr_A, lr_B, lambda_A, lambda_B)
+    if rc:
+        raise ValueError("fto_sgd_step_hogwild failed: %d" % rc)
 
 
 def errors(dims, idx, vals, A, B, positions: Optional[np.ndarray] = None) -> Tuple[float, float]:

@@ -28,7 +28,9 @@
 //  * lambda_A a is added once per processed sample (Algorithm 1, line 12),
 //    lambda_B B once per step;
 //  * synchronous (Jacobi) mode: every gradient is evaluated at the parameters
-//    the step started with, then all parameters are updated at once;
+//    the step started with, then all parameters are updated at once; the order
+//    Algorithm 1 prints (rows overwritten sample by sample, mode by mode) is a
+//    second entry point, fto_sgd_step_hogwild;
 //  * Psi: i.i.d. uniform positions with replacement from Philox4x32-10.
 //
 // Pins (see tests/test_oracle_*.py): Philox known-answer vectors of Salmon et
@@ -246,6 +248,60 @@ int fto_sgd_step_sync(int32_t order, const int64_t* dims, int64_t nnz, const int
             B[n][q] = (float)((double)B[n][q] -
                               (double)lr_B * (GB[n][q] / (double)n_samples + (double)lambda_B * (double)B[n][q]));
     }
+    return 0;
+}
+
+// One step of Algorithm 1 in the order it is printed (the "Hogwild" mode of the library, here
+// run sequentially so it is deterministic):
+//   factor phase (lines 1-16), sample by sample in the order of Psi, and inside a sample mode by
+//   mode: c of the OTHER modes from the CURRENT rows (so mode n already sees the rows that modes
+//   < n of the same sample, and all earlier samples, have just written), GS^(n), the three parts,
+//   and the row is overwritten at once with M = 1:  a <- a - lr_A (-e GS + lambda_A a);
+//   core phase (lines 17-39) over the same samples with the updated factor matrices: the
+//   gradients of all b^(n)_{:,r} are accumulated and B is updated once with M = |Psi|
+//   (Section 4.2: the b vectors depend on each other and are updated simultaneously).
+// Every row write is rounded to fp32, as the library stores fp32.
+int fto_sgd_step_hogwild(int32_t order, const int64_t* dims, int64_t nnz, const int32_t* const* idx,
+                         const float* vals, const int32_t* J, int32_t R, float* const* A,
+                         float* const* B, const int64_t* pos, int64_t n_samples, float lr_A,
+                         float lr_B, float lambda_A, float lambda_B) {
+    if (bad_shape(order, J, R) || !dims || !idx || !vals || !A || !B || nnz < 1) return -1;
+    if (n_samples < 1 || !pos) return -1;
+    const int N = order;
+    std::vector<const float*> a(N);
+    Terms t;
+    for (int64_t k = 0; k < n_samples; ++k) {
+        const int64_t p = pos[k];
+        if (p < 0 || p >= nnz) return -2;
+        for (int n = 0; n < N; ++n) {
+            if (idx[n][p] < 0 || idx[n][p] >= dims[n]) return -3;
+            a[n] = A[n] + (size_t)idx[n][p] * J[n];
+        }
+        for (int n = 0; n < N; ++n) {
+            nonzero_terms(N, J, R, a.data(), B, t);   // everything from the current rows
+            const double e = (double)vals[p] - t.xhat;
+            float* row = A[n] + (size_t)idx[n][p] * J[n];
+            for (int j = 0; j < J[n]; ++j)
+                row[j] = (float)((double)row[j] -
+                                 (double)lr_A * (-e * t.gs[n][j] + (double)lambda_A * (double)row[j]));
+        }
+    }
+    std::vector<std::vector<double>> GB(N);
+    for (int n = 0; n < N; ++n) GB[n].assign((size_t)J[n] * R, 0.0);
+    for (int64_t k = 0; k < n_samples; ++k) {
+        const int64_t p = pos[k];
+        for (int n = 0; n < N; ++n) a[n] = A[n] + (size_t)idx[n][p] * J[n];
+        nonzero_terms(N, J, R, a.data(), B, t);
+        const double e = (double)vals[p] - t.xhat;
+        for (int n = 0; n < N; ++n)
+            for (int j = 0; j < J[n]; ++j)
+                for (int r = 0; r < R; ++r)
+                    GB[n][(size_t)j * R + r] += -e * (double)a[n][j] * t.w[n][r];
+    }
+    for (int n = 0; n < N; ++n)
+        for (size_t q = 0; q < (size_t)J[n] * R; ++q)
+            B[n][q] = (float)((double)B[n][q] -
+                              (double)lr_B * (GB[n][q] / (double)n_samples + (double)lambda_B * (double)B[n][q]));
     return 0;
 }
 

@@ -174,15 +174,17 @@ void pick_generic_config(ftk_ctx* c) {
         }
 }
 
-int launch_grad_generic(ftk_ctx* c, float lambda_A) {
+int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A) {
+    const bool in_place = c->mode == FTK_HOGWILD;
     GradArgs g;
     g.L = c->L;
     g.batch = Batch{c->d_bidx, c->d_bval, c->n_samples, c->cap};
     g.A = c->d_A;
     g.B = c->d_B;
-    g.dA = c->d_dA;
+    g.dA = in_place ? c->d_A : c->d_dA;
     g.GB = c->d_GB;
     g.lambda_A = lambda_A;
+    g.scale = in_place ? -lr_A : 1.0f;
     g.b_in_lds = c->gen_b_in_lds;
     if (c->gen_threads == 0)
         return fail(c, FTK_EUNSUPPORTED, "generic gradient kernel: N*R = %d and sum J_n R = %d exceed the LDS budget",
@@ -208,7 +210,8 @@ int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
     return FTK_OK;
 }
 
-int launch_grad_mfma16(ftk_ctx* c, float lambda_A) {
+int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
+    const bool in_place = c->mode == FTK_HOGWILD;
     Mfma16Args g;
     g.coo = Coo{c->d_rec, c->rec_words};
     g.nnz = (uint64_t)c->nnz;
@@ -216,7 +219,8 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A) {
     g.M = c->n_samples;
     g.A = c->d_A;
     g.B = c->d_B;
-    g.dA = c->d_dA;
+    g.dA = in_place ? c->d_A : c->d_dA;
+    g.scale = in_place ? -lr_A : 1.0f;
     for (int n = 0; n < kMaxOrder; ++n) {
         g.A_off[n] = c->L.A_off[n];
         g.B_off[n] = c->L.B_off[n];
@@ -573,18 +577,20 @@ int ftk_get_samples(ftk_ctx* c, int64_t* pos_out) {
 int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
     if (!c) return FTK_EINVAL;
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step before ftk_sample");
-    if (c->mode != FTK_SYNC) return fail(c, FTK_EUNSUPPORTED, "only FTK_SYNC is built");
     const bool mfma = c->variant == V_MFMA16;
+    const bool in_place = c->mode == FTK_HOGWILD;
     int rc = mfma ? FTK_OK : ensure_batch(c);
     if (rc != FTK_OK) return rc;
-    rc = mfma ? launch_grad_mfma16(c, lambda_A) : launch_grad_generic(c, lambda_A);
+    rc = mfma ? launch_grad_mfma16(c, lambda_A, lr_A) : launch_grad_generic(c, lambda_A, lr_A);
     if (rc != FTK_OK) return rc;
     {
         ApplyArgs p = {};
         p.A = c->d_A;
         p.dA = c->d_dA;
         p.n4 = c->A_total / 4;
-        p.dense_blocks = blocks_for(p.n4, 256, c->num_cu * 16);
+        // in-place mode: the gradient pass already added -lr_A * gradient to A (and to the workgroup
+        // tables), so there is no accumulator to scan and the tables are added as they are
+        p.dense_blocks = in_place ? 0 : blocks_for(p.n4, 256, c->num_cu * 16);
         if (mfma) {
             p.hot_partial = c->d_hot_partial;
             p.hot_parts = c->mfma_grid;
@@ -603,7 +609,7 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
         p.B_total = c->L.B_total;
         p.gb_parts = mfma ? c->mfma_grid : 1;
         p.gb_clear = mfma ? 0 : 1;
-        p.lr_A = lr_A;
+        p.lr_A = in_place ? -1.0f : lr_A;
         p.lr_B = lr_B;
         p.lambda_B = lambda_B;
         p.inv_M = 1.0f / (float)c->n_samples;
@@ -678,7 +684,6 @@ int ftk_set_factors(ftk_ctx* c, const float* const* A_in, const float* const* B_
 int ftk_set_mode(ftk_ctx* c, int mode) {
     if (!c) return FTK_EINVAL;
     if (mode != FTK_SYNC && mode != FTK_HOGWILD) return fail(c, FTK_EINVAL, "unknown mode %d", mode);
-    if (mode == FTK_HOGWILD) return fail(c, FTK_EUNSUPPORTED, "FTK_HOGWILD is not built");
     c->mode = mode;
     return FTK_OK;
 }

@@ -88,9 +88,10 @@ struct GradArgs {
     Batch batch;
     const float* A;
     const float* B;
-    float* dA;
+    float* dA;         // where factor-row gradients are added: the accumulator (synchronous mode) or A itself
     float* GB;
     float lambda_A;
+    float scale;       // 1 (synchronous: the update pass applies -lr_A) or -lr_A (in-place mode)
     int b_in_lds;
 };
 
@@ -150,7 +151,7 @@ __global__ void grad_generic_kernel(GradArgs g) {
                 for (int j = 0; j < Jn; ++j) {
                     float gs = 0.0f;
                     for (int r = 0; r < R; ++r) gs = fmaf(Bn[j * R + r], w_l[(size_t)(n * R + r) * T + tid], gs);
-                    atomicAdd(g.dA + roff + j, fmaf(-e, gs, g.lambda_A * g.A[roff + j]));
+                    atomicAdd(g.dA + roff + j, g.scale * fmaf(-e, gs, g.lambda_A * g.A[roff + j]));
                 }
             }
         }

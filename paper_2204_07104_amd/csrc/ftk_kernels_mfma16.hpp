@@ -56,7 +56,7 @@ struct Mfma16Args {
     long long M;              // |Psi|
     const float* A;
     const float* B;
-    float* dA;
+    float* dA;                // where rows [K, I_n) are added: the accumulator (synchronous mode) or A itself
     long long A_off[kMaxOrder];
     int B_off[kMaxOrder];
     int K[kMaxOrder];         // rows [0, K[n]) of mode n live in the LDS table
@@ -67,6 +67,7 @@ struct Mfma16Args {
     float* gb_partial;        // [gridDim.x][N * 256]
     unsigned int row_bytes[kMaxOrder];   // I_n * 64: size of mode n's rows in A and dA
     float lambda_A;
+    float scale;              // 1 (synchronous: the update pass applies -lr_A) or -lr_A (in-place mode)
 };
 
 __device__ __forceinline__ void lds_wave_sync() {
@@ -232,7 +233,7 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int row = cur.iY[n][v];
-                grad[n][v] = fmaf(g.lambda_A, cur.aY[n][v], gs[n][v]);
+                grad[n][v] = g.scale * fmaf(g.lambda_A, cur.aY[n][v], gs[n][v]);
                 if (MASKED && !active(sub, v)) grad[n][v] = 0.0f;
                 cell[n][v] = reinterpret_cast<unsigned int*>(hot + (uint32_t)((g.hot_off[n] + row) * 16 + c));
                 // Every lane issues the atomic; lanes whose row lives in LDS (or is past the end of

@@ -306,6 +306,79 @@ def test_euler_homogeneity_of_core_gradient():
 
 
 # ----------------------------------------------------------------------------
+# the order Algorithm 1 prints (rows overwritten in place): replayed here with the dense model
+# ----------------------------------------------------------------------------
+def replay_in_place_step(dims, idx, vals, A, B, pos, lr_A, lr_B, lam_A, lam_B, h=1e-6):
+    """Sequential replay written from the definition: for every sample and every mode, the row moves
+    by -lr_A times the finite-difference gradient of that ONE entry's loss e^2/2 + lam_A |a|^2/2 at
+    the CURRENT parameters; afterwards B moves by -lr_B times the finite-difference gradient of the
+    mean loss over Psi at the updated factor matrices.  float64 throughout."""
+    N = len(dims)
+    A = [a.astype(np.float64) for a in A]
+    B64 = [b.astype(np.float64) for b in B]
+    G = dense_core(B64)
+
+    def entry_loss(p, n, row):
+        rows = [A[m][idx[m][p]] if m != n else row for m in range(N)]
+        e = float(vals[p]) - tucker_entry_fast(G, rows)
+        return 0.5 * e * e + 0.5 * lam_A * float(np.dot(row, row))
+
+    for p in pos:
+        for n in range(N):
+            row = A[n][idx[n][p]].copy()
+            g = np.zeros_like(row)
+            for j in range(row.shape[0]):
+                rp, rm = row.copy(), row.copy()
+                rp[j] += h
+                rm[j] -= h
+                g[j] = (entry_loss(p, n, rp) - entry_loss(p, n, rm)) / (2 * h)
+            A[n][idx[n][p]] = (row - lr_A * g).astype(np.float32).astype(np.float64)   # rows are stored in fp32
+    gB = [fd_grad(lambda: loss_B(A, B64, idx, vals, pos, lam_B), B64, n) for n in range(N)]
+    Bn = [B64[n] - lr_B * gB[n] for n in range(N)]
+    return A, Bn
+
+
+@pytest.mark.parametrize("dims,J,R", SHAPES[:4])
+def test_in_place_step_replays_algorithm_order(dims, J, R):
+    nnz = 10
+    idx, vals, A, B = random_problem(21, dims, J, R, nnz, scale=0.7)
+    pos = np.array([2, 5, 5, 0, 9, 2], dtype=np.int64)        # repeated samples, repeated rows
+    lr_A, lr_B, lam_A, lam_B = 0.05, 0.1, 0.3, 0.2
+    wantA, wantB = replay_in_place_step(dims, idx, vals, A, B, pos, lr_A, lr_B, lam_A, lam_B)
+    A1 = [a.copy() for a in A]
+    B1 = [b.copy() for b in B]
+    oracle.sgd_step_hogwild(dims, idx, vals, A1, B1, pos, lr_A, lr_B, lam_A, lam_B)
+    for n in range(len(dims)):
+        np.testing.assert_allclose(A1[n], wantA[n], rtol=0, atol=3e-6)
+        np.testing.assert_allclose(B1[n], wantB[n], rtol=0, atol=3e-6)
+
+
+def test_in_place_step_differs_from_synchronous_only_through_the_order():
+    """With one mode (N = 1) and samples on distinct rows no update can see another one: the two
+    orders give the same factor matrix.  With lr_A = 0 the core update is the synchronous one."""
+    dims, J, R = (12,), (3,), 2
+    idx, vals, A, B = random_problem(22, dims, J, R, 12)
+    idx = [np.arange(12, dtype=np.int32)]
+    pos = np.array([3, 7, 1, 10], dtype=np.int64)
+    res = []
+    for step in (oracle.sgd_step_sync, oracle.sgd_step_hogwild):
+        A1, B1 = [a.copy() for a in A], [b.copy() for b in B]
+        step(dims, idx, vals, A1, B1, pos, 0.1, 0.0, 0.05, 0.0)
+        res.append(A1[0])
+    np.testing.assert_array_equal(res[0], res[1])
+    dims, J, R = (5, 4, 6), (3, 2, 4), 3
+    idx, vals, A, B = random_problem(23, dims, J, R, 20)
+    pos = oracle.sample_positions(9, 15, 20)
+    res = []
+    for step in (oracle.sgd_step_sync, oracle.sgd_step_hogwild):
+        A1, B1 = [a.copy() for a in A], [b.copy() for b in B]
+        step(dims, idx, vals, A1, B1, pos, 0.0, 0.2, 0.05, 0.1)
+        res.append(B1)
+    for x, y in zip(*res):
+        np.testing.assert_array_equal(x, y)
+
+
+# ----------------------------------------------------------------------------
 # RMSE / MAE
 # ----------------------------------------------------------------------------
 def test_rmse_and_mae_against_dense_model():

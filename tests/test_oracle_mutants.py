@@ -26,6 +26,10 @@ MUTANTS = [
     ("init-uses-low-bits", "(o.w[0] >> 8)", "(o.w[0] & 0xFFFFFFu)"),
     ("untouched-rows-decay", "if (!touched[n][(size_t)i]) continue;",
      "if (!touched[n][(size_t)i]) { for (int j = 0; j < J[n]; ++j) A[n][(size_t)i * J[n] + j] *= (float)(1.0 - lr_A * lambda_A); continue; }"),
+    ("in-place-step-uses-stale-rows", "            nonzero_terms(N, J, R, a.data(), B, t);   // everything from the current rows\n",
+     "            if (n == 0) nonzero_terms(N, J, R, a.data(), B, t);\n"),
+    ("in-place-core-not-averaged", "(double)lr_B * (GB[n][q] / (double)n_samples + (double)lambda_B * (double)B[n][q]));\n    return 0;\n}\n\n// Summed",
+     "(double)lr_B * (GB[n][q] + (double)lambda_B * (double)B[n][q]));\n    return 0;\n}\n\n// Summed"),
     ("rmse-without-root", "*rmse_out = std::sqrt(sse / (double)m);", "*rmse_out = sse / (double)m;"),
 ]
 
@@ -33,9 +37,11 @@ MUTANTS = [
 @pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
 def test_planted_mistake_is_caught(tmp_path, name, old, new):
     text = open(SRC).read()
-    assert text.count(old) == 1, "mutation site for %s not found exactly once" % name
+    # the synchronous step comes first in the file; a snippet it shares with the in-place step is
+    # mutated there only (the in-place step has mutants of its own)
+    assert text.count(old) in (1, 2), "mutation site for %s not found" % name
     mutant = tmp_path / "mutant.cpp"
-    mutant.write_text(text.replace(old, new))
+    mutant.write_text(text.replace(old, new, 1))
     env = dict(os.environ, FTK_ORACLE_SOURCE=str(mutant), FTK_ORACLE_LIB=str(tmp_path / "libmutant.so"))
     proc = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
                            os.path.join(ROOT, "tests", "test_oracle_sampling.py"),
