@@ -15,6 +15,7 @@
 #include "../../include/ftk.h"
 #include "ftk_kernels_generic.hpp"
 #include "ftk_kernels_mfma16.hpp"
+#include "ftk_kernels_tiled.hpp"
 
 using namespace ftk;
 
@@ -22,8 +23,8 @@ namespace {
 
 thread_local std::string g_create_error;
 
-enum Variant { V_GENERIC = 0, V_MFMA16 = 1 };
-const char* const kVariantNames[] = {"generic", "mfma16"};
+enum Variant { V_GENERIC = 0, V_MFMA16 = 1, V_TILED = 2 };
+const char* const kVariantNames[] = {"generic", "mfma16", "tiled"};
 
 struct TimingSlot {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pending;
@@ -72,6 +73,10 @@ struct ftk_ctx {
 
     // frequently hit rows: rows [0, hot_K[n]) of mode n (internal numbering) are accumulated in LDS
     bool mfma16_ok = false;
+    bool tiled_ok = false;    // general matrix-core kernel: J_n, R <= 64
+    int tiled_P = 1;          // ranks padded to 16 * tiled_P
+    int tiled_waves = 8;
+    size_t tiled_lds_bytes = 0;
     int hot_K[kMaxOrder] = {};
     int hot_off[kMaxOrder] = {};
     int hot_H = 0;            // rows in the LDS table for the current |Psi|
@@ -248,6 +253,69 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
     }
 }
 
+template <int N, int P, int WAVES>
+int launch_tiled_npw(ftk_ctx* c, const TiledArgs& g) {
+    FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->tiled_lds_bytes));
+    Bracket t(c, FTK_K_GRAD);
+    hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
+                       c->stream, g);
+    FTK_HIP(c, hipGetLastError());
+    return FTK_OK;
+}
+
+template <int N>
+int launch_tiled_n(ftk_ctx* c, const TiledArgs& g) {
+    switch (c->tiled_P) {
+        case 1: return launch_tiled_npw<N, 1, 8>(c, g);
+        case 2: return launch_tiled_npw<N, 2, 8>(c, g);
+        default: return launch_tiled_npw<N, 4, 4>(c, g);
+    }
+}
+
+int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
+    const bool in_place = c->mode == FTK_HOGWILD;
+    TiledArgs g;
+    g.coo = Coo{c->d_rec, c->rec_words};
+    g.nnz = (uint64_t)c->nnz;
+    g.seed = c->sample_seed;
+    g.M = c->n_samples;
+    g.A = c->d_A;
+    g.B = c->d_B;
+    g.dA = in_place ? c->d_A : c->d_dA;
+    g.scale = in_place ? -lr_A : 1.0f;
+    g.R = c->L.R;
+    for (int n = 0; n < kMaxOrder; ++n) {
+        g.A_off[n] = c->L.A_off[n];
+        g.B_off[n] = c->L.B_off[n];
+        g.J[n] = c->L.J[n];
+        g.K[n] = c->hot_K[n];
+        g.top[n] = c->hot_K[n] >= 16 ? 16 : 0;
+        g.hot_off[n] = c->hot_off[n];
+        g.mode_bytes[n] = (unsigned int)(c->dims[n] * c->L.J[n] * 4);
+    }
+    g.H = c->hot_H;
+    g.hot_partial = c->d_hot_partial;
+    g.gb_partial = c->d_gb_partial;
+    g.B_total = c->L.B_total;
+    g.lambda_A = lambda_A;
+    // what the kernel assumes: padded ranks 16 P, records of 4 * ceil((N + 1) / 4) words, an LDS
+    // table that fits, partial tables sized for grid x waves
+    if (!c->tiled_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->d_hot_partial || !c->d_gb_partial ||
+        c->tiled_lds_bytes > (size_t)c->max_lds || (size_t)c->hot_H * 64 * c->tiled_P > (size_t)c->max_lds)
+        return fail(c, FTK_EUNSUPPORTED, "tiled kernel is not available for this shape");
+    switch (c->order) {
+        case 1: return launch_tiled_n<1>(c, g);
+        case 2: return launch_tiled_n<2>(c, g);
+        case 3: return launch_tiled_n<3>(c, g);
+        case 4: return launch_tiled_n<4>(c, g);
+        case 5: return launch_tiled_n<5>(c, g);
+        case 6: return launch_tiled_n<6>(c, g);
+        case 7: return launch_tiled_n<7>(c, g);
+        default: return launch_tiled_n<8>(c, g);
+    }
+}
+
 // Psi as arrays (positions, row numbers, values): needed by the generic kernel and ftk_get_samples
 int ensure_batch(ftk_ctx* c) {
     if (c->batch_valid) return FTK_OK;
@@ -287,6 +355,26 @@ void launch_errors_mfma16_n(ftk_ctx* c, const Coo& coo) {
                        (const float*)c->d_A, (const float*)c->d_B, c->L, c->d_sums);
 }
 
+template <int N, int P>
+void launch_errors_tiled_np(ftk_ctx* c, const Coo& coo) {
+    const long long groups = (c->nnz + 63) / 64;
+    const int grid = blocks_for(groups, 4, c->num_cu * 8);
+    const size_t lds = 4 * ((size_t)N * 256 * P * P + 4 * (size_t)tiled_wave_scratch(N));
+    hipFuncSetAttribute(reinterpret_cast<const void*>(errors_tiled_kernel<N, P>),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((errors_tiled_kernel<N, P>), dim3(grid), dim3(256), lds, c->stream, coo, (uint64_t)c->nnz,
+                       (const float*)c->d_A, (const float*)c->d_B, c->L, c->d_sums);
+}
+
+template <int N>
+void launch_errors_tiled_n(ftk_ctx* c, const Coo& coo) {
+    switch (c->tiled_P) {
+        case 1: launch_errors_tiled_np<N, 1>(c, coo); break;
+        case 2: launch_errors_tiled_np<N, 2>(c, coo); break;
+        default: launch_errors_tiled_np<N, 4>(c, coo); break;
+    }
+}
+
 int launch_errors(ftk_ctx* c, double* host_sums) {
     Coo coo{c->d_rec, c->rec_words};
     FTK_HIP(c, hipMemsetAsync(c->d_sums, 0, 2 * sizeof(double), c->stream));
@@ -298,6 +386,17 @@ int launch_errors(ftk_ctx* c, double* host_sums) {
             case 4: launch_errors_mfma16_n<4>(c, coo); break;
             case 5: launch_errors_mfma16_n<5>(c, coo); break;
             default: launch_errors_mfma16_n<6>(c, coo); break;
+        }
+    } else if (c->variant == V_TILED && c->rec_words == 4 * ((c->order + 1 + 3) / 4)) {
+        switch (c->order) {
+            case 1: launch_errors_tiled_n<1>(c, coo); break;
+            case 2: launch_errors_tiled_n<2>(c, coo); break;
+            case 3: launch_errors_tiled_n<3>(c, coo); break;
+            case 4: launch_errors_tiled_n<4>(c, coo); break;
+            case 5: launch_errors_tiled_n<5>(c, coo); break;
+            case 6: launch_errors_tiled_n<6>(c, coo); break;
+            case 7: launch_errors_tiled_n<7>(c, coo); break;
+            default: launch_errors_tiled_n<8>(c, coo); break;
         }
     } else {
         const int b_in_lds = (size_t)c->L.B_total * 4 <= 65536 - 256;
@@ -333,6 +432,16 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     const int N = c->order;
     long long rows_total = 0;
     for (int n = 0; n < N; ++n) rows_total += c->dims[n];
+    // LDS left for the table once the kernel's fixed needs are met, in table rows
+    long long budget_bytes, row_bytes;
+    if (c->variant == V_TILED) {
+        budget_bytes = (long long)c->max_lds - 4LL * (long long)tiled_lds_floats(N, c->tiled_P, c->tiled_waves, 0) - 1024;
+        row_bytes = 64LL * c->tiled_P;
+    } else {
+        budget_bytes = (long long)c->max_lds - 4LL * (kMfmaWaves * mfma16_wave_scratch(N) + N * 256) - 1024;
+        row_bytes = 64;
+    }
+    c->hot_H_max = (int)std::max(1LL, budget_bytes / row_bytes);
     const int H = (int)std::min<long long>(c->hot_H_max, rows_total);
     double min_count = 2.0 * (double)c->mfma_grid * (double)c->nnz / (double)std::max<long long>(n_samples, 1);
     if (const char* e = getenv("FTK_HOT_PMIN")) min_count = atof(e) * (double)c->nnz;   // tuning override
@@ -359,6 +468,7 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     }
     c->hot_H = std::max(off, 1);
     c->mfma_lds_bytes = 4 * ((size_t)c->hot_H * 16 + kMfmaWaves * mfma16_wave_scratch(N) + N * 256);
+    c->tiled_lds_bytes = 4 * tiled_lds_floats(N, c->tiled_P, c->tiled_waves, c->hot_H);
     c->hot_for_M = n_samples;
 }
 
@@ -389,7 +499,18 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     c->mfma16_ok = c->L.R == 16 && N <= 6 && c->max_lds >= 131072;
     for (int n = 0; n < N; ++n)   // 16-float rows, addressed with 32-bit element offsets inside a mode
         c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16 && dims[n] < (1LL << 25);
-    if (c->gen_threads == 0 && !c->mfma16_ok)
+    {
+        int pm = c->L.R;
+        c->tiled_ok = N <= 8 && c->L.R <= 64 && c->max_lds >= 131072;
+        for (int n = 0; n < N; ++n) {
+            pm = std::max(pm, c->L.J[n]);
+            c->tiled_ok = c->tiled_ok && c->L.J[n] <= 64 && dims[n] * c->L.J[n] < (1LL << 29);   // 32-bit byte offsets
+        }
+        c->tiled_P = pm <= 16 ? 1 : pm <= 32 ? 2 : 4;
+        c->tiled_waves = c->tiled_P == 4 ? 4 : 8;
+        if (4LL * (long long)tiled_lds_floats(N, c->tiled_P, c->tiled_waves, 16) + 1024 > c->max_lds) c->tiled_ok = false;
+    }
+    if (c->gen_threads == 0 && !c->mfma16_ok && !c->tiled_ok)
         return fail(c, FTK_EUNSUPPORTED, "N*R = %d with sum J_n R = %d exceeds the kernels' LDS budget", N * c->L.R,
                     c->L.B_total);
 
@@ -481,16 +602,14 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     FTK_HIP(c, hipGetLastError());
 
     // ---- kernel variant ----
-    if (c->mfma16_ok) {
+    c->variant = c->mfma16_ok ? V_MFMA16 : c->tiled_ok ? V_TILED : V_GENERIC;
+    if (c->mfma16_ok || c->tiled_ok) {
         c->mfma_grid = c->num_cu;
-        const long long budget = (long long)c->max_lds - 4LL * (kMfmaWaves * mfma16_wave_scratch(N) + N * 256) - 1024;
-        c->hot_H_max = (int)std::max(1LL, budget / 64);
+        // per-workgroup tables of the frequently hit rows: never more than the LDS can hold; per-wave
+        // (tiled) or per-workgroup (mfma16) tables of the core gradient
+        FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid * c->max_lds));
+        FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid * 8 * c->L.B_total * sizeof(float)));
         pick_hot_rows(c, 1LL << 20);
-        FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid * c->hot_H_max * 16 * sizeof(float)));
-        FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid * c->L.B_total * sizeof(float)));
-        c->variant = V_MFMA16;
-    } else {
-        c->variant = V_GENERIC;
     }
     FTK_HIP(c, hipStreamSynchronize(c->stream));
     return FTK_OK;
@@ -551,7 +670,7 @@ int ftk_sample(ftk_ctx* c, uint64_t seed, int64_t n_samples) {
     c->sample_seed = seed;
     c->n_samples = n_samples;
     c->batch_valid = false;
-    if (c->mfma16_ok && c->hot_for_M != n_samples) pick_hot_rows(c, n_samples);
+    if (c->variant != V_GENERIC && c->hot_for_M != n_samples) pick_hot_rows(c, n_samples);
     return FTK_OK;
 }
 
@@ -577,11 +696,13 @@ int ftk_get_samples(ftk_ctx* c, int64_t* pos_out) {
 int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
     if (!c) return FTK_EINVAL;
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step before ftk_sample");
-    const bool mfma = c->variant == V_MFMA16;
+    const bool mfma = c->variant != V_GENERIC;     // a matrix-core variant: per-workgroup tables
+    const bool tiled = c->variant == V_TILED;
     const bool in_place = c->mode == FTK_HOGWILD;
     int rc = mfma ? FTK_OK : ensure_batch(c);
     if (rc != FTK_OK) return rc;
-    rc = mfma ? launch_grad_mfma16(c, lambda_A, lr_A) : launch_grad_generic(c, lambda_A, lr_A);
+    rc = tiled ? launch_grad_tiled(c, lambda_A, lr_A)
+               : mfma ? launch_grad_mfma16(c, lambda_A, lr_A) : launch_grad_generic(c, lambda_A, lr_A);
     if (rc != FTK_OK) return rc;
     {
         ApplyArgs p = {};
@@ -595,10 +716,11 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
             p.hot_partial = c->d_hot_partial;
             p.hot_parts = c->mfma_grid;
             p.H = c->hot_H;
-            p.J = 16;
-            p.hot_blocks = (c->hot_H * 16 + 15) / 16;
+            p.J = tiled ? 16 * c->tiled_P : 16;
+            p.hot_blocks = (c->hot_H * p.J + 15) / 16;
             p.order = c->order;
             for (int n = 0; n < kMaxOrder; ++n) {
+                p.Jn[n] = c->L.J[n];
                 p.K[n] = c->hot_K[n];
                 p.hot_off[n] = c->hot_off[n];
                 p.A_off[n] = c->L.A_off[n];
@@ -607,7 +729,7 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
         p.B = c->d_B;
         p.GB = mfma ? c->d_gb_partial : c->d_GB;
         p.B_total = c->L.B_total;
-        p.gb_parts = mfma ? c->mfma_grid : 1;
+        p.gb_parts = tiled ? c->mfma_grid * c->tiled_waves : mfma ? c->mfma_grid : 1;
         p.gb_clear = mfma ? 0 : 1;
         p.lr_A = in_place ? -1.0f : lr_A;
         p.lr_B = lr_B;
@@ -737,10 +859,7 @@ int ftk_set_kernel(ftk_ctx* c, const char* name) {
     if (!c) return FTK_EINVAL;
     if (!name) return fail(c, FTK_EINVAL, "name is NULL");
     // the accumulators of both variants are clean between steps, so switching is always safe
-    if (!strcmp(name, "auto")) {
-        c->variant = c->mfma16_ok ? V_MFMA16 : V_GENERIC;
-        return FTK_OK;
-    }
+    if (!strcmp(name, "auto")) name = c->mfma16_ok ? "mfma16" : c->tiled_ok ? "tiled" : "generic";
     if (!strcmp(name, "generic")) {
         if (c->gen_threads == 0) return fail(c, FTK_EUNSUPPORTED, "the generic kernel does not fit this shape");
         c->variant = V_GENERIC;
@@ -749,6 +868,13 @@ int ftk_set_kernel(ftk_ctx* c, const char* name) {
     if (!strcmp(name, "mfma16")) {
         if (!c->mfma16_ok) return fail(c, FTK_EUNSUPPORTED, "mfma16 needs J_n = R = 16 and order <= 6");
         c->variant = V_MFMA16;
+        pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
+        return FTK_OK;
+    }
+    if (!strcmp(name, "tiled")) {
+        if (!c->tiled_ok) return fail(c, FTK_EUNSUPPORTED, "tiled needs J_n <= 64 and R <= 64");
+        c->variant = V_TILED;
+        pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
         return FTK_OK;
     }
     return fail(c, FTK_EUNSUPPORTED, "no kernel variant named '%s'", name);

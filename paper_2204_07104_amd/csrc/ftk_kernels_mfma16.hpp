@@ -484,7 +484,8 @@ struct ApplyArgs {
     int hot_parts;
     int hot_blocks;             // ceil(H * J / 16)
     int H;
-    int J;
+    int J;                      // floats per table row (J_n padded to a multiple of 16)
+    int Jn[kMaxOrder];          // floats per row of A^(n)
     int order;
     int K[kMaxOrder];
     int hot_off[kMaxOrder];
@@ -541,8 +542,8 @@ __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
         int n = -1;
         for (int m = 0; m < p.order; ++m)
             if (hrow >= p.hot_off[m] && hrow < p.hot_off[m] + p.K[m]) n = m;
-        if (n >= 0 && total != 0.0f) {
-            float* a = p.A + p.A_off[n] + (long long)(hrow - p.hot_off[n]) * p.J + j;
+        if (n >= 0 && j < p.Jn[n] && total != 0.0f) {
+            float* a = p.A + p.A_off[n] + (long long)(hrow - p.hot_off[n]) * p.Jn[n] + j;
             *a = fmaf(-p.lr_A, total, *a);
         }
     } else {

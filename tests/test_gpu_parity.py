@@ -27,6 +27,17 @@ def assert_params_close(got, want, what):
         assert worst <= 0.0, "%s[%d]: max excess over tolerance %.3e (max abs err %.3e)" % (what, n, worst, float(err.max()))
 
 
+# step sizes for one-step comparisons: large enough that the most frequently hit rows and the core
+# factors move by percents (the benchmark's own step sizes are chosen for many stable steps)
+TEST_STEP_SIZES = {
+    "C1": dict(lr_A=1e-3, lr_B=1e-3),
+    "C2": dict(lr_A=1e-8, lr_B=1e-2),
+    "C3": dict(lr_A=1e-11, lr_B=1e-4),
+    "C4": dict(lr_A=4e-3, lr_B=1.0),
+    "C5": dict(lr_A=5e-13, lr_B=1e-6),
+}
+
+
 def oracle_state(w):
     return oracle.init_factors(w.init_seed, w.dims, w.J, w.R)
 
@@ -36,6 +47,8 @@ def one_step_case(w, idx, vals, A0=None, B0=None, seed=None, kernel=None):
     with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
         if kernel:
             ft.ftk_set_kernel(kernel)
+            if kernel != "auto":
+                assert ft.ftk_kernel_name() == kernel
         if A0 is not None:
             ft.ftk_set_factors(A0, B0)
             A, B = [a.copy() for a in A0], [b.copy() for b in B0]
@@ -144,6 +157,9 @@ def test_ten_steps_rmse_scaled_c2_both_kernels():
 
 TINY = [
     # order, dims, nnz, J, R, M
+    (3, (40, 30, 20), 4000, (64, 64, 64), 64, 700),
+    (3, (200, 300, 20), 20000, (24, 40, 9), 20, 5000),      # ranks that are no multiple of 16, padded tiles
+    (2, (5000, 3), 30000, (32, 32), 48, 20001),             # a 3-row mode: everything collides
     (1, (50,), 200, (4,), 3, 100),
     (2, (40, 30), 500, (3, 5), 4, 333),
     (3, (20, 30, 10), 2000, (2, 3, 4), 2, 1000),
@@ -159,13 +175,16 @@ TINY = [
 ]
 
 
+@pytest.mark.parametrize("kernel", ["auto", "generic", "tiled"])
 @pytest.mark.parametrize("order,dims,nnz,J,R,M", TINY)
-def test_one_step_small_shapes(order, dims, nnz, J, R, M):
-    announce("tiny order=%d dims=%r J=%r R=%d M=%d" % (order, dims, J, R, M))
+def test_one_step_small_shapes(order, dims, nnz, J, R, M, kernel):
+    """Every gradient-kernel variant on every small shape: "auto" is the specialised J = R = 16 kernel
+    where it applies and the tiled matrix-core kernel elsewhere."""
+    announce("tiny order=%d dims=%r J=%r R=%d M=%d kernel=%s" % (order, dims, J, R, M, kernel))
     w = synth.tiny_workload(order, dims, nnz, J, R, M, seed=11 + order, values="normal")
     w = synth.replace(w, lr_A=1e-2, lr_B=1e-2)
     idx, vals = synth.make_tensor(w)
-    one_step_case(w, idx, vals)
+    one_step_case(w, idx, vals, kernel=kernel)
 
 
 @pytest.mark.parametrize("name,nnz,M,dims", [
@@ -176,7 +195,7 @@ def test_one_step_small_shapes(order, dims, nnz, J, R, M):
 ])
 def test_one_step_scaled_workloads(name, nnz, M, dims):
     announce("scaled %s" % name)
-    w = synth.WORKLOADS[name].scaled(nnz=nnz, n_samples=M, dims=dims)
+    w = synth.replace(synth.WORKLOADS[name].scaled(nnz=nnz, n_samples=M, dims=dims), **TEST_STEP_SIZES[name])
     idx, vals = synth.make_tensor(w)
     one_step_case(w, idx, vals)
 
