@@ -16,12 +16,18 @@
 // exists in two register layouts:
 //   X: lane (c, g) holds sample c, components 4g..4g+3
 //   Y: lane (c, g) holds component c of samples 4g..4g+3   (16 lanes cover one 64-byte row)
-// Rows are gathered in layout Y only (four full 64-byte rows per load instruction) and reach
-// layout X through a per-wave LDS buffer; -e w goes the other way.  The A gradient (with the -e
-// factor already folded into w) comes out of the matrix core directly in layout Y, which lets a
-// row be added with ONE 64-byte atomic request.
-// The row gather of the next tile is issued before the current tile is computed, and the record
-// reads of the next 64 samples are in flight during the whole current group of four tiles.
+// Rows are gathered in layout X (one 16-byte load per lane and mode: a quarter of a row) and feed
+// the projections straight from the registers they arrive in; layout Y, which the core gradient
+// and the regulariser term need later in the tile, is reached through a per-wave LDS buffer, and
+// -e w takes the same route.  The A gradient (with the -e factor already folded into w) comes out
+// of the matrix core directly in layout Y, which lets a row be added with ONE 64-byte atomic
+// request per 16 lanes.
+// A random 64-byte row read takes a few microseconds to come back on a loaded chip, far longer
+// than a tile's arithmetic, and a workgroup that owns a whole CU's LDS runs only two waves per
+// SIMD.  So every wave keeps a deep software pipeline of its own: the rows of the next THREE
+// tiles are always in flight (a ring of four register tiles, crossing group boundaries), the
+// records of the next group are already parked in LDS, and the records of the group after that
+// are on their way.
 //
 // Rows are numbered by descending frequency, so the rows most samples hit are rows [0, K_n) of
 // each mode: their gradient sums are kept in an LDS table (one per workgroup) and leave the
@@ -45,8 +51,8 @@ constexpr int kMfmaWaves = 8;                  // waves per workgroup (one workg
 constexpr int kMfmaThreads = kMfmaWaves * 64;
 constexpr int kTransposeFloats = 16 * 20;      // 16x16 tile, rows padded to 20 floats
 __host__ __device__ constexpr int mfma16_wave_scratch(int order) {
-    // floats per wave: N index columns + values of 64 samples | one transpose buffer per mode
-    return (order + 1) * 64 + order * kTransposeFloats;
+    // floats per wave: two buffers of (N index columns + values of 64 samples) | one transpose buffer per mode
+    return 2 * (order + 1) * 64 + order * kTransposeFloats;
 }
 
 struct Mfma16Args {
@@ -71,9 +77,13 @@ struct Mfma16Args {
 };
 
 __device__ __forceinline__ void lds_wave_sync() {
-    // LDS requests of one wave complete in order; this keeps the compiler from moving LDS reads
-    // above the writes of other lanes they depend on, and waits for outstanding LDS traffic.
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // Lanes of one wave exchange data through LDS without a workgroup barrier.  The LDS unit
+    // executes the requests of a wave in the order they were issued, so a read issued after
+    // another lane's write already sees it; all that is needed is that the COMPILER keeps the
+    // program order of the accesses (it reasons per thread and could otherwise move a read above a
+    // write to a different address).  No wait is issued here: the compiler waits for each read
+    // where its value is first used, which leaves the round trip free to overlap other work.
+    asm volatile("" ::: "memory");
 }
 
 // LDS float add by compare-and-swap.  The native LDS float add (ds_add_f32) retires about one
@@ -88,94 +98,86 @@ __device__ __forceinline__ void lds_float_add(float* p, float v) {
     } while (seen != expect);
 }
 
-template <int N>
-struct TileRows {
-    float aY[N][4];   // layout Y: component c of the rows of samples 4g..4g+3
-    int iY[N][4];     // their row numbers
-    float x;          // value of sample c (layout X)
-};
-
 // Everything a wave keeps across tiles.
 template <int N>
 struct WaveState {
     float Bq[N][4], Br[N][4];   // B^(n) in the two operand layouts: Bq[n][k] = B[4g+k][c], Br[n][k] = B[c][4g+k]
     floatx4 GBacc[N];           // core gradient, D layout: GB[j = 4g+v][r = c]
     floatx4 Top[N];             // gradient sums of rows 0..15 of each mode, D layout: [row 4g+v][j = c]
+    floatx4 ring[4][N];         // rows in flight, layout X: slot t % 4 holds tile t (components 4g..4g+3 of sample c)
 };
 
-// One group of 64 samples whose records are parked in this wave's LDS buffer: four tiles of 16.
-// MASKED: the group reaches past the end of Psi (only the last group can); samples past the end
-// were parked as row 0 / value 0 and every contribution of theirs is forced to zero.
 // Buffer resource over `bytes` bytes at p (raw buffer, 32-bit data).  Accesses at offsets past
 // `bytes` are dropped by the hardware: loads return 0 and atomics do nothing.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned int bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
 }
 
-template <int N, bool MASKED, class IssueNext>
-__device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, long long group, float* hot,
-                                              const int* sidx, const float* sval, float* tbuf, int c, int g4,
-                                              IssueNext&& issue_next_records) {
-    const long long M = g.M;
-    auto active = [&](int sub, int v) -> bool { return !MASKED || group * 64 + sub * 16 + 4 * g4 + v < M; };
+// Issue the row gather of tile `t` (0..3) of the group parked at `sbuf` into a ring slot:
+// layout X, lane (c, g) reads bytes [16g, 16g + 16) of sample c's row.
+template <int N>
+__device__ __forceinline__ void gather_rows(const __amdgpu_buffer_rsrc_t (&rsrc_A)[N], const int* sbuf, int t, int c,
+                                            int g4, floatx4 (&dst)[N]) {
+    typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+        const int row = sbuf[n * 64 + t * 16 + c];
+        const uintx4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc_A[n], row * 64 + g4 * 16, 0, 0);
+        dst[n] = floatx4{__uint_as_float(q[0]), __uint_as_float(q[1]), __uint_as_float(q[2]), __uint_as_float(q[3])};
+    }
+}
+
+// One group of 64 samples whose records are parked at `scur` (struct of arrays: N index columns,
+// then the values): four tiles of 16.  While tile t is computed, the rows of tile t + 3 are
+// requested: tile 3 of this group during tile 0, then tiles 0..2 of the wave's next group (parked
+// at `snxt`).  The requests are unconditional, so that the compiler's count of outstanding memory
+// operations is exact; behind a wave's last group the next group is parked as all row 0 and its
+// (unused) rows cost one cached line.
+// `lim` (1..64) is the number of samples of the group that exist: only the last group of Psi can
+// have fewer than 64.  The others were parked as row 0 / value 0; they run through the arithmetic
+// like any sample, with their error and their regulariser weight forced to zero, so that each of
+// their contributions is an exact zero (added to row 0, wherever row 0 is accumulated).
+template <int N>
+__device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, int lim, float* hot,
+                                              const int* scur, const int* snxt, float* tbuf, int c, int g4) {
     __amdgpu_buffer_rsrc_t rsrc_A[N], rsrc_dA[N];
 #pragma unroll
     for (int n = 0; n < N; ++n) {
         rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
         rsrc_dA[n] = make_rsrc(g.dA + g.A_off[n], g.row_bytes[n]);
     }
+    const float* sval = reinterpret_cast<const float*>(scur + N * 64);
 
-    // rows of tile `sub` gathered in layout Y (four full 64-byte rows per load instruction)
-    auto gather = [&](int sub, TileRows<N>& t) {
-        t.x = sval[sub * 16 + c];
-#pragma unroll
-        for (int n = 0; n < N; ++n) {
-            const int4 r = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
-            t.iY[n][0] = r.x;
-            t.iY[n][1] = r.y;
-            t.iY[n][2] = r.z;
-            t.iY[n][3] = r.w;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float a = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_A[n], (t.iY[n][v] * 16 + c) * 4, 0, 0));
-                t.aY[n][v] = active(sub, v) ? a : 0.0f;
-            }
-        }
-    };
-
-    TileRows<N> cur, nxt;
-    gather(0, nxt);
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
-        cur = nxt;
-        if (sub < 3) gather(sub + 1, nxt);
-        // Vector-memory results are waited for in issue order, so the long-latency random record
-        // reads of the next group go out only after this group's last row gather.
-        if (sub == 2) issue_next_records();
+        if (sub == 0)
+            gather_rows<N>(rsrc_A, scur, 3, c, g4, st.ring[3]);
+        else
+            gather_rows<N>(rsrc_A, snxt, sub - 1, c, g4, st.ring[sub - 1]);
 
-        // rows of all modes: layout Y -> LDS -> layout X
+        floatx4 aX[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n) aX[n] = st.ring[sub][n];
+        const float x = sval[sub * 16 + c];
+
+        // rows of all modes: layout X -> LDS -> layout Y (read back further down)
 #pragma unroll
         for (int n = 0; n < N; ++n)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c] = cur.aY[n][v];
-        lds_wave_sync();
-        float4 aX[N];
-#pragma unroll
-        for (int n = 0; n < N; ++n)
-            aX[n] = *reinterpret_cast<const float4*>(tbuf + n * kTransposeFloats + c * 20 + 4 * g4);
+            *reinterpret_cast<float4*>(tbuf + n * kTransposeFloats + c * 20 + 4 * g4) =
+                make_float4(aX[n][0], aX[n][1], aX[n][2], aX[n][3]);
 
         // projections, layout X:  s[n][v] = c^(n)_{r = 4g+v} of sample c
         floatx4 s[N];
 #pragma unroll
         for (int n = 0; n < N; ++n) s[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][0], aX[n].x, s[n], 0, 0, 0);
+        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][0], aX[n][0], s[n], 0, 0, 0);
 #pragma unroll
-        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][1], aX[n].y, s[n], 0, 0, 0);
+        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][1], aX[n][1], s[n], 0, 0, 0);
 #pragma unroll
-        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][2], aX[n].z, s[n], 0, 0, 0);
+        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][2], aX[n][2], s[n], 0, 0, 0);
 #pragma unroll
-        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][3], aX[n].w, s[n], 0, 0, 0);
+        for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][3], aX[n][3], s[n], 0, 0, 0);
 
         // leave-one-out products (prefix sweep, then suffix sweep), prediction, error
         floatx4 w[N];
@@ -185,10 +187,12 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
             w[n] = run;
             run *= s[n];
         }
-        float xhat = (run[0] + run[1]) + (run[2] + run[3]);
-        xhat += __shfl_xor(xhat, 16);
-        xhat += __shfl_xor(xhat, 32);
-        const float neg_e = xhat - cur.x;
+        // x^ of sample c = sum over r: four components here, the other twelve in the lanes of the
+        // other three g.  A product with an all-ones matrix adds across g and leaves the sum in
+        // every lane of column c, without a trip through LDS.
+        const float part = (run[0] + run[1]) + (run[2] + run[3]);
+        const floatx4 xsum = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, part, floatx4{0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0);
+        const float neg_e = sub * 16 + c < lim ? xsum[0] - x : 0.0f;
         run = floatx4{1.0f, 1.0f, 1.0f, 1.0f};
 #pragma unroll
         for (int n = N - 1; n >= 0; --n) {
@@ -196,8 +200,16 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
             run *= s[n];
         }
 
-        // -e w of all modes: layout X -> LDS -> layout Y.  (The a-reads of this buffer are
-        // complete: the projections above consumed them.)
+        // rows in layout Y, out of the buffer before -e w goes into it
+        lds_wave_sync();
+        float aY[N][4];
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) aY[n][v] = tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c];
+        lds_wave_sync();
+
+        // -e w of all modes: layout X -> LDS -> layout Y
 #pragma unroll
         for (int n = 0; n < N; ++n) {
             w[n] *= neg_e;
@@ -225,29 +237,37 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
         //   rows [top, K)   added to the workgroup's LDS table (reads, then compare-and-swaps)
         //   rows [K, I_n)   global float atomics
         float grad[N][4];
+        float lam[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) lam[v] = sub * 16 + 4 * g4 + v < lim ? g.lambda_A : 0.0f;
+        int iY[N][4];
         unsigned int* cell[N][4];
         unsigned int seen[N][4];
         unsigned int pending = 0;
+        // lanes with nothing to add to the LDS table aim their (unconditional) swaps at a word of their own
+        unsigned int* const dummy = reinterpret_cast<unsigned int*>(tbuf + (c + 16 * g4));
 #pragma unroll
         for (int n = 0; n < N; ++n) {
+            const int4 r = *reinterpret_cast<const int4*>(scur + n * 64 + sub * 16 + 4 * g4);
+            iY[n][0] = r.x;
+            iY[n][1] = r.y;
+            iY[n][2] = r.z;
+            iY[n][3] = r.w;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int row = cur.iY[n][v];
-                grad[n][v] = g.scale * fmaf(g.lambda_A, cur.aY[n][v], gs[n][v]);
-                if (MASKED && !active(sub, v)) grad[n][v] = 0.0f;
-                cell[n][v] = reinterpret_cast<unsigned int*>(hot + (uint32_t)((g.hot_off[n] + row) * 16 + c));
-                // Every lane issues the atomic; lanes whose row lives in LDS (or is past the end of
-                // Psi) aim past the end of the buffer, where the hardware drops the request.  An
+                const int row = iY[n][v];
+                grad[n][v] = g.scale * fmaf(lam[v], aY[n][v], gs[n][v]);
+                // Every lane issues the atomic; lanes whose row lives in LDS aim past the end of the
+                // buffer, where the hardware drops the request.  An
                 // unconditional instruction lets the compiler count outstanding memory operations
-                // exactly, so waiting for the prefetched rows never waits for these atomics.
-                const bool cold = row >= g.K[n] && active(sub, v);
+                // exactly, so waiting for prefetched rows never waits for atomics issued after them.
+                const bool cold = row >= g.K[n];
                 __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[n][v], rsrc_dA[n],
                                                                 cold ? (row * 16 + c) * 4 : (int)g.row_bytes[n] + c * 4, 0, 0);
-                if (row >= g.K[n]) {
-                } else if (row >= g.top[n] && active(sub, v)) {
-                    seen[n][v] = *cell[n][v];
-                    pending |= 1u << (n * 4 + v);
-                }
+                const bool in_table = !cold && row >= g.top[n];
+                cell[n][v] = in_table ? reinterpret_cast<unsigned int*>(hot + (uint32_t)((g.hot_off[n] + row) * 16 + c)) : dummy;
+                seen[n][v] = *cell[n][v];
+                if (in_table) pending |= 1u << (n * 4 + v);
             }
         }
 #pragma unroll
@@ -255,29 +275,38 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
             if (g.top[n] > 0) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const float onehot = cur.iY[n][k] == c ? 1.0f : 0.0f;   // inactive samples carry grad = 0
+                    const float onehot = iY[n][k] == c ? 1.0f : 0.0f;
                     st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot, grad[n][k], st.Top[n], 0, 0, 0);
                 }
             }
-        // one compare-and-swap per pending row element; lanes that lose a race go round again
-        while (pending) {
-#pragma unroll
-            for (int n = 0; n < N; ++n)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (pending & (1u << (n * 4 + v))) {
-                        const unsigned int expect = seen[n][v];
-                        seen[n][v] = atomicCAS(cell[n][v], expect, __float_as_uint(__uint_as_float(expect) + grad[n][v]));
-                        if (seen[n][v] == expect) pending &= ~(1u << (n * 4 + v));
-                    }
-        }
-
         // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
 #pragma unroll
             for (int n = 0; n < N; ++n)
-                st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(cur.aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
+                st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
+        // One compare-and-swap per pending row element; lanes that lose a race go round again.
+        // All swaps of a round are issued before the first result is looked at, so a round costs
+        // one LDS round trip, not one per element.
+        while (pending) {
+            unsigned int got[N][4];
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    got[n][v] = atomicCAS(cell[n][v], seen[n][v], __float_as_uint(__uint_as_float(seen[n][v]) + grad[n][v]));
+            __builtin_amdgcn_sched_barrier(0);   // all swaps go out before the first result is waited for
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if (got[n][v] == seen[n][v]) {   // done: never add this element again
+                        pending &= ~(1u << (n * 4 + v));
+                        cell[n][v] = dummy;
+                    }
+                    seen[n][v] = got[n][v];
+                }
+        }
     }
 }
 
@@ -285,13 +314,14 @@ template <int N>
 __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g) {
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;   // 16-byte words per record
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int kRecFloats = (N + 1) * 64;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int c = lane & 15, g4 = lane >> 4;
     float* hot = lds;
     float* wave_lds = lds + (size_t)g.H * 16 + wave * mfma16_wave_scratch(N);
-    int* sidx = reinterpret_cast<int*>(wave_lds);           // [N][64]
-    float* sval = wave_lds + N * 64;                         // [64]
-    float* tbuf = wave_lds + (N + 1) * 64;                   // [N][16][20]
+    int* sbuf = reinterpret_cast<int*>(wave_lds);            // two buffers of [N][64] row numbers + [64] values
+    float* tbuf = wave_lds + 2 * kRecFloats;                 // [N][16][20]
     float* gbred = lds + (size_t)g.H * 16 + kMfmaWaves * mfma16_wave_scratch(N);
 
     for (int q = tid; q < g.H * 16; q += kMfmaThreads) hot[q] = 0.0f;
@@ -308,6 +338,8 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
         }
         st.GBacc[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
         st.Top[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) st.ring[t][n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
     }
     __syncthreads();
 
@@ -316,43 +348,65 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     const long long group_stride = (long long)gridDim.x * kMfmaWaves;
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
 
-    // record of sample (group * 64 + lane): N row numbers and the value's bits
+    // record of sample (group * 64 + lane): N row numbers and the value's bits.  A group past
+    // the end of Psi (and a lane past the end of the last group) reads record 0 and is parked
+    // as row 0 / value 0.
     auto load_record = [&](long long grp, uint4 (&rec)[W4]) {
         const long long k = grp * 64 + lane;
         const uint32_t p = k < M ? sample_position(g.seed, (uint64_t)k, g.nnz) : 0u;
 #pragma unroll
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
+    auto park_record = [&](long long grp, const uint4 (&rec)[W4], int* dst) {
+        const bool act = grp * 64 + lane < M;
+        uint32_t flat[4 * W4];
+#pragma unroll
+        for (int q = 0; q < W4; ++q) {
+            flat[4 * q + 0] = rec[q].x;
+            flat[4 * q + 1] = rec[q].y;
+            flat[4 * q + 2] = rec[q].z;
+            flat[4 * q + 3] = rec[q].w;
+        }
+#pragma unroll
+        for (int n = 0; n < N; ++n) dst[n * 64 + lane] = act ? (int)flat[n] : 0;
+        dst[N * 64 + lane] = act ? (int)flat[N] : 0;
+    };
 
-    uint4 rec[W4];
     long long group = (long long)blockIdx.x * kMfmaWaves + wave;
-    if (group < n_groups) load_record(group, rec);
+    if (group < n_groups) {
+        __amdgpu_buffer_rsrc_t rsrc_A[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n) rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
 
-    for (; group < n_groups; group += group_stride) {
-        // park the 64 records (struct of arrays) for this wave
-        const bool full = (group + 1) * 64 <= M;
+        // fill the pipeline: records of this wave's first two groups, rows of the first three tiles
+        uint4 rec[W4];
         {
-            const bool act = full || group * 64 + lane < M;
-            uint32_t flat[4 * W4];
-#pragma unroll
-            for (int q = 0; q < W4; ++q) {
-                flat[4 * q + 0] = rec[q].x;
-                flat[4 * q + 1] = rec[q].y;
-                flat[4 * q + 2] = rec[q].z;
-                flat[4 * q + 3] = rec[q].w;
-            }
-#pragma unroll
-            for (int n = 0; n < N; ++n) sidx[n * 64 + lane] = act ? (int)flat[n] : 0;
-            sval[lane] = act ? __uint_as_float(flat[N]) : 0.0f;
+            uint4 rec0[W4];
+            load_record(group, rec0);
+            load_record(group + group_stride, rec);
+            park_record(group, rec0, sbuf);
         }
         lds_wave_sync();
-        auto issue_next = [&]() {
-            if (group + group_stride < n_groups) load_record(group + group_stride, rec);
+#pragma unroll
+        for (int t = 0; t < 3; ++t) gather_rows<N>(rsrc_A, sbuf, t, c, g4, st.ring[t]);
+
+        // One group: park the next group's records (requested a whole group ago), request the
+        // records of the group after it, then the four tiles.
+        auto one_group = [&](long long grp, int parity) {
+            int* scur = sbuf + parity * kRecFloats;
+            int* snxt = sbuf + (parity ^ 1) * kRecFloats;
+            park_record(grp + group_stride, rec, snxt);
+            load_record(grp + 2 * group_stride, rec);
+            lds_wave_sync();
+            const long long left = M - grp * 64;
+            process_group<N>(g, st, left < 64 ? (int)left : 64, hot, scur, snxt, tbuf, c, g4);
         };
-        if (full)
-            process_group<N, false>(g, st, group, hot, sidx, sval, tbuf, c, g4, issue_next);
-        else
-            process_group<N, true>(g, st, group, hot, sidx, sval, tbuf, c, g4, issue_next);
+        // The first group is peeled off the loop: the loop proper is then entered with the same
+        // sequence of outstanding memory operations as its own back edge, and the compiler's
+        // wait counts in the steady state are exact instead of the minimum over both entries.
+        one_group(group, 0);
+        group += group_stride;
+        for (int parity = 1; group < n_groups; group += group_stride, parity ^= 1) one_group(group, parity);
     }
 
     // rows 0..15 of each mode: from the wave's accumulators into the workgroup's LDS table
