@@ -78,6 +78,7 @@ struct ftk_ctx {
     int tiled_waves = 8;
     size_t tiled_lds_bytes = 0;
     int hot_K[kMaxOrder] = {};
+    int hot_top[kMaxOrder] = {};   // 16 where rows 0..15 of the mode go through the one-hot matrix product, else 0
     int hot_off[kMaxOrder] = {};
     int hot_H = 0;            // rows in the LDS table for the current |Psi|
     int hot_H_max = 0;        // rows the LDS budget allows (partial tables are sized for this)
@@ -230,7 +231,7 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
         g.A_off[n] = c->L.A_off[n];
         g.B_off[n] = c->L.B_off[n];
         g.K[n] = c->hot_K[n];
-        g.top[n] = c->hot_K[n] >= 16 ? 16 : 0;
+        g.top[n] = c->hot_top[n];
         g.row_bytes[n] = (unsigned int)(c->dims[n] * 64);
         g.hot_off[n] = c->hot_off[n];
     }
@@ -290,7 +291,7 @@ int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
         g.B_off[n] = c->L.B_off[n];
         g.J[n] = c->L.J[n];
         g.K[n] = c->hot_K[n];
-        g.top[n] = c->hot_K[n] >= 16 ? 16 : 0;
+        g.top[n] = c->hot_top[n];
         g.hot_off[n] = c->hot_off[n];
         g.mode_bytes[n] = (unsigned int)(c->dims[n] * c->L.J[n] * 4);
     }
@@ -465,6 +466,12 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
         c->hot_K[n] = taken[n];
         c->hot_off[n] = off;
         off += taken[n];
+        // The 16 most frequent rows go through a one-hot matrix product (four more matrix
+        // instructions per tile and mode) only where they collect a fair share of the samples:
+        // at least two of a tile's 16 on average.  Elsewhere they are ordinary table rows.
+        double top_hits = 0.0;
+        for (int r = 0; r < 16 && r < (int)c->dims[n]; ++r) top_hits += (double)c->sorted_counts[n][r];
+        c->hot_top[n] = (taken[n] >= 16 && top_hits * 8.0 >= (double)c->nnz) ? 16 : 0;
     }
     c->hot_H = std::max(off, 1);
     c->mfma_lds_bytes = 4 * ((size_t)c->hot_H * 16 + kMfmaWaves * mfma16_wave_scratch(N) + N * 256);
@@ -497,8 +504,8 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     c->L.B_total = b_off;
     pick_generic_config(c);
     c->mfma16_ok = c->L.R == 16 && N <= 6 && c->max_lds >= 131072;
-    for (int n = 0; n < N; ++n)   // 16-float rows, addressed with 32-bit element offsets inside a mode
-        c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16 && dims[n] < (1LL << 25);
+    for (int n = 0; n < N; ++n)   // 16-float rows whose byte offset inside a mode fits 30 bits
+        c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16 && dims[n] < (1LL << 24);
     {
         int pm = c->L.R;
         c->tiled_ok = N <= 8 && c->L.R <= 64 && c->max_lds >= 131072;

@@ -50,10 +50,21 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kMfmaWaves = 8;                  // waves per workgroup (one workgroup per CU)
 constexpr int kMfmaThreads = kMfmaWaves * 64;
 constexpr int kTransposeFloats = 16 * 20;      // 16x16 tile, rows padded to 20 floats
+// One parked group of 64 samples, per wave, in 32-bit words:
+//   [N][64] row words | [N][64] LDS-cell words | [64] values | [16] pending masks
+__host__ __device__ constexpr int mfma16_group_words(int order) { return (2 * order + 1) * 64 + 16; }
 __host__ __device__ constexpr int mfma16_wave_scratch(int order) {
-    // floats per wave: two buffers of (N index columns + values of 64 samples) | one transpose buffer per mode
-    return 2 * (order + 1) * 64 + order * kTransposeFloats;
+    // floats per wave: two parked groups | one transpose buffer per mode | 64 words that hold +inf
+    return 2 * mfma16_group_words(order) + order * kTransposeFloats + 64;
 }
+
+// A row word says everything the tile loop needs to know about one (sample, mode):
+//   bits 0..29  row * 64, the byte offset of the row inside its mode (rows < 2^24)
+//   bits 30..31 route of its gradient: 0 global atomic, 1 LDS table, 2 one of the 16 most frequent rows
+// Added to a lane's column offset it is the atomic's address, and any route but 0 puts that address
+// past the end of the mode's buffer, where the hardware drops the request.
+constexpr unsigned int kRouteShift = 30;
+constexpr unsigned int kRowMask = (1u << kRouteShift) - 1u;
 
 struct Mfma16Args {
     Coo coo;
@@ -98,6 +109,18 @@ __device__ __forceinline__ void lds_float_add(float* p, float v) {
     } while (seen != expect);
 }
 
+// LDS accessed by its 32-bit address (what the parked cell words hold).
+typedef __attribute__((address_space(3))) unsigned int lds_u32;
+__device__ __forceinline__ unsigned int lds_address(const void* p) {
+    return (unsigned int)(uintptr_t)reinterpret_cast<const __attribute__((address_space(3))) char*>(
+        (const __attribute__((address_space(3))) void*)p);
+}
+__device__ __forceinline__ unsigned int lds_cas(unsigned int addr, unsigned int expect, unsigned int desired) {
+    lds_u32* q = (lds_u32*)(uintptr_t)addr;
+    __atomic_compare_exchange_n(q, &expect, desired, false, __ATOMIC_RELAXED, __ATOMIC_RELAXED);
+    return expect;   // the value that was there
+}
+
 // Everything a wave keeps across tiles.
 template <int N>
 struct WaveState {
@@ -116,37 +139,42 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
 // Issue the row gather of tile `t` (0..3) of the group parked at `sbuf` into a ring slot:
 // layout X, lane (c, g) reads bytes [16g, 16g + 16) of sample c's row.
 template <int N>
-__device__ __forceinline__ void gather_rows(const __amdgpu_buffer_rsrc_t (&rsrc_A)[N], const int* sbuf, int t, int c,
-                                            int g4, floatx4 (&dst)[N]) {
+__device__ __forceinline__ void gather_rows(const __amdgpu_buffer_rsrc_t (&rsrc_A)[N], const unsigned int* sbuf, int t,
+                                            int c, int g4, floatx4 (&dst)[N]) {
     typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 #pragma unroll
     for (int n = 0; n < N; ++n) {
-        const int row = sbuf[n * 64 + t * 16 + c];
-        const uintx4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc_A[n], row * 64 + g4 * 16, 0, 0);
+        const unsigned int word = sbuf[n * 64 + t * 16 + c];
+        const uintx4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc_A[n], (int)((word & kRowMask) | (unsigned int)(g4 * 16)), 0, 0);
         dst[n] = floatx4{__uint_as_float(q[0]), __uint_as_float(q[1]), __uint_as_float(q[2]), __uint_as_float(q[3])};
     }
 }
 
-// One group of 64 samples whose records are parked at `scur` (struct of arrays: N index columns,
-// then the values): four tiles of 16.  While tile t is computed, the rows of tile t + 3 are
-// requested: tile 3 of this group during tile 0, then tiles 0..2 of the wave's next group (parked
-// at `snxt`).  The requests are unconditional, so that the compiler's count of outstanding memory
-// operations is exact; behind a wave's last group the next group is parked as all row 0 and its
-// (unused) rows cost one cached line.
+// One group of 64 samples parked at `scur` (row words, LDS-cell words, values, pending masks):
+// four tiles of 16.  While tile t is computed, the rows of tile t + 3 are requested: tile 3 of
+// this group during tile 0, then tiles 0..2 of the wave's next group (parked at `snxt`).  The
+// requests are unconditional, so that the compiler's count of outstanding memory operations is
+// exact; behind a wave's last group the next group is parked as all row 0 and its (unused) rows
+// cost one cached line.
 // `lim` (1..64) is the number of samples of the group that exist: only the last group of Psi can
 // have fewer than 64.  The others were parked as row 0 / value 0; they run through the arithmetic
 // like any sample, with their error and their regulariser weight forced to zero, so that each of
 // their contributions is an exact zero (added to row 0, wherever row 0 is accumulated).
 template <int N>
-__device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, int lim, float* hot,
-                                              const int* scur, const int* snxt, float* tbuf, int c, int g4) {
+__device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, int lim, unsigned int hot_addr,
+                                              const unsigned int* scur, const unsigned int* snxt, float* tbuf, int c,
+                                              int g4) {
     __amdgpu_buffer_rsrc_t rsrc_A[N], rsrc_dA[N];
 #pragma unroll
     for (int n = 0; n < N; ++n) {
         rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
         rsrc_dA[n] = make_rsrc(g.dA + g.A_off[n], g.row_bytes[n]);
     }
-    const float* sval = reinterpret_cast<const float*>(scur + N * 64);
+    const unsigned int* scell = scur + N * 64;
+    const float* sval = reinterpret_cast<const float*>(scur + 2 * N * 64);
+    const unsigned int* spend = scur + (2 * N + 1) * 64;
+    const unsigned int c4 = (unsigned int)c * 4u;
+    const unsigned int top_key = (2u << kRouteShift) + (unsigned int)c * 64u;   // row word of "row c, one of the top 16"
 
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
@@ -232,50 +260,53 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 #pragma unroll
             for (int v = 0; v < 4; ++v) wY[n][v] = tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c];
 
-        // Factor-row gradients -e GS + lambda_A a, one 64-byte row per 16 lanes, three routes:
-        //   rows [0, top)   summed over the tile by the matrix core against a one-hot operand
-        //   rows [top, K)   added to the workgroup's LDS table (reads, then compare-and-swaps)
-        //   rows [K, I_n)   global float atomics
-        float grad[N][4];
+        // Factor-row gradients -e GS + lambda_A a, one 64-byte row per 16 lanes.  Where each goes was
+        // decided when the group was parked (row word, LDS-cell word, pending mask):
+        //   the 16 most frequent rows  summed over the tile by the matrix core against a one-hot operand
+        //   rows of the LDS table      compare-and-swap float adds
+        //   all other rows             global float atomics
+        // Every lane issues every atomic and every swap.  An atomic whose row takes another route
+        // aims past the end of the buffer and is dropped by the hardware (an unconditional
+        // instruction lets the compiler count outstanding memory operations exactly, so waiting for
+        // prefetched rows never waits for atomics issued after them); a swap whose row takes
+        // another route aims at a word that holds +inf, which absorbs any finite addend, so it
+        // succeeds and changes nothing.
         float lam[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) lam[v] = sub * 16 + 4 * g4 + v < lim ? g.lambda_A : 0.0f;
-        int iY[N][4];
-        unsigned int* cell[N][4];
-        unsigned int seen[N][4];
-        unsigned int pending = 0;
-        // lanes with nothing to add to the LDS table aim their (unconditional) swaps at a word of their own
-        unsigned int* const dummy = reinterpret_cast<unsigned int*>(tbuf + (c + 16 * g4));
+        float grad[N][4];
+        unsigned int rw[N][4], cell[N][4], seen[N][4];
 #pragma unroll
         for (int n = 0; n < N; ++n) {
-            const int4 r = *reinterpret_cast<const int4*>(scur + n * 64 + sub * 16 + 4 * g4);
-            iY[n][0] = r.x;
-            iY[n][1] = r.y;
-            iY[n][2] = r.z;
-            iY[n][3] = r.w;
+            const uint4 r = *reinterpret_cast<const uint4*>(scur + n * 64 + sub * 16 + 4 * g4);
+            const uint4 q = *reinterpret_cast<const uint4*>(scell + n * 64 + sub * 16 + 4 * g4);
+            rw[n][0] = r.x, rw[n][1] = r.y, rw[n][2] = r.z, rw[n][3] = r.w;
+            cell[n][0] = q.x + c4, cell[n][1] = q.y + c4, cell[n][2] = q.z + c4, cell[n][3] = q.w + c4;
+        }
+        const unsigned int pending0 = spend[sub * 4 + g4];
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) grad[n][v] = fmaf(lam[v], aY[n][v], gs[n][v]);
+        if (g.scale != 1.0f) {   // in-place mode adds -lr_A * gradient
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) grad[n][v] *= g.scale;
+        }
+#pragma unroll
+        for (int n = 0; n < N; ++n)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int row = iY[n][v];
-                grad[n][v] = g.scale * fmaf(lam[v], aY[n][v], gs[n][v]);
-                // Every lane issues the atomic; lanes whose row lives in LDS aim past the end of the
-                // buffer, where the hardware drops the request.  An
-                // unconditional instruction lets the compiler count outstanding memory operations
-                // exactly, so waiting for prefetched rows never waits for atomics issued after them.
-                const bool cold = row >= g.K[n];
-                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[n][v], rsrc_dA[n],
-                                                                cold ? (row * 16 + c) * 4 : (int)g.row_bytes[n] + c * 4, 0, 0);
-                const bool in_table = !cold && row >= g.top[n];
-                cell[n][v] = in_table ? reinterpret_cast<unsigned int*>(hot + (uint32_t)((g.hot_off[n] + row) * 16 + c)) : dummy;
-                seen[n][v] = *cell[n][v];
-                if (in_table) pending |= 1u << (n * 4 + v);
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[n][v], rsrc_dA[n], (int)(rw[n][v] + c4), 0, 0);
+                seen[n][v] = *(lds_u32*)(uintptr_t)cell[n][v];
             }
-        }
 #pragma unroll
         for (int n = 0; n < N; ++n)
             if (g.top[n] > 0) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const float onehot = iY[n][k] == c ? 1.0f : 0.0f;
+                    const float onehot = rw[n][k] == top_key ? 1.0f : 0.0f;
                     st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot, grad[n][k], st.Top[n], 0, 0, 0);
                 }
             }
@@ -285,27 +316,41 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 #pragma unroll
             for (int n = 0; n < N; ++n)
                 st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
-        // One compare-and-swap per pending row element; lanes that lose a race go round again.
-        // All swaps of a round are issued before the first result is looked at, so a round costs
-        // one LDS round trip, not one per element.
-        while (pending) {
-            unsigned int got[N][4];
+
+        // One round of swaps, all issued before the first result is looked at.
+        unsigned int got[N][4];
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                got[n][v] = lds_cas(cell[n][v], seen[n][v], __float_as_uint(__uint_as_float(seen[n][v]) + grad[n][v]));
+        __builtin_amdgcn_sched_barrier(0);
+        bool lost = false;
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) lost = lost || got[n][v] != seen[n][v];
+        // Rarely, another wave changed a word between the read and the swap: the lanes that lost
+        // go round again, element by element, for their rows of the LDS table only.
+        if (__builtin_amdgcn_ballot_w64(lost) != 0) {
+            unsigned int pending = 0;
 #pragma unroll
             for (int n = 0; n < N; ++n)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    got[n][v] = atomicCAS(cell[n][v], seen[n][v], __float_as_uint(__uint_as_float(seen[n][v]) + grad[n][v]));
-            __builtin_amdgcn_sched_barrier(0);   // all swaps go out before the first result is waited for
+                    if (got[n][v] != seen[n][v]) pending |= 1u << (n * 4 + v);
+            pending &= pending0;
+            while (pending) {
 #pragma unroll
-            for (int n = 0; n < N; ++n)
+                for (int n = 0; n < N; ++n)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    if (got[n][v] == seen[n][v]) {   // done: never add this element again
-                        pending &= ~(1u << (n * 4 + v));
-                        cell[n][v] = dummy;
-                    }
-                    seen[n][v] = got[n][v];
-                }
+                    for (int v = 0; v < 4; ++v)
+                        if (pending & (1u << (n * 4 + v))) {
+                            const unsigned int expect = got[n][v];
+                            got[n][v] = lds_cas(cell[n][v], expect, __float_as_uint(__uint_as_float(expect) + grad[n][v]));
+                            if (got[n][v] == expect) pending &= ~(1u << (n * 4 + v));
+                        }
+            }
         }
     }
 }
@@ -314,18 +359,20 @@ template <int N>
 __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g) {
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;   // 16-byte words per record
-    constexpr int kRecFloats = (N + 1) * 64;
+    constexpr int kGroupWords = mfma16_group_words(N);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int c = lane & 15, g4 = lane >> 4;
     float* hot = lds;
     float* wave_lds = lds + (size_t)g.H * 16 + wave * mfma16_wave_scratch(N);
-    int* sbuf = reinterpret_cast<int*>(wave_lds);            // two buffers of [N][64] row numbers + [64] values
-    float* tbuf = wave_lds + 2 * kRecFloats;                 // [N][16][20]
+    unsigned int* sbuf = reinterpret_cast<unsigned int*>(wave_lds);   // two parked groups
+    float* tbuf = wave_lds + 2 * kGroupWords;                          // [N][16][20]
+    float* sink = tbuf + N * kTransposeFloats;                         // [64] words of +inf
     float* gbred = lds + (size_t)g.H * 16 + kMfmaWaves * mfma16_wave_scratch(N);
 
     for (int q = tid; q < g.H * 16; q += kMfmaThreads) hot[q] = 0.0f;
     for (int q = tid; q < N * 256; q += kMfmaThreads) gbred[q] = 0.0f;
+    sink[lane] = __uint_as_float(0x7f800000u);
 
     WaveState<N> st;
 #pragma unroll
@@ -347,6 +394,10 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     const long long n_groups = (M + 63) / 64;
     const long long group_stride = (long long)gridDim.x * kMfmaWaves;
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
+    const unsigned int hot_addr = lds_address(hot);
+    // the +inf word this lane's sample uses for swaps that must change nothing: the samples of a
+    // tile that share a quarter g = (sample % 16) / 4 are handled by the 16 lanes (c, g)
+    const unsigned int sink_addr = lds_address(sink) + (unsigned int)(((lane >> 2) & 3) * 64);
 
     // record of sample (group * 64 + lane): N row numbers and the value's bits.  A group past
     // the end of Psi (and a lane past the end of the last group) reads record 0 and is parked
@@ -357,7 +408,9 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
 #pragma unroll
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
-    auto park_record = [&](long long grp, const uint4 (&rec)[W4], int* dst) {
+    // Park a group: per (sample, mode) the row word and the LDS-cell word, the values, and for
+    // each (tile, quarter) the 4 * N bits that say which of its rows live in the LDS table.
+    auto park_record = [&](long long grp, const uint4 (&rec)[W4], unsigned int* dst) {
         const bool act = grp * 64 + lane < M;
         uint32_t flat[4 * W4];
 #pragma unroll
@@ -367,9 +420,20 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
             flat[4 * q + 2] = rec[q].z;
             flat[4 * q + 3] = rec[q].w;
         }
+        unsigned int pend = 0;
+        const int shift = (lane & 15) * 4;   // lanes 0..15 build the mask of (tile, quarter) = (lane / 4, lane % 4)
 #pragma unroll
-        for (int n = 0; n < N; ++n) dst[n * 64 + lane] = act ? (int)flat[n] : 0;
-        dst[N * 64 + lane] = act ? (int)flat[N] : 0;
+        for (int n = 0; n < N; ++n) {
+            const int row = act ? (int)flat[n] : 0;
+            const bool in_table = row >= g.top[n] && row < g.K[n];
+            const unsigned int route = row < g.top[n] ? 2u : in_table ? 1u : 0u;
+            dst[n * 64 + lane] = (unsigned int)row * 64u + (route << kRouteShift);
+            dst[(N + n) * 64 + lane] = in_table ? hot_addr + (unsigned int)(g.hot_off[n] + row) * 64u : sink_addr;
+            const unsigned long long in_table_lanes = __builtin_amdgcn_ballot_w64(in_table);
+            pend |= (unsigned int)((in_table_lanes >> shift) & 15ull) << (4 * n);
+        }
+        dst[2 * N * 64 + lane] = act ? flat[N] : 0u;
+        if (lane < 16) dst[(2 * N + 1) * 64 + lane] = pend;
     };
 
     long long group = (long long)blockIdx.x * kMfmaWaves + wave;
@@ -393,13 +457,13 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
         // One group: park the next group's records (requested a whole group ago), request the
         // records of the group after it, then the four tiles.
         auto one_group = [&](long long grp, int parity) {
-            int* scur = sbuf + parity * kRecFloats;
-            int* snxt = sbuf + (parity ^ 1) * kRecFloats;
+            unsigned int* scur = sbuf + parity * kGroupWords;
+            unsigned int* snxt = sbuf + (parity ^ 1) * kGroupWords;
             park_record(grp + group_stride, rec, snxt);
             load_record(grp + 2 * group_stride, rec);
             lds_wave_sync();
             const long long left = M - grp * 64;
-            process_group<N>(g, st, left < 64 ? (int)left : 64, hot, scur, snxt, tbuf, c, g4);
+            process_group<N>(g, st, left < 64 ? (int)left : 64, hot_addr, scur, snxt, tbuf, c, g4);
         };
         // The first group is peeled off the loop: the loop proper is then entered with the same
         // sequence of outstanding memory operations as its own back edge, and the compiler's
