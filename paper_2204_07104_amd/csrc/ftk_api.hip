@@ -234,7 +234,9 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
         g.top[n] = c->hot_top[n];
         g.row_bytes[n] = (unsigned int)(c->dims[n] * 64);
         g.hot_off[n] = c->hot_off[n];
+        g.first_row[n] = (unsigned int)(c->L.A_off[n] / 16);
     }
+    g.all_bytes = (unsigned int)(c->A_total * 4);
     g.H = c->hot_H;
     g.hot_partial = c->d_hot_partial;
     g.gb_partial = c->d_gb_partial;
@@ -439,12 +441,15 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
         budget_bytes = (long long)c->max_lds - 4LL * (long long)tiled_lds_floats(N, c->tiled_P, c->tiled_waves, 0) - 1024;
         row_bytes = 64LL * c->tiled_P;
     } else {
-        budget_bytes = (long long)c->max_lds - 4LL * (kMfmaWaves * mfma16_wave_scratch(N) + N * 256) - 1024;
+        budget_bytes = (long long)c->max_lds - 4LL * (kMfmaWaves * mfma16_wave_scratch(N) + N * 256 + kSinkRows * 16) - 1024;
         row_bytes = 64;
     }
     c->hot_H_max = (int)std::max(1LL, budget_bytes / row_bytes);
     const int H = (int)std::min<long long>(c->hot_H_max, rows_total);
-    double min_count = 2.0 * (double)c->mfma_grid * (double)c->nnz / (double)std::max<long long>(n_samples, 1);
+    // A table row saves its workgroup one global atomic per hit (~12 ns of a per-CU unit that is the
+    // kernel's bottleneck) and costs one 64-byte store and one read at the end of the step: worth
+    // it from a fraction of an expected hit per workgroup and step.
+    double min_count = 0.25 * (double)c->mfma_grid * (double)c->nnz / (double)std::max<long long>(n_samples, 1);
     if (const char* e = getenv("FTK_HOT_PMIN")) min_count = atof(e) * (double)c->nnz;   // tuning override
     int taken[kMaxOrder] = {};
     for (int t = 0; t < H; ++t) {
@@ -474,7 +479,7 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
         c->hot_top[n] = (taken[n] >= 16 && top_hits * 8.0 >= (double)c->nnz) ? 16 : 0;
     }
     c->hot_H = std::max(off, 1);
-    c->mfma_lds_bytes = 4 * ((size_t)c->hot_H * 16 + kMfmaWaves * mfma16_wave_scratch(N) + N * 256);
+    c->mfma_lds_bytes = 4 * ((size_t)(c->hot_H + kSinkRows) * 16 + kMfmaWaves * mfma16_wave_scratch(N) + N * 256);
     c->tiled_lds_bytes = 4 * tiled_lds_floats(N, c->tiled_P, c->tiled_waves, c->hot_H);
     c->hot_for_M = n_samples;
 }
@@ -506,6 +511,8 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     c->mfma16_ok = c->L.R == 16 && N <= 6 && c->max_lds >= 131072;
     for (int n = 0; n < N; ++n)   // 16-float rows whose byte offset inside a mode fits 30 bits
         c->mfma16_ok = c->mfma16_ok && c->L.J[n] == 16 && dims[n] < (1LL << 24);
+    // the whole packed array is one buffer for the kernel's atomics: 31-bit byte offsets
+    c->mfma16_ok = c->mfma16_ok && c->A_total * 4 < 0x7fffffc0LL;
     {
         int pm = c->L.R;
         c->tiled_ok = N <= 8 && c->L.R <= 64 && c->max_lds >= 131072;

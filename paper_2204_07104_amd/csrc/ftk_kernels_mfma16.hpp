@@ -51,20 +51,30 @@ constexpr int kMfmaWaves = 8;                  // waves per workgroup (one workg
 constexpr int kMfmaThreads = kMfmaWaves * 64;
 constexpr int kTransposeFloats = 16 * 20;      // 16x16 tile, rows padded to 20 floats
 // One parked group of 64 samples, per wave, in 32-bit words:
-//   [N][64] row words | [N][64] LDS-cell words | [64] values | [16] pending masks
-__host__ __device__ constexpr int mfma16_group_words(int order) { return (2 * order + 1) * 64 + 16; }
-__host__ __device__ constexpr int mfma16_wave_scratch(int order) {
-    // floats per wave: two parked groups | one transpose buffer per mode | 64 words that hold +inf
-    return 2 * mfma16_group_words(order) + order * kTransposeFloats + 64;
+//   [N][64] row words | [64] values | [4][4][4N] atomic list | [4][4][4N] table list | [8] list lengths (+8 unused)
+// The lists are per tile and hold, compacted, the (sample, mode) pairs of the tile whose gradient
+// row goes to a global atomic resp. to the workgroup's LDS table; list position p sits at
+// [p % 4][p / 4], so that the 16 lanes of quarter g = p % 4 find their entries side by side.
+__host__ __device__ constexpr int mfma16_list_words(int order) { return 4 * 16 * order; }   // 16 N positions per tile
+__host__ __device__ constexpr int mfma16_group_words(int order) {
+    return (order + 1) * 64 + 2 * mfma16_list_words(order) + 16;
 }
+__host__ __device__ constexpr int mfma16_wave_scratch(int order) {
+    // floats per wave: two parked groups | one transpose buffer per mode
+    return 2 * mfma16_group_words(order) + order * kTransposeFloats;
+}
+constexpr int kSinkRows = 4;   // rows of +inf behind the LDS table (see the scatter stage)
 
-// A row word says everything the tile loop needs to know about one (sample, mode):
+// A row word describes one (sample, mode):
 //   bits 0..29  row * 64, the byte offset of the row inside its mode (rows < 2^24)
 //   bits 30..31 route of its gradient: 0 global atomic, 1 LDS table, 2 one of the 16 most frequent rows
-// Added to a lane's column offset it is the atomic's address, and any route but 0 puts that address
-// past the end of the mode's buffer, where the hardware drops the request.
 constexpr unsigned int kRouteShift = 30;
 constexpr unsigned int kRowMask = (1u << kRouteShift) - 1u;
+// An atomic-list entry is (row number counted over the whole packed parameter array) << 7 | slot,
+// a table-list entry is slot << 20 | byte offset of the row's cell in the LDS table; slot = 16 n + s
+// names the tile's staged gradient row of mode n, sample s.  An unused atomic entry names a row far
+// past the end of the array.
+constexpr unsigned int kNoAtomic = 0xffffff80u;   // slot 0, row far past the end
 
 struct Mfma16Args {
     Coo coo;
@@ -83,6 +93,8 @@ struct Mfma16Args {
     float* hot_partial;       // [gridDim.x][H][16]
     float* gb_partial;        // [gridDim.x][N * 256]
     unsigned int row_bytes[kMaxOrder];   // I_n * 64: size of mode n's rows in A and dA
+    unsigned int all_bytes;              // size of the whole packed A (and dA), below 2^31 - 64
+    unsigned int first_row[kMaxOrder];   // A_off[n] / 16: number of mode n's row 0 counted over the packed array
     float lambda_A;
     float scale;              // 1 (synchronous: the update pass applies -lr_A) or -lr_A (in-place mode)
 };
@@ -164,15 +176,14 @@ template <int N>
 __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, int lim, unsigned int hot_addr,
                                               const unsigned int* scur, const unsigned int* snxt, float* tbuf, int c,
                                               int g4) {
-    __amdgpu_buffer_rsrc_t rsrc_A[N], rsrc_dA[N];
+    __amdgpu_buffer_rsrc_t rsrc_A[N];
 #pragma unroll
-    for (int n = 0; n < N; ++n) {
-        rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
-        rsrc_dA[n] = make_rsrc(g.dA + g.A_off[n], g.row_bytes[n]);
-    }
-    const unsigned int* scell = scur + N * 64;
-    const float* sval = reinterpret_cast<const float*>(scur + 2 * N * 64);
-    const unsigned int* spend = scur + (2 * N + 1) * 64;
+    for (int n = 0; n < N; ++n) rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
+    const __amdgpu_buffer_rsrc_t rsrc_dA = make_rsrc(g.dA, g.all_bytes);
+    const float* sval = reinterpret_cast<const float*>(scur + N * 64);
+    const unsigned int* atomic_list = scur + (N + 1) * 64;
+    const unsigned int* table_list = atomic_list + mfma16_list_words(N);
+    const unsigned int* list_len = table_list + mfma16_list_words(N);
     const unsigned int c4 = (unsigned int)c * 4u;
     const unsigned int top_key = (2u << kRouteShift) + (unsigned int)c * 64u;   // row word of "row c, one of the top 16"
 
@@ -260,30 +271,11 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 #pragma unroll
             for (int v = 0; v < 4; ++v) wY[n][v] = tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c];
 
-        // Factor-row gradients -e GS + lambda_A a, one 64-byte row per 16 lanes.  Where each goes was
-        // decided when the group was parked (row word, LDS-cell word, pending mask):
-        //   the 16 most frequent rows  summed over the tile by the matrix core against a one-hot operand
-        //   rows of the LDS table      compare-and-swap float adds
-        //   all other rows             global float atomics
-        // Every lane issues every atomic and every swap.  An atomic whose row takes another route
-        // aims past the end of the buffer and is dropped by the hardware (an unconditional
-        // instruction lets the compiler count outstanding memory operations exactly, so waiting for
-        // prefetched rows never waits for atomics issued after them); a swap whose row takes
-        // another route aims at a word that holds +inf, which absorbs any finite addend, so it
-        // succeeds and changes nothing.
+        // Factor-row gradients -e GS + lambda_A a (layout Y: one 64-byte row per 16 lanes).
         float lam[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) lam[v] = sub * 16 + 4 * g4 + v < lim ? g.lambda_A : 0.0f;
         float grad[N][4];
-        unsigned int rw[N][4], cell[N][4], seen[N][4];
-#pragma unroll
-        for (int n = 0; n < N; ++n) {
-            const uint4 r = *reinterpret_cast<const uint4*>(scur + n * 64 + sub * 16 + 4 * g4);
-            const uint4 q = *reinterpret_cast<const uint4*>(scell + n * 64 + sub * 16 + 4 * g4);
-            rw[n][0] = r.x, rw[n][1] = r.y, rw[n][2] = r.z, rw[n][3] = r.w;
-            cell[n][0] = q.x + c4, cell[n][1] = q.y + c4, cell[n][2] = q.z + c4, cell[n][3] = q.w + c4;
-        }
-        const unsigned int pending0 = spend[sub * 4 + g4];
 #pragma unroll
         for (int n = 0; n < N; ++n)
 #pragma unroll
@@ -294,22 +286,54 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 #pragma unroll
                 for (int v = 0; v < 4; ++v) grad[n][v] *= g.scale;
         }
+        // Where each row goes was decided when the group was parked:
+        //   the 16 most frequent rows of a mode: summed over the tile by the matrix core against a
+        //     one-hot operand, straight from the registers
+        //   every other row: staged in the wave's LDS buffer (the -e w reads above are done), then
+        //     fetched again through the tile's two compacted lists, four rows per instruction:
+        //     rows of the workgroup's LDS table by compare-and-swap float adds, the rest by global
+        //     float atomics.
+        // A global float atomic instruction costs this chip the same ~110 clocks of a per-CU unit
+        // whether one or all four of its 16-lane rows are in range, so the lists matter: without
+        // them nearly every instruction of every (mode, quarter) would carry at least one such row.
 #pragma unroll
         for (int n = 0; n < N; ++n)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[n][v], rsrc_dA[n], (int)(rw[n][v] + c4), 0, 0);
-                seen[n][v] = *(lds_u32*)(uintptr_t)cell[n][v];
-            }
+            for (int v = 0; v < 4; ++v) tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c] = grad[n][v];
+        lds_wave_sync();
 #pragma unroll
         for (int n = 0; n < N; ++n)
             if (g.top[n] > 0) {
+                const uint4 r = *reinterpret_cast<const uint4*>(scur + n * 64 + sub * 16 + 4 * g4);
+                const unsigned int rw[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const float onehot = rw[n][k] == top_key ? 1.0f : 0.0f;
+                    const float onehot = rw[k] == top_key ? 1.0f : 0.0f;
                     st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot, grad[n][k], st.Top[n], 0, 0, 0);
                 }
             }
+        const int n_atomic = __builtin_amdgcn_readfirstlane((int)list_len[sub]);
+        const int n_table = __builtin_amdgcn_readfirstlane((int)list_len[4 + sub]);
+
+        // Global atomics.  Eight instructions go out whatever the list holds (entries past its end
+        // aim beyond the array and are dropped by the hardware, cheaply): a fixed count lets the
+        // compiler wait for prefetched rows without waiting for atomics issued after them.
+        auto atomics4 = [&](int first) {
+            const uint4 e4 = *reinterpret_cast<const uint4*>(atomic_list + sub * (16 * N) + g4 * (4 * N) + first);
+            const unsigned int e[4] = {e4.x, e4.y, e4.z, e4.w};
+            float val[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) val[i] = tbuf[(e[i] & 127u) * 20u + (unsigned int)c];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val[i], rsrc_dA, (int)(((e[i] >> 1) & ~63u) | c4), 0, 0);
+        };
+        atomics4(0);
+        if (N > 1) atomics4(4);
+#pragma unroll
+        for (int b = 2; b < N; ++b)
+            if (n_atomic > 16 * b) atomics4(4 * b);
+
         // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
@@ -317,41 +341,44 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
             for (int n = 0; n < N; ++n)
                 st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
 
-        // One round of swaps, all issued before the first result is looked at.
-        unsigned int got[N][4];
+        // LDS table, four list positions (16 rows) per batch.  Entries past the end of the list aim
+        // at a row of +inf, which absorbs any finite addend: their swaps succeed and change nothing.
+        auto table4 = [&](int first) {
+            const uint4 e4 = *reinterpret_cast<const uint4*>(table_list + sub * (16 * N) + g4 * (4 * N) + first);
+            const unsigned int e[4] = {e4.x, e4.y, e4.z, e4.w};
+            float val[4];
+            unsigned int cell[4], seen[4], got[4];
 #pragma unroll
-        for (int n = 0; n < N; ++n)
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                got[n][v] = lds_cas(cell[n][v], seen[n][v], __float_as_uint(__uint_as_float(seen[n][v]) + grad[n][v]));
-        __builtin_amdgcn_sched_barrier(0);
-        bool lost = false;
-#pragma unroll
-        for (int n = 0; n < N; ++n)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) lost = lost || got[n][v] != seen[n][v];
-        // Rarely, another wave changed a word between the read and the swap: the lanes that lost
-        // go round again, element by element, for their rows of the LDS table only.
-        if (__builtin_amdgcn_ballot_w64(lost) != 0) {
-            unsigned int pending = 0;
-#pragma unroll
-            for (int n = 0; n < N; ++n)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (got[n][v] != seen[n][v]) pending |= 1u << (n * 4 + v);
-            pending &= pending0;
-            while (pending) {
-#pragma unroll
-                for (int n = 0; n < N; ++n)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (pending & (1u << (n * 4 + v))) {
-                            const unsigned int expect = got[n][v];
-                            got[n][v] = lds_cas(cell[n][v], expect, __float_as_uint(__uint_as_float(expect) + grad[n][v]));
-                            if (got[n][v] == expect) pending &= ~(1u << (n * 4 + v));
-                        }
+            for (int i = 0; i < 4; ++i) {
+                val[i] = tbuf[(e[i] >> 20) * 20u + (unsigned int)c];
+                cell[i] = hot_addr + (e[i] & 0xfffffu) + c4;
+                seen[i] = *(lds_u32*)(uintptr_t)cell[i];
             }
-        }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                got[i] = lds_cas(cell[i], seen[i], __float_as_uint(__uint_as_float(seen[i]) + val[i]));
+            __builtin_amdgcn_sched_barrier(0);   // all four swaps go out before the first result is waited for
+            bool lost = false;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) lost = lost || got[i] != seen[i];
+            // Rarely, another wave (or another quarter of this instruction) changed a word between
+            // the read and the swap: the lanes that lost go round again for their listed rows.
+            if (__builtin_amdgcn_ballot_w64(lost) != 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    bool again = got[i] != seen[i] && (first + i) * 4 + g4 < n_table;
+                    while (again) {
+                        const unsigned int expect = got[i];
+                        got[i] = lds_cas(cell[i], expect, __float_as_uint(__uint_as_float(expect) + val[i]));
+                        again = got[i] != expect;
+                    }
+                }
+            }
+        };
+#pragma unroll
+        for (int b = 0; b < N; ++b)
+            if (n_table > 16 * b) table4(4 * b);
+        lds_wave_sync();   // the next tile overwrites the staged rows
     }
 }
 
@@ -364,15 +391,14 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int c = lane & 15, g4 = lane >> 4;
     float* hot = lds;
-    float* wave_lds = lds + (size_t)g.H * 16 + wave * mfma16_wave_scratch(N);
+    float* wave_lds = lds + (size_t)(g.H + kSinkRows) * 16 + wave * mfma16_wave_scratch(N);
     unsigned int* sbuf = reinterpret_cast<unsigned int*>(wave_lds);   // two parked groups
     float* tbuf = wave_lds + 2 * kGroupWords;                          // [N][16][20]
-    float* sink = tbuf + N * kTransposeFloats;                         // [64] words of +inf
-    float* gbred = lds + (size_t)g.H * 16 + kMfmaWaves * mfma16_wave_scratch(N);
+    float* gbred = lds + (size_t)(g.H + kSinkRows) * 16 + kMfmaWaves * mfma16_wave_scratch(N);
 
     for (int q = tid; q < g.H * 16; q += kMfmaThreads) hot[q] = 0.0f;
+    for (int q = tid; q < kSinkRows * 16; q += kMfmaThreads) hot[g.H * 16 + q] = __uint_as_float(0x7f800000u);
     for (int q = tid; q < N * 256; q += kMfmaThreads) gbred[q] = 0.0f;
-    sink[lane] = __uint_as_float(0x7f800000u);
 
     WaveState<N> st;
 #pragma unroll
@@ -395,9 +421,6 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     const long long group_stride = (long long)gridDim.x * kMfmaWaves;
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
     const unsigned int hot_addr = lds_address(hot);
-    // the +inf word this lane's sample uses for swaps that must change nothing: the samples of a
-    // tile that share a quarter g = (sample % 16) / 4 are handled by the 16 lanes (c, g)
-    const unsigned int sink_addr = lds_address(sink) + (unsigned int)(((lane >> 2) & 3) * 64);
 
     // record of sample (group * 64 + lane): N row numbers and the value's bits.  A group past
     // the end of Psi (and a lane past the end of the last group) reads record 0 and is parked
@@ -408,8 +431,10 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
 #pragma unroll
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
-    // Park a group: per (sample, mode) the row word and the LDS-cell word, the values, and for
-    // each (tile, quarter) the 4 * N bits that say which of its rows live in the LDS table.
+    // Park a group (lane = sample): row words, values, and the two compacted lists of each tile.
+    const int my_tile = lane >> 4, my_s = lane & 15;
+    const unsigned long long tile_lanes = 0xffffull << (16 * my_tile);
+    const unsigned long long lanes_below = tile_lanes & ((1ull << lane) - 1ull);   // of my tile
     auto park_record = [&](long long grp, const uint4 (&rec)[W4], unsigned int* dst) {
         const bool act = grp * 64 + lane < M;
         uint32_t flat[4 * W4];
@@ -420,20 +445,46 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
             flat[4 * q + 2] = rec[q].z;
             flat[4 * q + 3] = rec[q].w;
         }
-        unsigned int pend = 0;
-        const int shift = (lane & 15) * 4;   // lanes 0..15 build the mask of (tile, quarter) = (lane / 4, lane % 4)
+        unsigned int* atomic_list = dst + (N + 1) * 64 + my_tile * (16 * N);
+        unsigned int* table_list = atomic_list + mfma16_list_words(N);
+        // every list position starts out unused: lane (tile, quarter q, j) clears positions [q][j], [q][j+4], ...
+        {
+            const int q = (lane >> 2) & 3, j = lane & 3;
+            const unsigned int unused_cell = (unsigned int)(g.H + q) * 64u;   // a row of +inf, one per quarter
+#pragma unroll
+            for (int i = 0; i < 4 * N; i += 4) {
+                atomic_list[q * (4 * N) + j + i] = kNoAtomic;
+                table_list[q * (4 * N) + j + i] = unused_cell;
+            }
+        }
+        lds_wave_sync();
+        int n_atomic = 0, n_table = 0;   // entries of my tile's lists so far
 #pragma unroll
         for (int n = 0; n < N; ++n) {
             const int row = act ? (int)flat[n] : 0;
-            const bool in_table = row >= g.top[n] && row < g.K[n];
-            const unsigned int route = row < g.top[n] ? 2u : in_table ? 1u : 0u;
+            const bool to_table = row >= g.top[n] && row < g.K[n];
+            const bool to_atomic = row >= g.K[n];
+            const unsigned int route = to_atomic ? 0u : to_table ? 1u : 2u;
             dst[n * 64 + lane] = (unsigned int)row * 64u + (route << kRouteShift);
-            dst[(N + n) * 64 + lane] = in_table ? hot_addr + (unsigned int)(g.hot_off[n] + row) * 64u : sink_addr;
-            const unsigned long long in_table_lanes = __builtin_amdgcn_ballot_w64(in_table);
-            pend |= (unsigned int)((in_table_lanes >> shift) & 15ull) << (4 * n);
+            const unsigned long long atomic_lanes = __builtin_amdgcn_ballot_w64(to_atomic);
+            const unsigned long long table_lanes = __builtin_amdgcn_ballot_w64(to_table);
+            const unsigned int slot = (unsigned int)(n * 16 + my_s);
+            if (to_atomic) {
+                const int p = n_atomic + __popcll(atomic_lanes & lanes_below);
+                atomic_list[(p & 3) * (4 * N) + (p >> 2)] = ((g.first_row[n] + (unsigned int)row) << 7) | slot;
+            }
+            if (to_table) {
+                const int p = n_table + __popcll(table_lanes & lanes_below);
+                table_list[(p & 3) * (4 * N) + (p >> 2)] = (slot << 20) | ((unsigned int)(g.hot_off[n] + row) * 64u);
+            }
+            n_atomic += __popcll(atomic_lanes & tile_lanes);
+            n_table += __popcll(table_lanes & tile_lanes);
         }
-        dst[2 * N * 64 + lane] = act ? flat[N] : 0u;
-        if (lane < 16) dst[(2 * N + 1) * 64 + lane] = pend;
+        dst[N * 64 + lane] = act ? flat[N] : 0u;
+        if (my_s == 0) {
+            dst[(N + 1) * 64 + 2 * mfma16_list_words(N) + my_tile] = (unsigned int)n_atomic;
+            dst[(N + 1) * 64 + 2 * mfma16_list_words(N) + 4 + my_tile] = (unsigned int)n_table;
+        }
     };
 
     long long group = (long long)blockIdx.x * kMfmaWaves + wave;
