@@ -731,7 +731,7 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
             p.hot_parts = c->mfma_grid;
             p.H = c->hot_H;
             p.J = tiled ? 16 * c->tiled_P : 16;
-            p.hot_blocks = (c->hot_H * p.J + 15) / 16;
+            p.hot_blocks = (c->hot_H * p.J + 63) / 64;
             p.order = c->order;
             for (int n = 0; n < kMaxOrder; ++n) {
                 p.Jn[n] = c->L.J[n];
@@ -749,7 +749,7 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
         p.lr_B = lr_B;
         p.lambda_B = lambda_B;
         p.inv_M = 1.0f / (float)c->n_samples;
-        const int b_blocks = (c->L.B_total + 15) / 16;
+        const int b_blocks = (c->L.B_total + 63) / 64;
         Bracket t(c, FTK_K_APPLY);
         hipLaunchKernelGGL(apply_kernel, dim3(p.dense_blocks + p.hot_blocks + b_blocks), dim3(256), 0, c->stream, p);
     }

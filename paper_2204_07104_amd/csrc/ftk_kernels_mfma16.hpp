@@ -639,8 +639,8 @@ __global__ void __launch_bounds__(256) errors_mfma16_kernel(Coo coo, uint64_t nn
 //   blocks [0, dense_blocks)                 A <- A - lr_A dA over the dense accumulator (rows that
 //                                            were updated with global atomics), clearing it
 //   next hot_blocks blocks                   A <- A - lr_A sum_b hot_partial[b] for the rows kept in
-//                                            the workgroups' LDS tables (16 elements per block,
-//                                            16 threads striding over the partial tables of each)
+//                                            the workgroups' LDS tables (64 elements per block,
+//                                            4 threads striding over the partial tables of each)
 //   last B_blocks blocks                     B <- B - lr_B (sum_b GB[b] / M + lambda_B B)
 // ---------------------------------------------------------------------------------------------
 struct ApplyArgs {
@@ -651,7 +651,7 @@ struct ApplyArgs {
     // frequently hit rows
     const float* hot_partial;   // [hot_parts][H][J]
     int hot_parts;
-    int hot_blocks;             // ceil(H * J / 16)
+    int hot_blocks;             // ceil(H * J / 64)
     int H;
     int J;                      // floats per table row (J_n padded to a multiple of 16)
     int Jn[kMaxOrder];          // floats per row of A^(n)
@@ -669,7 +669,7 @@ struct ApplyArgs {
 };
 
 __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
-    __shared__ float red[16][17];
+    __shared__ float red[4][64];
     const int tid = threadIdx.x;
     int blk = (int)blockIdx.x;
     if (blk < p.dense_blocks) {
@@ -690,22 +690,32 @@ __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
         return;
     }
     blk -= p.dense_blocks;
-    const int ql = tid & 15, sub = tid >> 4;
+    // 64 consecutive elements per block (256 contiguous bytes of every partial table), four
+    // threads per element striding over the tables
+    const int ql = tid & 63, sub = tid >> 6;
     const bool is_hot = blk < p.hot_blocks;
     if (!is_hot) blk -= p.hot_blocks;
     const int count = is_hot ? p.H * p.J : p.B_total;
     const int parts = is_hot ? p.hot_parts : p.gb_parts;
     const float* src = is_hot ? p.hot_partial : p.GB;
-    const int q = blk * 16 + ql;
-    float acc = 0.0f;
-    if (q < count)
-        for (int b = sub; b < parts; b += 16) acc += src[(size_t)b * count + q];
-    red[sub][ql] = acc;
-    __syncthreads();
-    if (tid >= 16 || q >= count) return;
-    float total = 0.0f;
+    const int q = blk * 64 + ql;
+    float acc0 = 0.0f, acc1 = 0.0f;
+    if (q < count) {
+        // eight independent loads in flight per thread
+        int b = sub;
+        for (; b + 28 < parts; b += 32) {
+            float t[8];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) total += red[r][tid];
+            for (int u = 0; u < 8; ++u) t[u] = src[(size_t)(b + 4 * u) * count + q];
+            acc0 += (t[0] + t[2]) + (t[4] + t[6]);
+            acc1 += (t[1] + t[3]) + (t[5] + t[7]);
+        }
+        for (; b < parts; b += 4) acc0 += src[(size_t)b * count + q];
+    }
+    red[sub][ql] = acc0 + acc1;
+    __syncthreads();
+    if (tid >= 64 || q >= count) return;
+    const float total = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
     if (is_hot) {
         const int hrow = q / p.J, j = q - hrow * p.J;
         int n = -1;
