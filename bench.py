@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
 # what the same counters read for kernels of known size (profiles/grad_mfma16_C2.txt, section 2)
-MEASURED_TRAFFIC_BYTES = {("C2", "grad:mfma16"): 172.4e6 + 121.8e6}
+MEASURED_TRAFFIC_BYTES = {("C2", "grad:mfma16"): 171.7e6 + 108.8e6}
 FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X fp32 dense matrix (and vector) peak, published
 KERNEL_SLOTS = ["sample_gather", "grad", "apply"]
 
@@ -51,7 +51,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--kernel", default="auto")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the CPU-oracle leg (0: skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target wall time of the CPU-oracle leg (0: skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
