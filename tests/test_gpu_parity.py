@@ -354,6 +354,25 @@ def test_c2_full_size_one_step():
     assert moved_B > 1e-2, moved_B
 
 
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
+def test_other_workloads_full_size_one_step(name):
+    """The other named workloads at full size, on the kernel the library picks for them: the sample
+    set bit-exact and every parameter after one synchronous step against the oracle (up to half a
+    minute of one host core for the 4e6 samples of C3 and the 64 x 64 contractions of C5)."""
+    w = synth.replace(synth.WORKLOADS[name], **TEST_STEP_SIZES[name])
+    announce("%s full size: generating" % name)
+    idx, vals = synth.make_tensor(w)
+    announce("%s full size: step" % name)
+    gA, gB, A, B = one_step_case(w, idx, vals)
+    A0, B0 = oracle_state(w)
+    assert all(np.isfinite(a).all() for a in A + B)
+    moved_A = max(float(np.abs(a.astype(np.float64) - a0).max()) for a, a0 in zip(A, A0))
+    moved_B = max(float(np.abs(b.astype(np.float64) - b0).max()) for b, b0 in zip(B, B0))
+    announce("%s full size: largest change of A %.3e, of B %.3e" % (name, moved_A, moved_B))
+    assert moved_A > 1e-4, moved_A
+    assert moved_B > 1e-4, moved_B
+
+
 # ------------------------------------------------------------------------------------------------
 # in-place (Hogwild) mode: judged on its RMSE curve
 # ------------------------------------------------------------------------------------------------
