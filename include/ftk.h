@@ -135,6 +135,28 @@ int ftk_rmse(ftk_ctx* ctx, double* out);
 int ftk_mae(ftk_ctx* ctx, double* out);
 
 /*
+ * RMSE and MAE of the current parameters on a held-out set Gamma of n_eval entries given as
+ * coordinates + values (Section 5.1: both accuracy measures are taken over a test set Gamma):
+ *   RMSE = sqrt( sum_Gamma (x - xhat)^2 / |Gamma| ),  MAE = sum_Gamma |x - xhat| / |Gamma|.
+ * idx: array of `order` pointers to int32[n_eval] (0-based, the caller's row numbers, struct of
+ * arrays as for ftk_create), vals: fp32[n_eval]; host memory, or device memory if flags has
+ * FTK_PTRS_DEVICE.  Borrowed for the duration of the call only.  Either output may be NULL.
+ * The set is copied to the device, checked and evaluated in one streaming pass; errors are summed
+ * in double.  Waits for the stream.  FTK_EINVAL: n_eval outside 1..2^32-1, NULL idx / vals, an
+ * index outside [0, I_n), unknown flag bits.  FTK_ENOMEM / FTK_EDEVICE as for ftk_create.
+ */
+int ftk_evaluate(ftk_ctx* ctx, int64_t n_eval, const int32_t* const* idx, const float* vals, uint32_t flags,
+                 double* rmse_out, double* mae_out);
+
+/*
+ * Step size of iteration t (t = 0, 1, ...) under the decay the paper trains with (Section 5.1):
+ *   gamma_t = alpha / (1 + beta * t^1.5).
+ * A plain host function: callers pass the result to ftk_sgd_step as lr_A / lr_B.  Returns NaN for
+ * t < 0 or a negative denominator.
+ */
+double ftk_step_size(double alpha, double beta, int64_t t);
+
+/*
  * Copy parameters out / in.  A[n]: host fp32[I_n * J_n] row-major; B[n]: host fp32[J_n * R]
  * row-major.  Either array of pointers may be NULL (skipped), as may single entries.
  */

@@ -27,9 +27,15 @@ FTK_MAX_ORDER = 8
 # every symbol include/ftk.h declares
 SYMBOLS = [
     "ftk_create", "ftk_destroy", "ftk_sample", "ftk_get_samples", "ftk_sgd_step", "ftk_rmse", "ftk_mae",
+    "ftk_evaluate", "ftk_step_size",
     "ftk_get_factors", "ftk_set_factors", "ftk_set_mode", "ftk_set_stream", "ftk_set_timing",
     "ftk_get_timing", "ftk_set_kernel", "ftk_kernel_name", "ftk_last_error",
 ]
+
+
+def ftk_step_size(alpha: float, beta: float, t: int) -> float:
+    """alpha / (1 + beta * t^1.5), evaluated by the library (host function, needs no GPU)."""
+    return float(load().ftk_step_size(float(alpha), float(beta), int(t)))
 
 
 class FtkError(RuntimeError):
@@ -84,6 +90,10 @@ def load():
     L.ftk_rmse.restype = C.c_int
     L.ftk_mae.argtypes = [vp, C.POINTER(C.c_double)]
     L.ftk_mae.restype = C.c_int
+    L.ftk_evaluate.argtypes = [vp, C.c_int64, vp, vp, C.c_uint32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.ftk_evaluate.restype = C.c_int
+    L.ftk_step_size.argtypes = [C.c_double, C.c_double, C.c_int64]
+    L.ftk_step_size.restype = C.c_double
     L.ftk_get_factors.argtypes = [vp, vp, vp]
     L.ftk_get_factors.restype = C.c_int
     L.ftk_set_factors.argtypes = [vp, vp, vp]
@@ -209,6 +219,20 @@ class FastTucker:
         out = C.c_double(0.0)
         self._check(self._L.ftk_mae(self._ctx, C.byref(out)))
         return out.value
+
+    def ftk_evaluate(self, idx: Sequence[np.ndarray], vals: np.ndarray) -> Tuple[float, float]:
+        """(RMSE, MAE) of the current parameters on a held-out set given as host arrays."""
+        if len(idx) != self.order:
+            raise ValueError("idx must hold one array per mode")
+        cols = [np.ascontiguousarray(a, dtype=np.int32) for a in idx]
+        v = np.ascontiguousarray(vals, dtype=np.float32)
+        n_eval = int(v.shape[0])
+        if any(a.shape != (n_eval,) for a in cols):
+            raise ValueError("idx arrays and vals must have the same length")
+        ptrs = (C.c_void_p * self.order)(*[a.ctypes.data for a in cols])
+        rmse, mae = C.c_double(0.0), C.c_double(0.0)
+        self._check(self._L.ftk_evaluate(self._ctx, n_eval, ptrs, v.ctypes.data, 0, C.byref(rmse), C.byref(mae)))
+        return rmse.value, mae.value
 
     def ftk_get_factors(self) -> Tuple[List[np.ndarray], List[np.ndarray]]:
         A = [np.empty((self.dims[n], self.J[n]), dtype=np.float32) for n in range(self.order)]

@@ -351,61 +351,61 @@ int ensure_batch(ftk_ctx* c) {
 }
 
 template <int N>
-void launch_errors_mfma16_n(ftk_ctx* c, const Coo& coo) {
-    const long long groups = (c->nnz + 63) / 64;
+void launch_errors_mfma16_n(ftk_ctx* c, const Coo& coo, long long nnz) {
+    const long long groups = (nnz + 63) / 64;
     const int grid = blocks_for(groups, 4, c->num_cu * 8);
-    hipLaunchKernelGGL(errors_mfma16_kernel<N>, dim3(grid), dim3(256), 0, c->stream, coo, (uint64_t)c->nnz,
+    hipLaunchKernelGGL(errors_mfma16_kernel<N>, dim3(grid), dim3(256), 0, c->stream, coo, (uint64_t)nnz,
                        (const float*)c->d_A, (const float*)c->d_B, c->L, c->d_sums);
 }
 
 template <int N, int P>
-void launch_errors_tiled_np(ftk_ctx* c, const Coo& coo) {
-    const long long groups = (c->nnz + 63) / 64;
+void launch_errors_tiled_np(ftk_ctx* c, const Coo& coo, long long nnz) {
+    const long long groups = (nnz + 63) / 64;
     const int grid = blocks_for(groups, 4, c->num_cu * 8);
     const size_t lds = 4 * ((size_t)N * 256 * P * P + 4 * (size_t)tiled_wave_scratch(N));
     hipFuncSetAttribute(reinterpret_cast<const void*>(errors_tiled_kernel<N, P>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((errors_tiled_kernel<N, P>), dim3(grid), dim3(256), lds, c->stream, coo, (uint64_t)c->nnz,
+    hipLaunchKernelGGL((errors_tiled_kernel<N, P>), dim3(grid), dim3(256), lds, c->stream, coo, (uint64_t)nnz,
                        (const float*)c->d_A, (const float*)c->d_B, c->L, c->d_sums);
 }
 
 template <int N>
-void launch_errors_tiled_n(ftk_ctx* c, const Coo& coo) {
+void launch_errors_tiled_n(ftk_ctx* c, const Coo& coo, long long nnz) {
     switch (c->tiled_P) {
-        case 1: launch_errors_tiled_np<N, 1>(c, coo); break;
-        case 2: launch_errors_tiled_np<N, 2>(c, coo); break;
-        default: launch_errors_tiled_np<N, 4>(c, coo); break;
+        case 1: launch_errors_tiled_np<N, 1>(c, coo, nnz); break;
+        case 2: launch_errors_tiled_np<N, 2>(c, coo, nnz); break;
+        default: launch_errors_tiled_np<N, 4>(c, coo, nnz); break;
     }
 }
 
-int launch_errors(ftk_ctx* c, double* host_sums) {
-    Coo coo{c->d_rec, c->rec_words};
+// Sums of squared and absolute errors over `nnz` packed records (internal row numbers).
+int launch_errors(ftk_ctx* c, Coo coo, long long nnz, double* host_sums) {
     FTK_HIP(c, hipMemsetAsync(c->d_sums, 0, 2 * sizeof(double), c->stream));
     if (c->variant == V_MFMA16 && c->rec_words == 4 * ((c->order + 1 + 3) / 4)) {
         switch (c->order) {
-            case 1: launch_errors_mfma16_n<1>(c, coo); break;
-            case 2: launch_errors_mfma16_n<2>(c, coo); break;
-            case 3: launch_errors_mfma16_n<3>(c, coo); break;
-            case 4: launch_errors_mfma16_n<4>(c, coo); break;
-            case 5: launch_errors_mfma16_n<5>(c, coo); break;
-            default: launch_errors_mfma16_n<6>(c, coo); break;
+            case 1: launch_errors_mfma16_n<1>(c, coo, nnz); break;
+            case 2: launch_errors_mfma16_n<2>(c, coo, nnz); break;
+            case 3: launch_errors_mfma16_n<3>(c, coo, nnz); break;
+            case 4: launch_errors_mfma16_n<4>(c, coo, nnz); break;
+            case 5: launch_errors_mfma16_n<5>(c, coo, nnz); break;
+            default: launch_errors_mfma16_n<6>(c, coo, nnz); break;
         }
     } else if (c->variant == V_TILED && c->rec_words == 4 * ((c->order + 1 + 3) / 4)) {
         switch (c->order) {
-            case 1: launch_errors_tiled_n<1>(c, coo); break;
-            case 2: launch_errors_tiled_n<2>(c, coo); break;
-            case 3: launch_errors_tiled_n<3>(c, coo); break;
-            case 4: launch_errors_tiled_n<4>(c, coo); break;
-            case 5: launch_errors_tiled_n<5>(c, coo); break;
-            case 6: launch_errors_tiled_n<6>(c, coo); break;
-            case 7: launch_errors_tiled_n<7>(c, coo); break;
-            default: launch_errors_tiled_n<8>(c, coo); break;
+            case 1: launch_errors_tiled_n<1>(c, coo, nnz); break;
+            case 2: launch_errors_tiled_n<2>(c, coo, nnz); break;
+            case 3: launch_errors_tiled_n<3>(c, coo, nnz); break;
+            case 4: launch_errors_tiled_n<4>(c, coo, nnz); break;
+            case 5: launch_errors_tiled_n<5>(c, coo, nnz); break;
+            case 6: launch_errors_tiled_n<6>(c, coo, nnz); break;
+            case 7: launch_errors_tiled_n<7>(c, coo, nnz); break;
+            default: launch_errors_tiled_n<8>(c, coo, nnz); break;
         }
     } else {
         const int b_in_lds = (size_t)c->L.B_total * 4 <= 65536 - 256;
         const size_t lds = b_in_lds ? (size_t)c->L.B_total * 4 : 0;
-        const int grid = blocks_for(c->nnz, 256, c->num_cu * 8);
-        hipLaunchKernelGGL(errors_generic_kernel, dim3(grid), dim3(256), lds, c->stream, coo, c->L, (uint64_t)c->nnz,
+        const int grid = blocks_for(nnz, 256, c->num_cu * 8);
+        hipLaunchKernelGGL(errors_generic_kernel, dim3(grid), dim3(256), lds, c->stream, coo, c->L, (uint64_t)nnz,
                            (const float*)c->d_A, (const float*)c->d_B, b_in_lds, c->d_sums);
     }
     FTK_HIP(c, hipGetLastError());
@@ -427,10 +427,9 @@ void release(ftk_ctx* c) {
     delete c;
 }
 
-// Choose which rows are accumulated in LDS for a sample set of n_samples entries: rows expected to
-// be hit at least twice per workgroup per step (below that a private copy saves no atomics and
-// only costs table traffic), most frequent first, as many as the LDS budget allows.  Rows are
-// already sorted by count within a mode, so this is a merge of sorted lists.
+// Choose which rows are accumulated in LDS for a sample set of n_samples entries: most frequent
+// first, down to a fraction of an expected hit per workgroup and step, as many as the LDS budget
+// allows.  Rows are already sorted by count within a mode, so this is a merge of sorted lists.
 void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     const int N = c->order;
     long long rows_total = 0;
@@ -761,7 +760,7 @@ int ftk_rmse(ftk_ctx* c, double* out) {
     if (!c) return FTK_EINVAL;
     if (!out) return fail(c, FTK_EINVAL, "out is NULL");
     double s[2] = {0.0, 0.0};
-    int rc = launch_errors(c, s);
+    int rc = launch_errors(c, Coo{c->d_rec, c->rec_words}, c->nnz, s);
     if (rc != FTK_OK) return rc;
     *out = sqrt(s[0] / (double)c->nnz);
     return FTK_OK;
@@ -771,10 +770,68 @@ int ftk_mae(ftk_ctx* c, double* out) {
     if (!c) return FTK_EINVAL;
     if (!out) return fail(c, FTK_EINVAL, "out is NULL");
     double s[2] = {0.0, 0.0};
-    int rc = launch_errors(c, s);
+    int rc = launch_errors(c, Coo{c->d_rec, c->rec_words}, c->nnz, s);
     if (rc != FTK_OK) return rc;
     *out = s[1] / (double)c->nnz;
     return FTK_OK;
+}
+
+int ftk_evaluate(ftk_ctx* c, int64_t n_eval, const int32_t* const* idx, const float* vals, uint32_t flags,
+                 double* rmse_out, double* mae_out) {
+    if (!c) return FTK_EINVAL;
+    if (n_eval < 1 || n_eval >= (1LL << 32)) return fail(c, FTK_EINVAL, "n_eval %lld outside 1..2^32-1", (long long)n_eval);
+    if (!idx || !vals) return fail(c, FTK_EINVAL, "NULL argument");
+    if (flags & ~(uint32_t)FTK_PTRS_DEVICE) return fail(c, FTK_EINVAL, "unknown flag bits 0x%x", flags);
+    const int N = c->order;
+    for (int n = 0; n < N; ++n)
+        if (!idx[n]) return fail(c, FTK_EINVAL, "idx[%d] is NULL", n);
+    const hipMemcpyKind kind = (flags & FTK_PTRS_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    uint32_t* d_rec = nullptr;
+    uint32_t* d_col = nullptr;
+    struct Guard {
+        uint32_t*& a;
+        uint32_t*& b;
+        ~Guard() {
+            if (a) hipFree(a);
+            if (b) hipFree(b);
+        }
+    } guard{d_rec, d_col};
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    FTK_HIP(c, hipMalloc(&d_rec, (size_t)n_eval * c->rec_words * sizeof(uint32_t)));
+    FTK_HIP(c, hipMalloc(&d_col, (size_t)n_eval * sizeof(uint32_t)));
+    if (c->rec_words != N + 1) FTK_HIP(c, hipMemset(d_rec, 0, (size_t)n_eval * c->rec_words * sizeof(uint32_t)));
+    const int scan_blocks = blocks_for(n_eval, 256, c->num_cu * 8);
+    for (int n = 0; n <= N; ++n) {
+        FTK_HIP(c, hipMemcpy(d_col, n < N ? (const void*)idx[n] : (const void*)vals, (size_t)n_eval * sizeof(uint32_t), kind));
+        if (n < N) {
+            FTK_HIP(c, hipMemset(c->d_flag, 0, sizeof(unsigned int)));
+            hipLaunchKernelGGL(check_range_kernel, dim3(scan_blocks), dim3(256), 0, c->stream, (const int32_t*)d_col,
+                               (uint64_t)n_eval, (int32_t)c->dims[n], c->d_flag);
+            FTK_HIP(c, hipGetLastError());
+            unsigned int bad = 0;
+            FTK_HIP(c, hipMemcpy(&bad, c->d_flag, sizeof bad, hipMemcpyDeviceToHost));
+            if (bad) return fail(c, FTK_EINVAL, "idx[%d] holds %u entries outside [0, %lld)", n, bad, (long long)c->dims[n]);
+        }
+        // row numbers go through the same renumbering as the stored entries; values are copied as bits
+        hipLaunchKernelGGL(pack_records_kernel, dim3(scan_blocks), dim3(256), 0, c->stream, (const uint32_t*)d_col,
+                           (uint64_t)n_eval, n < N ? (const int32_t*)c->d_new_of_old[n] : (const int32_t*)nullptr, d_rec,
+                           c->rec_words, n);
+        FTK_HIP(c, hipGetLastError());
+        FTK_HIP(c, hipStreamSynchronize(c->stream));
+    }
+    double s[2] = {0.0, 0.0};
+    int rc = launch_errors(c, Coo{d_rec, c->rec_words}, n_eval, s);
+    if (rc != FTK_OK) return rc;
+    if (rmse_out) *rmse_out = sqrt(s[0] / (double)n_eval);
+    if (mae_out) *mae_out = s[1] / (double)n_eval;
+    return FTK_OK;
+}
+
+double ftk_step_size(double alpha, double beta, int64_t t) {
+    if (t < 0) return NAN;
+    const double denom = 1.0 + beta * pow((double)t, 1.5);
+    if (!(denom > 0.0)) return NAN;
+    return alpha / denom;
 }
 
 int ftk_get_factors(ftk_ctx* c, float* const* A_out, float* const* B_out) {

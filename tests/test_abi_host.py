@@ -64,6 +64,7 @@ def test_null_context_is_rejected_everywhere():
     assert L.ftk_sgd_step(None, 0.0, 0.0, 0.0, 0.0) == binding.FTK_EINVAL
     assert L.ftk_rmse(None, C.byref(d)) == binding.FTK_EINVAL
     assert L.ftk_mae(None, C.byref(d)) == binding.FTK_EINVAL
+    assert L.ftk_evaluate(None, 1, None, None, 0, C.byref(d), C.byref(d)) == binding.FTK_EINVAL
     assert L.ftk_get_factors(None, None, None) == binding.FTK_EINVAL
     assert L.ftk_set_factors(None, None, None) == binding.FTK_EINVAL
     assert L.ftk_get_samples(None, None) == binding.FTK_EINVAL
@@ -82,3 +83,16 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "ftk_oracle" not in text, f
+
+
+def test_step_size_schedule_values():
+    """gamma_t = alpha / (1 + beta t^1.5) (Section 5.1): exact where t^1.5 is an integer."""
+    import math
+    assert binding.ftk_step_size(0.009, 0.1, 0) == 0.009                      # t = 0: alpha itself
+    assert math.isclose(binding.ftk_step_size(0.009, 0.1, 4), 0.009 / 1.8, rel_tol=1e-15)    # 4^1.5 = 8
+    assert math.isclose(binding.ftk_step_size(2.0, 0.5, 9), 2.0 / 14.5, rel_tol=1e-15)       # 9^1.5 = 27
+    assert binding.ftk_step_size(1.0, 0.0, 1000) == 1.0                      # beta = 0: constant
+    seq = [binding.ftk_step_size(0.005, 0.05, t) for t in range(50)]
+    assert all(a > b > 0.0 for a, b in zip(seq, seq[1:]))                    # strictly decreasing, positive
+    assert math.isnan(binding.ftk_step_size(1.0, 1.0, -1))
+    assert math.isnan(binding.ftk_step_size(1.0, -1.0, 1))                   # denominator 0

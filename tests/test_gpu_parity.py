@@ -261,6 +261,42 @@ def test_rmse_and_mae_match_oracle():
         assert ma == pytest.approx(want_ma, rel=1e-5)
 
 
+@pytest.mark.parametrize("order,dims,J,R", [
+    (3, (700, 500, 90), (16, 16, 16), 16),      # matrix-core kernel for J = R = 16
+    (3, (300, 200, 50), (24, 40, 9), 20),       # tiled kernel, padded ranks
+    (4, (60, 50, 40, 30), (8, 8, 8, 8), 8),
+    (2, (900, 800), (80, 3), 70),               # generic kernel
+])
+def test_held_out_set_evaluation_matches_oracle(order, dims, J, R):
+    """ftk_evaluate on entries that are NOT the stored ones (other seed, other length, ragged tail)
+    after two steps of training, against the oracle's error sums over the same entries."""
+    announce("held-out evaluation order=%d J=%r R=%d" % (order, J, R))
+    w = synth.tiny_workload(order, dims, 30_000, J, R, 4_000, seed=5, values="normal")
+    w = synth.replace(w, lr_A=1e-5, lr_B=1e-5)    # two steps that lower the error on every one of the shapes
+    idx, vals = synth.make_tensor(w)
+    held = synth.replace(w, nnz=12_345, data_seed=w.data_seed + 77)
+    hidx, hvals = synth.make_tensor(held)
+    A, B = oracle_state(w)
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
+        for t in range(2):
+            ft.ftk_sample(w.sample_seed0 + t, w.n_samples)
+            ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+            pos = oracle.sample_positions(w.sample_seed0 + t, w.n_samples, w.nnz)
+            oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+        got_rmse, got_mae = ft.ftk_evaluate(hidx, hvals)
+        # a row number outside the mode is refused, and the context stays usable
+        bad = [a.copy() for a in hidx]
+        bad[order - 1][17] = dims[order - 1]
+        with pytest.raises(binding.FtkError) as e:
+            ft.ftk_evaluate(bad, hvals)
+        assert e.value.code == binding.FTK_EINVAL
+        again = ft.ftk_evaluate(hidx, hvals)
+    want_rmse, want_mae = oracle.errors(w.dims, hidx, hvals, A, B)
+    assert abs(got_rmse - want_rmse) <= 1e-4 * want_rmse, (got_rmse, want_rmse)
+    assert abs(got_mae - want_mae) <= 1e-4 * want_mae, (got_mae, want_mae)
+    assert again == (got_rmse, got_mae)
+
+
 def test_call_order_and_bad_input_errors():
     announce("error paths")
     w = synth.tiny_workload(3, (10, 10, 10), 100, (2, 2, 2), 2, 10)
