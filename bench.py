@@ -51,6 +51,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--kernel", default="auto")
+    ap.add_argument("--sampling", default="entries", choices=["entries", "tiles"],
+                    help="rule Psi is drawn by; 'tiles' is the library's variant rule (not the headline metric)")
+    ap.add_argument("--mode", default="sync", choices=["sync", "hogwild"],
+                    help="'hogwild' times the in-place mode (not the headline metric)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target wall time of the CPU-oracle leg (0: skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -78,6 +82,10 @@ def main() -> int:
     ft.ftk_set_stream(stream.cuda_stream)
     if args.kernel != "auto":
         ft.ftk_set_kernel(args.kernel)
+    if args.sampling == "tiles":
+        ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
+    if args.mode == "hogwild":
+        ft.ftk_set_mode(binding.FTK_HOGWILD)
     print("[bench] context ready, gradient kernel = %s" % ft.ftk_kernel_name(), file=sys.stderr, flush=True)
 
     def run_steps(first: int, count: int) -> None:
@@ -173,8 +181,10 @@ def main() -> int:
         "value": value, "unit": "nonzeros/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: order-%d COO %s, nnz=%d, J=%s, R=%d, |Psi|=%d per step, synchronous step"
-                               % (w.name, w.order, "x".join(str(d) for d in w.dims), w.nnz, list(w.J), w.R, w.n_samples),
+        "config": {"workload": "%s: order-%d COO %s, nnz=%d, J=%s, R=%d, |Psi|=%d per step, %s step%s"
+                               % (w.name, w.order, "x".join(str(d) for d in w.dims), w.nnz, list(w.J), w.R, w.n_samples,
+                                  "synchronous" if args.mode == "sync" else "in-place (Hogwild)",
+                                  "" if args.sampling == "entries" else ", tile-sampling variant"),
                    "kernel": roofline["kernel"], "rmse_after": rmse_after, "datagen_s": round(t_gen, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

@@ -163,6 +163,25 @@ double ftk_step_size(double alpha, double beta, int64_t t);
 int ftk_get_factors(ftk_ctx* ctx, float* const* A_out, float* const* B_out);
 int ftk_set_factors(ftk_ctx* ctx, const float* const* A_in, const float* const* B_in);
 
+/*
+ * How ftk_sample draws Psi.  The paper only says that Psi is selected at random from Omega
+ * (Section 4.1); two rules are built:
+ * FTK_SAMPLE_ENTRIES (default): M positions i.i.d. uniform over the stored entries, see ftk_sample.
+ * FTK_SAMPLE_TILES: Psi is made of runs of 64 entries that are neighbours in a pseudo-random order
+ *   of Omega fixed by nnz alone, so that each run is one contiguous read: stored place q holds the
+ *   caller's entry pi(q) = (a q + b) mod nnz with b = floor(nnz / 3) and a the largest integer
+ *   <= max(1, floor(nnz * 618034 / 1000000)) coprime to nnz; group g = k / 64 draws its run T_g with
+ *   the entry rule (same seed, sample number g) among ceil(nnz / 64) runs, and sample k is the
+ *   caller's entry pi((64 T_g + k mod 64) mod nnz).  Samples of a run are distinct entries but the
+ *   runs overlap nowhere or completely, so Psi is less random than under the default rule; every
+ *   entry is still equally likely (exactly, when 64 divides nnz).  The first switch to this rule
+ *   allocates a second copy of the stored entries.  ftk_get_samples reports positions in the
+ *   caller's numbering under either rule.
+ * Takes effect at the next ftk_sample / ftk_sgd_step.  FTK_EINVAL for an unknown rule.
+ */
+enum { FTK_SAMPLE_ENTRIES = 0, FTK_SAMPLE_TILES = 1 };
+int ftk_set_sampling(ftk_ctx* ctx, int rule);
+
 /* FTK_SYNC (default) or FTK_HOGWILD. */
 int ftk_set_mode(ftk_ctx* ctx, int mode);
 

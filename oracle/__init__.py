@@ -50,6 +50,10 @@ def lib():
         L.fto_philox4x32_10.restype = None
         L.fto_sample_positions.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_void_p]
         L.fto_sample_positions.restype = C.c_int
+        L.fto_sample_positions_tiles.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_void_p]
+        L.fto_sample_positions_tiles.restype = C.c_int
+        L.fto_tile_order_constants.argtypes = [C.c_int64, C.c_void_p, C.c_void_p]
+        L.fto_tile_order_constants.restype = C.c_int
         L.fto_init_uniform.argtypes = [C.c_uint64, C.c_int32, C.c_int64, C.c_void_p]
         L.fto_init_uniform.restype = C.c_int
         L.fto_nonzero_terms.argtypes = [C.c_int32, C.c_void_p, C.c_int32, _pp_f, _pp_f,
@@ -99,6 +103,22 @@ def sample_positions(seed: int, n_samples: int, nnz: int) -> np.ndarray:
     if rc:
         raise ValueError("fto_sample_positions failed: %d" % rc)
     return pos
+
+
+def tile_order_constants(nnz: int) -> Tuple[int, int]:
+    """(a, b) of the fixed pseudo-random order pi(q) = (a q + b) mod nnz used by tile sampling."""
+    a, b = C.c_int64(0), C.c_int64(0)
+    if lib().fto_tile_order_constants(nnz, C.addressof(a), C.addressof(b)):
+        raise ValueError("fto_tile_order_constants failed")
+    return a.value, b.value
+
+
+def sample_positions_tiles(seed: int, n_samples: int, nnz: int) -> np.ndarray:
+    """Psi under the tile-sampling variant: runs of 64 neighbours in the order pi (caller's positions)."""
+    out = np.empty(n_samples, dtype=np.int64)
+    if lib().fto_sample_positions_tiles(seed & (2**64 - 1), n_samples, nnz, out.ctypes.data):
+        raise ValueError("fto_sample_positions_tiles failed")
+    return out
 
 
 def init_uniform(init_seed: int, array_id: int, shape) -> np.ndarray:

@@ -158,6 +158,47 @@ int fto_sample_positions(uint64_t seed, int64_t n_samples, int64_t nnz, int64_t*
     return 0;
 }
 
+// Tile sampling, a VARIANT of the rule above (the paper only says Psi is drawn at random from
+// Omega, Section 4.1): Psi is made of whole runs of 64 entries that are neighbours in a fixed
+// pseudo-random order of Omega, so that a run can be fetched with one contiguous read.
+//   order of Omega:   stored place q holds the caller's entry  pi(q) = (a q + b) mod nnz,
+//                     b = floor(nnz / 3),  a = the largest integer <= max(1, floor(nnz * 618034 / 1000000))
+//                     with gcd(a, nnz) = 1  (so pi is a bijection of [0, nnz))
+//   run of group g:   T_g = the position the entry rule above draws for sample g among
+//                     n_runs = ceil(nnz / 64) places (same seed, counter g / 2, halves by parity of g)
+//   sample k:         g = k / 64,  q_k = (64 T_g + k mod 64) mod nnz,  p_k = pi(q_k)
+int fto_tile_order_constants(int64_t nnz, int64_t* a_out, int64_t* b_out) {
+    if (nnz < 1 || !a_out || !b_out) return -1;
+    uint64_t a = (uint64_t)nnz * 618034ull / 1000000ull;   // nnz < 2^32: no overflow
+    if (a < 1) a = 1;
+    for (; a > 1; --a) {
+        uint64_t x = a, y = (uint64_t)nnz;
+        while (y) {
+            const uint64_t t = x % y;
+            x = y;
+            y = t;
+        }
+        if (x == 1) break;
+    }
+    *a_out = (int64_t)a;
+    *b_out = nnz / 3;
+    return 0;
+}
+
+int fto_sample_positions_tiles(uint64_t seed, int64_t n_samples, int64_t nnz, int64_t* pos_out) {
+    if (n_samples < 0 || nnz < 1 || nnz >= (1ll << 32) || !pos_out) return -1;
+    int64_t a = 0, b = 0;
+    fto_tile_order_constants(nnz, &a, &b);
+    const uint64_t n_runs = ((uint64_t)nnz + 63) / 64;
+    for (int64_t k = 0; k < n_samples; ++k) {
+        const uint64_t g = (uint64_t)k / 64;
+        const uint64_t run = sample_position(seed, g, n_runs);
+        const uint64_t q = (64 * run + (uint64_t)k % 64) % (uint64_t)nnz;
+        pos_out[k] = (int64_t)(((uint64_t)a * q + (uint64_t)b) % (uint64_t)nnz);   // a, q < 2^32
+    }
+    return 0;
+}
+
 // Initial parameters U[0, 0.5): element q of parameter array `array_id`
 // (n for A^(n), N + n for B^(n)) is 0.5 * 2^-24 * (top 24 bits of word 0 of
 // Philox(counter = (lo32 q, hi32 q, array_id, 1), key = init_seed)).

@@ -21,13 +21,14 @@ LIB_PATH = os.environ.get("FTK_LIB") or os.path.join(HERE, "libftk.so")
 FTK_OK, FTK_EINVAL, FTK_ENOMEM, FTK_EDEVICE, FTK_ESTATE, FTK_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 FTK_PTRS_HOST, FTK_PTRS_DEVICE = 0, 1
 FTK_SYNC, FTK_HOGWILD = 0, 1
+FTK_SAMPLE_ENTRIES, FTK_SAMPLE_TILES = 0, 1
 FTK_K_SAMPLE, FTK_K_GRAD, FTK_K_APPLY, FTK_K_COUNT = 0, 1, 2, 3
 FTK_MAX_ORDER = 8
 
 # every symbol include/ftk.h declares
 SYMBOLS = [
     "ftk_create", "ftk_destroy", "ftk_sample", "ftk_get_samples", "ftk_sgd_step", "ftk_rmse", "ftk_mae",
-    "ftk_evaluate", "ftk_step_size",
+    "ftk_evaluate", "ftk_step_size", "ftk_set_sampling",
     "ftk_get_factors", "ftk_set_factors", "ftk_set_mode", "ftk_set_stream", "ftk_set_timing",
     "ftk_get_timing", "ftk_set_kernel", "ftk_kernel_name", "ftk_last_error",
 ]
@@ -98,6 +99,8 @@ def load():
     L.ftk_get_factors.restype = C.c_int
     L.ftk_set_factors.argtypes = [vp, vp, vp]
     L.ftk_set_factors.restype = C.c_int
+    L.ftk_set_sampling.argtypes = [vp, C.c_int]
+    L.ftk_set_sampling.restype = C.c_int
     L.ftk_set_mode.argtypes = [vp, C.c_int]
     L.ftk_set_mode.restype = C.c_int
     L.ftk_set_stream.argtypes = [vp, vp]
@@ -261,6 +264,9 @@ class FastTucker:
             keep.append(B)
         self._check(self._L.ftk_set_factors(self._ctx, C.cast(pa, C.c_void_p) if pa is not None else None,
                                             C.cast(pb, C.c_void_p) if pb is not None else None))
+
+    def ftk_set_sampling(self, rule: int) -> None:
+        self._check(self._L.ftk_set_sampling(self._ctx, int(rule)))
 
     def ftk_set_mode(self, mode: int) -> None:
         self._check(self._L.ftk_set_mode(self._ctx, int(mode)))

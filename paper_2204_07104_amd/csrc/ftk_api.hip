@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <numeric>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -77,6 +78,9 @@ struct ftk_ctx {
     int tiled_P = 1;          // ranks padded to 16 * tiled_P
     int tiled_waves = 8;
     size_t tiled_lds_bytes = 0;
+    int sampling = FTK_SAMPLE_ENTRIES;
+    uint32_t* d_rec_tiles = nullptr;   // the records in the order of the tile-sampling rule (built on first use)
+    uint64_t tile_a = 1, tile_b = 0;
     int hot_K[kMaxOrder] = {};
     int hot_top[kMaxOrder] = {};   // 16 where rows 0..15 of the mode go through the one-hot matrix product, else 0
     int hot_off[kMaxOrder] = {};
@@ -180,6 +184,19 @@ void pick_generic_config(ftk_ctx* c) {
         }
 }
 
+// The sampling rule in force and the record array it reads.
+SampleRule sample_rule(const ftk_ctx* c) {
+    SampleRule r;
+    r.nnz = (uint64_t)c->nnz;
+    r.n_runs = c->sampling == FTK_SAMPLE_TILES ? ((uint64_t)c->nnz + 63) / 64 : 0;
+    r.a = c->tile_a;
+    r.b = c->tile_b;
+    return r;
+}
+Coo sampled_records(const ftk_ctx* c) {
+    return Coo{c->sampling == FTK_SAMPLE_TILES ? c->d_rec_tiles : c->d_rec, c->rec_words};
+}
+
 int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A) {
     const bool in_place = c->mode == FTK_HOGWILD;
     GradArgs g;
@@ -219,8 +236,8 @@ int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
 int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
     const bool in_place = c->mode == FTK_HOGWILD;
     Mfma16Args g;
-    g.coo = Coo{c->d_rec, c->rec_words};
-    g.nnz = (uint64_t)c->nnz;
+    g.coo = sampled_records(c);
+    g.rule = sample_rule(c);
     g.seed = c->sample_seed;
     g.M = c->n_samples;
     g.A = c->d_A;
@@ -279,8 +296,8 @@ int launch_tiled_n(ftk_ctx* c, const TiledArgs& g) {
 int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
     const bool in_place = c->mode == FTK_HOGWILD;
     TiledArgs g;
-    g.coo = Coo{c->d_rec, c->rec_words};
-    g.nnz = (uint64_t)c->nnz;
+    g.coo = sampled_records(c);
+    g.rule = sample_rule(c);
     g.seed = c->sample_seed;
     g.M = c->n_samples;
     g.A = c->d_A;
@@ -338,12 +355,11 @@ int ensure_batch(ftk_ctx* c) {
         FTK_HIP(c, hipMalloc(&c->d_bval, (size_t)cap * sizeof(float)));
         c->cap = cap;
     }
-    Coo coo{c->d_rec, c->rec_words};
     {
         Bracket t(c, FTK_K_SAMPLE);
-        hipLaunchKernelGGL(sample_gather_kernel, dim3((unsigned)((n_samples + 255) / 256)), dim3(256), 0, c->stream, coo,
-                           c->order, (uint64_t)c->nnz, c->sample_seed, (long long)n_samples, c->cap, c->d_pos,
-                           c->d_bidx, c->d_bval);
+        hipLaunchKernelGGL(sample_gather_kernel, dim3((unsigned)((n_samples + 255) / 256)), dim3(256), 0, c->stream,
+                           sampled_records(c), c->order, sample_rule(c), c->sample_seed, (long long)n_samples, c->cap,
+                           c->d_pos, c->d_bidx, c->d_bval);
     }
     FTK_HIP(c, hipGetLastError());
     c->batch_valid = true;
@@ -420,7 +436,7 @@ void release(ftk_ctx* c) {
     drop_pending(c);
     for (int n = 0; n < kMaxOrder; ++n)
         if (c->d_new_of_old[n]) hipFree(c->d_new_of_old[n]);
-    void* ptrs[] = {c->d_rec, c->d_stage, c->d_A, c->d_dA, c->d_B, c->d_GB, c->d_sums, c->d_flag,
+    void* ptrs[] = {c->d_rec, c->d_rec_tiles, c->d_stage, c->d_A, c->d_dA, c->d_B, c->d_GB, c->d_sums, c->d_flag,
                     c->d_pos, c->d_bidx, c->d_bval, c->d_hot_partial, c->d_gb_partial};
     for (void* p : ptrs)
         if (p) hipFree(p);
@@ -871,6 +887,32 @@ int ftk_set_factors(ftk_ctx* c, const float* const* A_in, const float* const* B_
                                       hipMemcpyHostToDevice, c->stream));
     }
     FTK_HIP(c, hipStreamSynchronize(c->stream));
+    return FTK_OK;
+}
+
+int ftk_set_sampling(ftk_ctx* c, int rule) {
+    if (!c) return FTK_EINVAL;
+    if (rule != FTK_SAMPLE_ENTRIES && rule != FTK_SAMPLE_TILES) return fail(c, FTK_EINVAL, "unknown sampling rule %d", rule);
+    if (rule == FTK_SAMPLE_TILES && !c->d_rec_tiles) {
+        // first use: the order pi(q) = (a q + b) mod nnz and a second copy of the records in it
+        uint64_t a = (uint64_t)c->nnz * 618034ull / 1000000ull;
+        if (a < 1) a = 1;
+        while (a > 1 && std::gcd(a, (uint64_t)c->nnz) != 1) --a;
+        c->tile_a = a;
+        c->tile_b = (uint64_t)c->nnz / 3;
+        FTK_HIP(c, hipStreamSynchronize(c->stream));
+        uint32_t* d = nullptr;
+        FTK_HIP(c, hipMalloc(&d, (size_t)c->nnz * c->rec_words * sizeof(uint32_t)));
+        hipLaunchKernelGGL(reorder_records_kernel, dim3(blocks_for(c->nnz, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
+                           (const uint32_t*)c->d_rec, d, (uint64_t)c->nnz, c->rec_words, c->tile_a, c->tile_b);
+        if (hipGetLastError() != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess) {
+            hipFree(d);
+            return fail(c, FTK_EDEVICE, "reordering the records failed");
+        }
+        c->d_rec_tiles = d;
+    }
+    if (rule != c->sampling) c->batch_valid = false;
+    c->sampling = rule;
     return FTK_OK;
 }
 

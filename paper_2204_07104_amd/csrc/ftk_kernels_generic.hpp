@@ -59,13 +59,13 @@ __host__ __device__ inline int record_words(int order) { return ((order + 1 + 3)
 // Psi: positions from Philox, and the sampled entries gathered into a dense batch
 // (step a1 + a2: the only place the tensor is read with random access).
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) sample_gather_kernel(Coo coo, int order, uint64_t nnz, uint64_t seed,
+__global__ void __launch_bounds__(256) sample_gather_kernel(Coo coo, int order, SampleRule rule, uint64_t seed,
                                                             long long M, long long cap, uint32_t* __restrict__ pos,
                                                             int32_t* __restrict__ bidx, float* __restrict__ bval) {
     const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= M) return;
-    const uint32_t p = sample_position(seed, (uint64_t)k, nnz);
-    pos[k] = p;
+    const uint32_t p = sample_place(seed, (uint64_t)k, rule);
+    pos[k] = caller_position(p, rule);
     const uint4* r4 = reinterpret_cast<const uint4*>(coo.rec + (size_t)p * coo.words);
     uint32_t w[kMaxOrder + 4];
     for (int q = 0; q < coo.words / 4; ++q) {
@@ -265,6 +265,18 @@ __global__ void __launch_bounds__(256) pack_records_kernel(const uint32_t* __res
     for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t v = src[p];
         rec[p * words + slot] = new_of_old ? (uint32_t)new_of_old[v] : v;
+    }
+}
+
+// records in the pseudo-random order of the tile-sampling rule: dst[q] = src[(a q + b) mod nnz]
+__global__ void __launch_bounds__(256) reorder_records_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst,
+                                                              uint64_t nnz, int words, uint64_t a, uint64_t b) {
+    const int w4 = words / 4;
+    const uint4* s4 = reinterpret_cast<const uint4*>(src);
+    uint4* d4 = reinterpret_cast<uint4*>(dst);
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nnz; q += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t p = (a * q + b) % nnz;
+        for (int i = 0; i < w4; ++i) d4[q * w4 + i] = s4[p * w4 + i];
     }
 }
 

@@ -77,8 +77,8 @@ constexpr unsigned int kRowMask = (1u << kRouteShift) - 1u;
 constexpr unsigned int kNoAtomic = 0xffffff80u;   // slot 0, row far past the end
 
 struct Mfma16Args {
-    Coo coo;
-    uint64_t nnz;
+    Coo coo;                  // records in the order the sampling rule reads them
+    SampleRule rule;
     uint64_t seed;
     long long M;              // |Psi|
     const float* A;
@@ -427,7 +427,7 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     // as row 0 / value 0.
     auto load_record = [&](long long grp, uint4 (&rec)[W4]) {
         const long long k = grp * 64 + lane;
-        const uint32_t p = k < M ? sample_position(g.seed, (uint64_t)k, g.nnz) : 0u;
+        const uint32_t p = k < M ? sample_place(g.seed, (uint64_t)k, g.rule) : 0u;
 #pragma unroll
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };

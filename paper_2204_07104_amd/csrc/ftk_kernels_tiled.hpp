@@ -25,8 +25,8 @@
 namespace ftk {
 
 struct TiledArgs {
-    Coo coo;
-    uint64_t nnz;
+    Coo coo;                     // records in the order the sampling rule reads them
+    SampleRule rule;
     uint64_t seed;
     long long M;                 // |Psi|
     const float* A;
@@ -102,7 +102,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
     auto load_record = [&](long long grp, uint4 (&rec)[W4]) {
         const long long k = grp * 64 + lane;
-        const uint32_t p = k < M ? sample_position(g.seed, (uint64_t)k, g.nnz) : 0u;
+        const uint32_t p = k < M ? sample_place(g.seed, (uint64_t)k, g.rule) : 0u;
 #pragma unroll
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };

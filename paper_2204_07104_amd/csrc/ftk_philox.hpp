@@ -40,6 +40,34 @@ __device__ __forceinline__ uint32_t sample_position(uint64_t seed, uint64_t k, u
     return (uint32_t)__umul64hi(u, nnz);   // nnz < 2^32, so the position fits 32 bits
 }
 
+// Tile-sampling variant: Psi is made of runs of 64 neighbours in a fixed pseudo-random order of
+// the stored entries (stored place q holds the caller's entry (a q + b) mod nnz).  Group g = k / 64
+// draws its run with the entry rule above among n_runs = ceil(nnz / 64) runs; sample k sits at
+// stored place (64 run + k % 64) mod nnz.
+struct SampleRule {
+    uint64_t nnz;
+    uint64_t n_runs;   // 0: entry sampling (the default rule)
+    uint64_t a, b;     // the order of the stored entries in tile mode
+};
+
+__device__ __forceinline__ uint32_t tile_place(uint64_t seed, uint64_t k, const SampleRule& r) {
+    const uint64_t run = sample_position(seed, k >> 6, r.n_runs);
+    uint64_t q = 64 * run + (k & 63);
+    if (q >= r.nnz) q %= r.nnz;   // only the last run wraps (several times if nnz < 64)
+    return (uint32_t)q;
+}
+
+// where sample k is read from: its position among the caller's entries (entry rule, records in the
+// caller's order) or its stored place (tile rule, records in the pseudo-random order)
+__device__ __forceinline__ uint32_t sample_place(uint64_t seed, uint64_t k, const SampleRule& r) {
+    return r.n_runs ? tile_place(seed, k, r) : sample_position(seed, k, r.nnz);
+}
+
+// the caller's position of the entry stored at place q (tile rule); a, q < 2^32
+__device__ __forceinline__ uint32_t caller_position(uint32_t q, const SampleRule& r) {
+    return r.n_runs ? (uint32_t)((r.a * (uint64_t)q + r.b) % r.nnz) : q;
+}
+
 // U[0, 0.5): top 24 bits of output word 0, scaled by 2^-25.
 __device__ __forceinline__ float init_value(uint64_t init_seed, uint32_t array_id, uint64_t q) {
     const U4 o = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), array_id, 1u, (uint32_t)init_seed,

@@ -42,9 +42,12 @@ def oracle_state(w):
     return oracle.init_factors(w.init_seed, w.dims, w.J, w.R)
 
 
-def one_step_case(w, idx, vals, A0=None, B0=None, seed=None, kernel=None):
+def one_step_case(w, idx, vals, A0=None, B0=None, seed=None, kernel=None, tiles=False):
     seed = w.sample_seed0 if seed is None else seed
+    draw = oracle.sample_positions_tiles if tiles else oracle.sample_positions
     with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
+        if tiles:
+            ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
         if kernel:
             ft.ftk_set_kernel(kernel)
             if kernel != "auto":
@@ -59,7 +62,7 @@ def one_step_case(w, idx, vals, A0=None, B0=None, seed=None, kernel=None):
                 assert np.array_equal(x, y), "initial parameters differ from the oracle's"
         ft.ftk_sample(seed, w.n_samples)
         pos = ft.ftk_get_samples()
-        want = oracle.sample_positions(seed, w.n_samples, w.nnz)
+        want = draw(seed, w.n_samples, w.nnz)
         assert np.array_equal(pos, want), "sample set differs from the oracle's"
         ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
         gA, gB = ft.ftk_get_factors()
@@ -87,6 +90,42 @@ def test_sample_set_bit_exact(nnz, M, seed):
         got2 = ft.ftk_get_samples()
     assert np.array_equal(got, oracle.sample_positions(seed, M, nnz))
     assert np.array_equal(got2, oracle.sample_positions(seed + 1, max(1, M // 2), nnz))
+
+
+@pytest.mark.parametrize("nnz,M,seed", [(1, 70, 3), (50, 130, 4), (64, 64, 5), (65, 200, 6), (1000, 1000, 7),
+                                        (100_000, 10_001, 8), (999_983, 262_145, 2**63 + 11)])
+def test_tile_sampling_sample_set_bit_exact(nnz, M, seed):
+    """The tile-sampling variant: positions (in the caller's numbering) bit-exact against the oracle,
+    and switching back restores the default rule."""
+    announce("tile sampling nnz=%d M=%d seed=%d" % (nnz, M, seed))
+    idx = [np.zeros(nnz, dtype=np.int32)]
+    vals = np.zeros(nnz, dtype=np.float32)
+    with binding.FastTucker((1,), idx, vals, (1,), 1) as ft:
+        ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
+        ft.ftk_sample(seed, M)
+        got = ft.ftk_get_samples()
+        ft.ftk_set_sampling(binding.FTK_SAMPLE_ENTRIES)
+        back = ft.ftk_get_samples()
+        with pytest.raises(binding.FtkError):
+            ft.ftk_set_sampling(2)
+    assert np.array_equal(got, oracle.sample_positions_tiles(seed, M, nnz))
+    assert np.array_equal(back, oracle.sample_positions(seed, M, nnz))
+
+
+@pytest.mark.parametrize("kernel", ["auto", "generic", "tiled"])
+@pytest.mark.parametrize("order,dims,nnz,J,R,M", [
+    (3, (700, 500, 90), 30_011, (16, 16, 16), 16, 7_013),
+    (3, (300, 200, 50), 20_000, (24, 40, 9), 20, 5_000),
+    (4, (60, 50, 40, 30), 9_999, (8, 8, 8, 8), 8, 3_001),
+])
+def test_one_step_with_tile_sampling(order, dims, nnz, J, R, M, kernel):
+    """One synchronous step on a tile-sampled Psi, every kernel variant: the entries are read from the
+    reordered copy of the tensor, the gradients must be those of the oracle's positions."""
+    announce("tile-sampled step order=%d J=%r kernel=%s" % (order, J, kernel))
+    w = synth.tiny_workload(order, dims, nnz, J, R, M, seed=21 + order, values="normal")
+    w = synth.replace(w, lr_A=1e-4, lr_B=1e-4)
+    idx, vals = synth.make_tensor(w)
+    one_step_case(w, idx, vals, kernel=kernel, tiles=True)
 
 
 def test_initial_parameters_bit_exact():
@@ -129,21 +168,24 @@ def test_c1_one_step_and_ten_step_rmse():
 def test_ten_steps_rmse_scaled_c2_both_kernels():
     """10 synchronous steps on the C2 recipe at reduced size (J = R = 16: the matrix-core kernels),
     RMSE after every step within 1e-3 relative of the oracle's, for the specialised and the generic
-    gradient kernel."""
+    gradient kernel, and for the specialised kernel under the tile-sampling rule."""
     w = synth.WORKLOADS["C2"].scaled(nnz=300_000, n_samples=30_000, dims=(4_800, 1_777, 220))
     w = synth.replace(w, lr_A=2e-7, lr_B=1e-4)
     idx, vals = synth.make_tensor(w)
-    for kernel in ("auto", "generic"):
-        announce("10 steps scaled C2, kernel=%s" % kernel)
+    for kernel, tiles in (("auto", False), ("generic", False), ("auto", True)):
+        announce("10 steps scaled C2, kernel=%s%s" % (kernel, ", tile sampling" if tiles else ""))
+        draw = oracle.sample_positions_tiles if tiles else oracle.sample_positions
         A, B = oracle_state(w)
         with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
             ft.ftk_set_kernel(kernel)
+            if tiles:
+                ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
             assert ft.ftk_kernel_name() == ("mfma16" if kernel == "auto" else "generic")
             first = None
             for t in range(10):
                 ft.ftk_sample(w.sample_seed0 + t, w.n_samples)
                 ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
-                pos = oracle.sample_positions(w.sample_seed0 + t, w.n_samples, w.nnz)
+                pos = draw(w.sample_seed0 + t, w.n_samples, w.nnz)
                 oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
                 got, want = ft.ftk_rmse(), oracle.rmse(w.dims, idx, vals, A, B)
                 assert got == pytest.approx(want, rel=1e-3), "step %d" % t
@@ -294,7 +336,7 @@ def test_held_out_set_evaluation_matches_oracle(order, dims, J, R):
     want_rmse, want_mae = oracle.errors(w.dims, hidx, hvals, A, B)
     assert abs(got_rmse - want_rmse) <= 1e-4 * want_rmse, (got_rmse, want_rmse)
     assert abs(got_mae - want_mae) <= 1e-4 * want_mae, (got_mae, want_mae)
-    assert again == (got_rmse, got_mae)
+    assert again == pytest.approx((got_rmse, got_mae), rel=1e-12)    # block sums are added in any order
 
 
 def test_call_order_and_bad_input_errors():

@@ -112,3 +112,49 @@ def test_init_factors_shapes():
     A, B = oracle.init_factors(1, (5, 6, 7), (2, 3, 4), 3)
     assert [a.shape for a in A] == [(5, 2), (6, 3), (7, 4)]
     assert [b.shape for b in B] == [(2, 3), (3, 3), (4, 3)]
+
+
+# ------------------------------------------------------------------------------------------------
+# tile sampling (variant rule): runs of 64 neighbours in a fixed pseudo-random order of Omega
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("nnz", [1, 2, 3, 7, 63, 64, 65, 100, 1000, 4096, 99_991, 100_000, 1_000_003])
+def test_tile_order_is_a_bijection(nnz):
+    """pi(q) = (a q + b) mod nnz with gcd(a, nnz) = 1, a as large as allowed below 0.618034 nnz."""
+    import math
+    a, b = oracle.tile_order_constants(nnz)
+    assert 1 <= a <= max(1, nnz * 618034 // 1000000) and math.gcd(a, nnz) == 1
+    assert b == nnz // 3
+    for bigger in range(a + 1, max(1, nnz * 618034 // 1000000) + 1):   # nothing larger qualifies
+        assert math.gcd(bigger, nnz) != 1
+    if nnz <= 100_000:
+        q = np.arange(nnz, dtype=np.int64)
+        assert np.array_equal(np.sort((a * q + b) % nnz), q)            # brute force: every entry exactly once
+
+
+@pytest.mark.parametrize("nnz,M,seed", [(1, 70, 3), (50, 130, 4), (64, 64, 5), (65, 200, 6), (1000, 1000, 7),
+                                        (100_000, 10_000, 8), (99_991, 12_345, 2**63 + 11)])
+def test_tile_samples_are_runs_of_neighbours_drawn_by_the_entry_rule(nnz, M, seed):
+    """Undo pi: the samples of a group sit at consecutive stored places (mod nnz) starting at 64 T_g, and
+    T_g is what the entry rule (pinned above by known-answer vectors) draws for sample g among the runs."""
+    a, b = oracle.tile_order_constants(nnz)
+    a_inv = pow(a, -1, nnz) if nnz > 1 else 0
+    pos = oracle.sample_positions_tiles(seed, M, nnz)
+    assert pos.shape == (M,) and pos.min() >= 0 and pos.max() < nnz
+    stored = [((int(p) - b) * a_inv) % nnz for p in pos]
+    n_runs = (nnz + 63) // 64
+    runs = oracle.sample_positions(seed, (M + 63) // 64, n_runs)
+    for k in range(M):
+        assert stored[k] == (64 * int(runs[k // 64]) + k % 64) % nnz, k
+
+
+def test_tile_sampling_covers_omega_uniformly():
+    """Every stored entry is equally likely: chi-square over 977 bins of 1.28e6 samples (nnz a multiple of
+    64, so that no entry is favoured by the wrap-around of the last run)."""
+    nnz = 64 * 15_625
+    pos = oracle.sample_positions_tiles(12345, 1_280_000, nnz)
+    counts = np.bincount(pos * 977 // nnz, minlength=977).astype(np.float64)
+    expect = 1_280_000 / 977
+    chi2 = float(((counts - expect) ** 2 / expect).sum())
+    # samples come in runs of 64: the statistic is inflated by up to that factor relative to i.i.d. draws
+    assert chi2 < 64 * (976 + 6 * np.sqrt(2 * 976)), chi2
+    assert len(np.unique(pos[:64])) == 64 and len(np.unique(pos)) > 600_000
