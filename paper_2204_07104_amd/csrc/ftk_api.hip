@@ -88,7 +88,8 @@ struct ftk_ctx {
     int hot_H_max = 0;        // rows the LDS budget allows (partial tables are sized for this)
     long long hot_for_M = -1; // |Psi| the current choice was made for
     std::vector<std::vector<unsigned int>> sorted_counts;   // per mode: occurrence counts, descending
-    int mfma_grid = 0;
+    int mfma_grid = 0;                // workgroups of the persistent gradient kernels for the current |Psi|
+    int mfma_grid_max = 0;            // what the partial tables are sized for (one workgroup per CU)
     size_t mfma_lds_bytes = 0;
     float* d_hot_partial = nullptr;   // [mfma_grid][hot_H][16]
     float* d_gb_partial = nullptr;    // [mfma_grid][B_total]
@@ -448,6 +449,13 @@ void release(ftk_ctx* c) {
 // allows.  Rows are already sorted by count within a mode, so this is a merge of sorted lists.
 void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     const int N = c->order;
+    // One workgroup per CU, but no more than there are groups of 64 samples to give every wave
+    // one: every workgroup writes (and the update pass reads) a whole partial table.
+    {
+        const long long waves = c->variant == V_TILED ? c->tiled_waves : kMfmaWaves;
+        const long long groups = (n_samples + 63) / 64;
+        c->mfma_grid = (int)std::max<long long>(1, std::min<long long>(c->mfma_grid_max, (groups + waves - 1) / waves));
+    }
     long long rows_total = 0;
     for (int n = 0; n < N; ++n) rows_total += c->dims[n];
     // LDS left for the table once the kernel's fixed needs are met, in table rows
@@ -633,11 +641,12 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     // ---- kernel variant ----
     c->variant = c->mfma16_ok ? V_MFMA16 : c->tiled_ok ? V_TILED : V_GENERIC;
     if (c->mfma16_ok || c->tiled_ok) {
-        c->mfma_grid = c->num_cu;
+        c->mfma_grid_max = c->num_cu;
+        c->mfma_grid = c->mfma_grid_max;
         // per-workgroup tables of the frequently hit rows: never more than the LDS can hold; per-wave
         // (tiled) or per-workgroup (mfma16) tables of the core gradient
-        FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid * c->max_lds));
-        FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid * 8 * c->L.B_total * sizeof(float)));
+        FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid_max * c->max_lds));
+        FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid_max * 8 * c->L.B_total * sizeof(float)));
         pick_hot_rows(c, 1LL << 20);
     }
     FTK_HIP(c, hipStreamSynchronize(c->stream));
