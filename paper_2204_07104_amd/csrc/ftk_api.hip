@@ -994,7 +994,7 @@ int ftk_set_kernel(ftk_ctx* c, const char* name) {
         return FTK_OK;
     }
     if (!strcmp(name, "tiled")) {
-        if (!c->tiled_ok) return fail(c, FTK_EUNSUPPORTED, "tiled needs J_n <= 64 and R <= 64");
+        if (!c->tiled_ok) return fail(c, FTK_EUNSUPPORTED, "tiled needs order <= 8, J_n <= 64, R <= 64 and padded core factors that fit LDS twice");
         c->variant = V_TILED;
         pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
         return FTK_OK;

@@ -677,13 +677,25 @@ __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
         float4* D4 = reinterpret_cast<float4*>(p.dA);
         for (long long q = (long long)blk * 256 + tid; q < p.n4; q += (long long)p.dense_blocks * 256) {
             const float4 d = D4[q];
-            if (d.x != 0.0f || d.y != 0.0f || d.z != 0.0f || d.w != 0.0f) {
+            const bool nx = d.x != 0.0f, ny = d.y != 0.0f, nz = d.z != 0.0f, nw = d.w != 0.0f;
+            if (nx && ny && nz && nw) {
                 float4 a = A4[q];
                 a.x = fmaf(-p.lr_A, d.x, a.x);
                 a.y = fmaf(-p.lr_A, d.y, a.y);
                 a.z = fmaf(-p.lr_A, d.z, a.z);
                 a.w = fmaf(-p.lr_A, d.w, a.w);
                 A4[q] = a;
+                D4[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            } else if (nx || ny || nz || nw) {
+                // Only the elements with a sum of their own are written.  Four consecutive floats can
+                // belong to two rows (J_n need not be a multiple of 4), and the neighbour may be a row
+                // of the workgroup tables, which the blocks further down update in this same launch:
+                // writing its unchanged value back from here would race with them.
+                float* a = p.A + 4 * q;
+                if (nx) a[0] = fmaf(-p.lr_A, d.x, a[0]);
+                if (ny) a[1] = fmaf(-p.lr_A, d.y, a[1]);
+                if (nz) a[2] = fmaf(-p.lr_A, d.z, a[2]);
+                if (nw) a[3] = fmaf(-p.lr_A, d.w, a[3]);
                 D4[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             }
         }

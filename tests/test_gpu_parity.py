@@ -229,6 +229,64 @@ def test_one_step_small_shapes(order, dims, nnz, J, R, M, kernel):
     one_step_case(w, idx, vals, kernel=kernel)
 
 
+def _random_case(case_seed):
+    """A shape nobody picked by hand: order 1..6, ragged ranks (now and then 16 everywhere, now and then
+    past the matrix-core kernels' limit), a skewed mode, sample counts off every tile boundary."""
+    rng = np.random.default_rng(1000 + case_seed)
+    order = int(rng.integers(1, 7))
+    dims = tuple(int(x) for x in rng.integers(2, 400, size=order))
+    flavour = case_seed % 4
+    if flavour == 0:
+        J, R = (16,) * order, 16
+    elif flavour == 1:
+        J, R = tuple(int(x) for x in rng.integers(1, 17, size=order)), int(rng.integers(1, 17))
+    elif flavour == 2:
+        J, R = tuple(int(x) for x in rng.integers(1, 65, size=order)), int(rng.integers(1, 65))
+    else:
+        J, R = tuple(int(x) for x in rng.integers(1, 90, size=order)), int(rng.integers(1, 90))
+    nnz = int(rng.integers(50, 20_000))
+    M = int(rng.integers(1, 6_000))
+    zipf = tuple(1.1 if (n == 0 and dims[0] > 50) else None for n in range(order))
+    return order, dims, nnz, J, R, M, zipf
+
+
+@pytest.mark.parametrize("case_seed", range(24))
+def test_one_step_random_shapes(case_seed):
+    order, dims, nnz, J, R, M, zipf = _random_case(case_seed)
+    announce("random case %d: order=%d dims=%r J=%r R=%d nnz=%d M=%d" % (case_seed, order, dims, J, R, nnz, M))
+    w = synth.tiny_workload(order, dims, nnz, J, R, M, seed=300 + case_seed, values="normal", zipf=zipf)
+    # a step small enough for any of these shapes (predictions of order R (J/16)^N at the start)
+    scale = max(1.0, float(R) * float(np.prod([max(j, 1) / 16.0 for j in J])))
+    w = synth.replace(w, lr_A=1e-4 / scale ** 2, lr_B=1e-4 / scale ** 2)
+    idx, vals = synth.make_tensor(w)
+    # every variant that is built for the shape: the tiled kernel keeps B and its transpose, padded, in LDS
+    # (high orders with ranks above 32 do not fit), the one-lane-per-sample kernel keeps N R columns per lane
+    # there; a shape none of them takes is refused by ftk_create with FTK_EUNSUPPORTED
+    ran = []
+    for kernel, tiles in ((None, False), ("generic", False), ("tiled", case_seed % 2 == 1)):
+        try:
+            gA, gB, A, B = one_step_case(w, idx, vals, kernel=kernel, tiles=tiles)
+            assert all(np.isfinite(x).all() for x in A + B)
+            ran.append(kernel or "auto")
+        except binding.FtkError as e:
+            assert e.code == binding.FTK_EUNSUPPORTED, e
+    announce("random case %d ran on: %s" % (case_seed, ", ".join(ran) or "no variant (shape refused)"))
+    assert ran or order * R > 256
+
+
+def test_rows_whose_length_is_no_multiple_of_four_next_to_table_rows():
+    """The update pass scans the accumulator four floats at a time while other blocks of the same launch
+    update the rows kept in the workgroups' tables: with J_n = 50 a group of four floats can hold the end of
+    one row and the start of the next, and an element must never be written by both (a lost update once
+    showed up as one wrong element now and then).  Same small shape, several fresh contexts."""
+    w = synth.tiny_workload(4, (153, 311, 144, 358), 1227, (48, 40, 25, 50), 22, 3329, seed=302, values="normal")
+    w = synth.replace(w, lr_A=1.5e-10, lr_B=1.5e-10)
+    idx, vals = synth.make_tensor(w)
+    for rep in range(12):
+        announce("straddling rows, repetition %d" % rep)
+        one_step_case(w, idx, vals)
+
+
 @pytest.mark.parametrize("name,nnz,M,dims", [
     ("C2", 200_000, 20_000, (4_800, 1_777, 220)),
     ("C3", 100_000, 5_000, (10_000, 6_250, 300)),
