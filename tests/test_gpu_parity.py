@@ -274,6 +274,35 @@ def test_one_step_random_shapes(case_seed):
     assert ran or order * R > 256
 
 
+@pytest.mark.parametrize("order,dims,J,R", [
+    (3, (900, 300, 40), (16, 16, 16), 16),
+    (3, (500, 200, 30), (20, 7, 33), 12),
+])
+def test_sample_count_changing_from_step_to_step(order, dims, J, R):
+    """|Psi| changes every step (1 sample, one group, many groups, back): the number of workgroups, the rows
+    kept in the workgroup tables and the partial tables the update pass reads all follow it.  Parameters
+    against the oracle after every step, both sampling rules."""
+    w = synth.tiny_workload(order, dims, 40_000, J, R, 1, seed=77, values="normal", zipf=(1.1, None, None))
+    scale = max(1.0, float(R) * float(np.prod([j / 16.0 for j in J])))
+    lr = 3e-5 / scale ** 2
+    idx, vals = synth.make_tensor(w)
+    for tiles in (False, True):
+        draw = oracle.sample_positions_tiles if tiles else oracle.sample_positions
+        A, B = oracle_state(w)
+        with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
+            if tiles:
+                ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
+            for t, M in enumerate([700, 64, 9_000, 1, 3_329, 130, 20_000, 65]):
+                announce("changing |Psi|: step %d with %d samples%s" % (t, M, ", tiles" if tiles else ""))
+                ft.ftk_sample(500 + t, M)
+                ft.ftk_sgd_step(lr, lr, w.lambda_A, w.lambda_B)
+                oracle.sgd_step_sync(w.dims, idx, vals, A, B, draw(500 + t, M, w.nnz), lr, lr, w.lambda_A, w.lambda_B)
+                gA, gB = ft.ftk_get_factors()
+                for g, o in zip(gA + gB, A + B):
+                    err = np.abs(g.astype(np.float64) - o)
+                    assert float((err - (t + 1) * (ATOL + RTOL * np.abs(o))).max()) <= 0.0, "step %d" % t
+
+
 def test_rows_whose_length_is_no_multiple_of_four_next_to_table_rows():
     """The update pass scans the accumulator four floats at a time while other blocks of the same launch
     update the rows kept in the workgroups' tables: with J_n = 50 a group of four floats can hold the end of
