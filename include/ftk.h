@@ -72,7 +72,7 @@ enum {
     FTK_HOGWILD = 1        /* in-place factor rows (Algorithm 1's order, run concurrently): see ftk_sgd_step */
 };
 
-#define FTK_MAX_ORDER 8
+#define FTK_MAX_ORDER 10
 
 /*
  * Create a context for one tensor and initialise the parameters.

@@ -23,7 +23,7 @@ FTK_PTRS_HOST, FTK_PTRS_DEVICE = 0, 1
 FTK_SYNC, FTK_HOGWILD = 0, 1
 FTK_SAMPLE_ENTRIES, FTK_SAMPLE_TILES = 0, 1
 FTK_K_SAMPLE, FTK_K_GRAD, FTK_K_APPLY, FTK_K_COUNT = 0, 1, 2, 3
-FTK_MAX_ORDER = 8
+FTK_MAX_ORDER = 10
 
 # every symbol include/ftk.h declares
 SYMBOLS = [

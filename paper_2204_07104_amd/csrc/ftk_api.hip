@@ -245,7 +245,7 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
     g.B = c->d_B;
     g.dA = in_place ? c->d_A : c->d_dA;
     g.scale = in_place ? -lr_A : 1.0f;
-    for (int n = 0; n < kMaxOrder; ++n) {
+    for (int n = 0; n < kMfma16MaxOrder; ++n) {
         g.A_off[n] = c->L.A_off[n];
         g.B_off[n] = c->L.B_off[n];
         g.K[n] = c->hot_K[n];

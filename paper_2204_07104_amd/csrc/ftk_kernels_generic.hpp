@@ -9,7 +9,7 @@
 
 namespace ftk {
 
-constexpr int kMaxOrder = 8;
+constexpr int kMaxOrder = 10;
 
 // Everything a kernel needs to find the parameters.  A^(n) for all modes share one allocation
 // (mode n starts at float offset A_off[n]); so do dA^(n) (same offsets), B^(n) and GB^(n)

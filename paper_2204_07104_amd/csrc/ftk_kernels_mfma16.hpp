@@ -76,6 +76,7 @@ constexpr unsigned int kRowMask = (1u << kRouteShift) - 1u;
 // past the end of the array.
 constexpr unsigned int kNoAtomic = 0xffffff80u;   // slot 0, row far past the end
 
+constexpr int kMfma16MaxOrder = 6;   // orders this kernel is instantiated for
 struct Mfma16Args {
     Coo coo;                  // records in the order the sampling rule reads them
     SampleRule rule;
@@ -84,17 +85,17 @@ struct Mfma16Args {
     const float* A;
     const float* B;
     float* dA;                // where rows [K, I_n) are added: the accumulator (synchronous mode) or A itself
-    long long A_off[kMaxOrder];
-    int B_off[kMaxOrder];
-    int K[kMaxOrder];         // rows [0, K[n]) of mode n live in the LDS table
-    int top[kMaxOrder];       // 16 if K[n] >= 16 (rows 0..15 go through the one-hot matrix product), else 0
-    int hot_off[kMaxOrder];   // first LDS table row of mode n
+    long long A_off[kMfma16MaxOrder];
+    int B_off[kMfma16MaxOrder];
+    int K[kMfma16MaxOrder];         // rows [0, K[n]) of mode n live in the LDS table
+    int top[kMfma16MaxOrder];       // 16 if K[n] >= 16 (rows 0..15 go through the one-hot matrix product), else 0
+    int hot_off[kMfma16MaxOrder];   // first LDS table row of mode n
     int H;                    // rows in the LDS table (>= sum K[n])
     float* hot_partial;       // [gridDim.x][H][16]
     float* gb_partial;        // [gridDim.x][N * 256]
-    unsigned int row_bytes[kMaxOrder];   // I_n * 64: size of mode n's rows in A and dA
+    unsigned int row_bytes[kMfma16MaxOrder];   // I_n * 64: size of mode n's rows in A and dA
     unsigned int all_bytes;              // size of the whole packed A (and dA), below 2^31 - 64
-    unsigned int first_row[kMaxOrder];   // A_off[n] / 16: number of mode n's row 0 counted over the packed array
+    unsigned int first_row[kMfma16MaxOrder];   // A_off[n] / 16: number of mode n's row 0 counted over the packed array
     float lambda_A;
     float scale;              // 1 (synchronous: the update pass applies -lr_A) or -lr_A (in-place mode)
 };

@@ -46,7 +46,7 @@ def test_create_rejects_bad_arguments_without_a_device():
     good = dict(order=2, dims=(3, 3), nnz=4, idx_ptrs=[i0.ctypes.data, i0.ctypes.data], vals_ptr=v.ctypes.data,
                 J=(2, 2), R=2)
     cases = [
-        dict(good, order=0), dict(good, order=9), dict(good, nnz=0), dict(good, nnz=1 << 32),
+        dict(good, order=0), dict(good, order=11), dict(good, nnz=0), dict(good, nnz=1 << 32),
         dict(good, dims=(0, 3)), dict(good, dims=(3, 1 << 31)), dict(good, J=(0, 2)), dict(good, R=0),
         dict(good, idx_ptrs=[i0.ctypes.data, None]), dict(good, vals_ptr=None), dict(good, flags=8),
     ]
