@@ -49,7 +49,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "O5", "O6", "O7", "O8", "O9", "O10"],
+                    help="C2 is the headline workload; O5..O10 are the paper's order-scalability sweep")
     ap.add_argument("--kernel", default="auto")
     ap.add_argument("--sampling", default="entries", choices=["entries", "tiles"],
                     help="rule Psi is drawn by; 'tiles' is the library's variant rule (not the headline metric)")

@@ -70,6 +70,14 @@ WORKLOADS = {
 }
 
 
+# The paper's order-scalability sweep (Section 5.4, synthetic data table): orders 5..10, 10 000 rows per mode,
+# 1e8 stored entries with values 1..5; it reports the sweep for J_n = R = 4.  With U(0, 0.5) parameters and
+# J = R = 4 the starting prediction is 4 / 4^N: tiny, so plain step sizes are stable.
+for _n in range(5, 11):
+    WORKLOADS["O%d" % _n] = Workload("O%d" % _n, (10_000,) * _n, 100_000_000, (4,) * _n, 4, 1_000_000,
+                                     (None,) * _n, "int1to5", lr_A=1e-3, lr_B=1e-3, data_seed=200 + _n)
+
+
 def _coprime_multiplier(I: int) -> int:
     a = max(1, int(round(0.6180339887 * I)))
     while math.gcd(a, I) != 1:
