@@ -371,8 +371,10 @@ template <int N>
 void launch_errors_mfma16_n(ftk_ctx* c, const Coo& coo, long long nnz) {
     const long long groups = (nnz + 63) / 64;
     const int grid = blocks_for(groups, 4, c->num_cu * 8);
+    ModeBytes row_bytes = {};
+    for (int n = 0; n < N; ++n) row_bytes.v[n] = (unsigned int)(c->dims[n] * 64);
     hipLaunchKernelGGL(errors_mfma16_kernel<N>, dim3(grid), dim3(256), 0, c->stream, coo, (uint64_t)nnz,
-                       (const float*)c->d_A, (const float*)c->d_B, c->L, c->d_sums);
+                       (const float*)c->d_A, (const float*)c->d_B, c->L, row_bytes, c->d_sums);
 }
 
 template <int N, int P>

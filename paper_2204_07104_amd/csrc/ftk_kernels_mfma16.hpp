@@ -547,28 +547,45 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Evaluation pass over ALL stored entries (RMSE / MAE, Section 5.1) for J_n = R = 16: a streaming
+// Evaluation pass over a set of entries (RMSE / MAE, Section 5.1) for J_n = R = 16: a streaming
 // version of the forward half of the gradient kernel.  A wave reads 64 consecutive records
-// (coalesced), gathers their rows 16 lanes per row, transposes through LDS and runs the
-// projections on the matrix core; squared and absolute errors are summed in double.
+// (coalesced), parks their row numbers, gathers the rows of a 16-entry tile in layout X (16-byte
+// loads, the next tile requested while the current one is multiplied) and runs the projections
+// on the matrix core; the sum over r is one more product with an all-ones matrix.  Squared and
+// absolute errors are summed in double.  No transposes: only layout X is needed here.
 // ---------------------------------------------------------------------------------------------
+struct ModeBytes {
+    unsigned int v[kMfma16MaxOrder];   // I_n * 64: size of mode n's rows in A
+};
+
 template <int N>
 __global__ void __launch_bounds__(256) errors_mfma16_kernel(Coo coo, uint64_t nnz, const float* __restrict__ A,
-                                                            const float* __restrict__ B, Layout L,
+                                                            const float* __restrict__ B, Layout L, ModeBytes row_bytes,
                                                             double* __restrict__ sums /* [2]: sse, sae */) {
+    typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
     constexpr int W4 = (N + 1 + 3) / 4;
-    __shared__ int sidx_all[4][N][64];
-    __shared__ float tbuf_all[4][kTransposeFloats];
+    __shared__ int sidx_all[4][(N + 1) * 64];   // per wave: [N][64] row byte offsets | [64] values
     __shared__ double red[2][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g4 = lane >> 4;
-    int (*sidx)[64] = sidx_all[wave];
-    float* tbuf = tbuf_all[wave];
+    int* sidx = sidx_all[wave];
+    const float* sval = reinterpret_cast<const float*>(sidx + N * 64);
     float Bq[N][4];
+    __amdgpu_buffer_rsrc_t rsrc_A[N];
 #pragma unroll
-    for (int n = 0; n < N; ++n)
+    for (int n = 0; n < N; ++n) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) Bq[n][k] = B[L.B_off[n] + (4 * g4 + k) * 16 + c];
+        rsrc_A[n] = make_rsrc(A + L.A_off[n], row_bytes.v[n]);
+    }
+
+    auto gather = [&](int t, floatx4 (&dst)[N]) {
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const uintx4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc_A[n], sidx[n * 64 + t * 16 + c] + g4 * 16, 0, 0);
+            dst[n] = floatx4{__uint_as_float(q[0]), __uint_as_float(q[1]), __uint_as_float(q[2]), __uint_as_float(q[3])};
+        }
+    };
 
     const uint4* rec4 = reinterpret_cast<const uint4*>(coo.rec);
     const uint64_t n_groups = (nnz + 63) / 64;
@@ -585,38 +602,33 @@ __global__ void __launch_bounds__(256) errors_mfma16_kernel(Coo coo, uint64_t nn
             flat[4 * q + 2] = r.z;
             flat[4 * q + 3] = r.w;
         }
+        lds_wave_sync();   // the previous group's reads of the parked words come first
 #pragma unroll
-        for (int n = 0; n < N; ++n) sidx[n][lane] = act ? (int)flat[n] : 0;
-        const float xval = act ? __uint_as_float(flat[N]) : 0.0f;
+        for (int n = 0; n < N; ++n) sidx[n * 64 + lane] = act ? (int)(flat[n] * 64u) : 0;
+        sidx[N * 64 + lane] = act ? (int)flat[N] : 0;
         lds_wave_sync();
+        floatx4 cur[N], nxt[N];
+        gather(0, nxt);
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub) {
-            floatx4 prod = {1.0f, 1.0f, 1.0f, 1.0f};
 #pragma unroll
-            for (int n = 0; n < N; ++n) {
-                const int4 r = *reinterpret_cast<const int4*>(&sidx[n][sub * 16 + 4 * g4]);
-                const int rows[4] = {r.x, r.y, r.z, r.w};
-                const float* An = A + L.A_off[n];
+            for (int n = 0; n < N; ++n) cur[n] = nxt[n];
+            if (sub < 3) gather(sub + 1, nxt);
+            floatx4 acc[N];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) tbuf[(4 * g4 + v) * 20 + c] = An[(uint32_t)(rows[v] * 16 + c)];
-                lds_wave_sync();
-                const float4 ax = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
-                lds_wave_sync();
-                floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][0], ax.x, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][1], ax.y, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][2], ax.z, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][3], ax.w, acc, 0, 0, 0);
-                prod *= acc;
-            }
-            // xhat of sample (sub * 16 + c): sum over the 16 r held by lanes (c, 0..3) x 4 registers
-            float xhat = (prod[0] + prod[1]) + (prod[2] + prod[3]);
-            xhat += __shfl_xor(xhat, 16);
-            xhat += __shfl_xor(xhat, 32);
-            // the value of sample sub * 16 + c sits in lane sub * 16 + c
-            const float x = __shfl(xval, sub * 16 + c);
+            for (int n = 0; n < N; ++n) acc[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int n = 0; n < N; ++n) acc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(Bq[n][k], cur[n][k], acc[n], 0, 0, 0);
+            floatx4 prod = acc[0];
+#pragma unroll
+            for (int n = 1; n < N; ++n) prod *= acc[n];
+            // xhat of entry (sub * 16 + c): four of its r here, the rest in the other three lane groups
+            const float part = (prod[0] + prod[1]) + (prod[2] + prod[3]);
+            const floatx4 xsum = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, part, floatx4{0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0);
             if (g4 == 0 && group * 64 + sub * 16 + c < nnz) {
-                const double e = (double)x - (double)xhat;
+                const double e = (double)sval[sub * 16 + c] - (double)xsum[0];
                 sse += e * e;
                 sae += fabs(e);
             }
