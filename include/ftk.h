@@ -32,7 +32,8 @@
  *  - Indices are 0-based int32; sample positions are int64 at this boundary.
  *  - All matrices are dense row-major fp32: A^(n) is I_n x J_n, B^(n) is J_n x R.
  *  - "host" / "device" is stated for every pointer.  Device pointers must belong to the HIP
- *    device that was current when ftk_create() ran; that device must be current in later calls.
+ *    device that was current when ftk_create() ran; that device must be current in later calls
+ *    (calls that touch device memory return FTK_ESTATE otherwise).
  *  - The library owns copies of the tensor, the parameters and Psi.  Caller buffers can be
  *    released as soon as the call they were passed to returns.
  *  - ftk_sample / ftk_sgd_step only enqueue work on the context's stream (the null stream
@@ -56,7 +57,7 @@ enum {
     FTK_EINVAL = -1,       /* bad argument (null pointer, size out of range, index out of range) */
     FTK_ENOMEM = -2,       /* a host or device allocation failed */
     FTK_EDEVICE = -3,      /* a HIP call failed, or no usable gfx950 device */
-    FTK_ESTATE = -4,       /* call order: e.g. ftk_sgd_step before ftk_sample */
+    FTK_ESTATE = -4,       /* call order (e.g. ftk_sgd_step before ftk_sample), or another HIP device is current */
     FTK_EUNSUPPORTED = -5  /* valid but outside what the kernels are built for */
 };
 

@@ -130,6 +130,15 @@ inline int blocks_for(long long work, int threads, int cap_blocks) {
     return (int)b;
 }
 
+// Every pointer the context holds belongs to the device that was current in ftk_create.
+int check_device(ftk_ctx* c) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(c, FTK_EDEVICE, "hipGetDevice failed");
+    if (dev != c->device)
+        return fail(c, FTK_ESTATE, "current HIP device is %d, the context was created on device %d", dev, c->device);
+    return FTK_OK;
+}
+
 // event bracket around one kernel launch when timing is on
 struct Bracket {
     ftk_ctx* c;
@@ -474,8 +483,7 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     // A table row saves its workgroup one global atomic per hit (~12 ns of a per-CU unit that is the
     // kernel's bottleneck) and costs one 64-byte store and one read at the end of the step: worth
     // it from a fraction of an expected hit per workgroup and step.
-    double min_count = 0.25 * (double)c->mfma_grid * (double)c->nnz / (double)std::max<long long>(n_samples, 1);
-    if (const char* e = getenv("FTK_HOT_PMIN")) min_count = atof(e) * (double)c->nnz;   // tuning override
+    const double min_count = 0.25 * (double)c->mfma_grid * (double)c->nnz / (double)std::max<long long>(n_samples, 1);
     int taken[kMaxOrder] = {};
     for (int t = 0; t < H; ++t) {
         int best = -1;
@@ -716,6 +724,7 @@ int ftk_sample(ftk_ctx* c, uint64_t seed, int64_t n_samples) {
 
 int ftk_get_samples(ftk_ctx* c, int64_t* pos_out) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     if (!pos_out) return fail(c, FTK_EINVAL, "pos_out is NULL");
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_get_samples before ftk_sample");
     {
@@ -735,6 +744,7 @@ int ftk_get_samples(ftk_ctx* c, int64_t* pos_out) {
 
 int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step before ftk_sample");
     const bool mfma = c->variant != V_GENERIC;     // a matrix-core variant: per-workgroup tables
     const bool tiled = c->variant == V_TILED;
@@ -785,6 +795,7 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
 
 int ftk_rmse(ftk_ctx* c, double* out) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     if (!out) return fail(c, FTK_EINVAL, "out is NULL");
     double s[2] = {0.0, 0.0};
     int rc = launch_errors(c, Coo{c->d_rec, c->rec_words}, c->nnz, s);
@@ -795,6 +806,7 @@ int ftk_rmse(ftk_ctx* c, double* out) {
 
 int ftk_mae(ftk_ctx* c, double* out) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     if (!out) return fail(c, FTK_EINVAL, "out is NULL");
     double s[2] = {0.0, 0.0};
     int rc = launch_errors(c, Coo{c->d_rec, c->rec_words}, c->nnz, s);
@@ -806,6 +818,7 @@ int ftk_mae(ftk_ctx* c, double* out) {
 int ftk_evaluate(ftk_ctx* c, int64_t n_eval, const int32_t* const* idx, const float* vals, uint32_t flags,
                  double* rmse_out, double* mae_out) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     if (n_eval < 1 || n_eval >= (1LL << 32)) return fail(c, FTK_EINVAL, "n_eval %lld outside 1..2^32-1", (long long)n_eval);
     if (!idx || !vals) return fail(c, FTK_EINVAL, "NULL argument");
     if (flags & ~(uint32_t)FTK_PTRS_DEVICE) return fail(c, FTK_EINVAL, "unknown flag bits 0x%x", flags);
@@ -863,6 +876,7 @@ double ftk_step_size(double alpha, double beta, int64_t t) {
 
 int ftk_get_factors(ftk_ctx* c, float* const* A_out, float* const* B_out) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     for (int n = 0; n < c->order; ++n) {
         if (A_out && A_out[n]) {
             const long long na = c->dims[n] * c->L.J[n];
@@ -883,6 +897,7 @@ int ftk_get_factors(ftk_ctx* c, float* const* A_out, float* const* B_out) {
 
 int ftk_set_factors(ftk_ctx* c, const float* const* A_in, const float* const* B_in) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     for (int n = 0; n < c->order; ++n) {
         if (A_in && A_in[n]) {
             const long long na = c->dims[n] * c->L.J[n];
@@ -903,6 +918,7 @@ int ftk_set_factors(ftk_ctx* c, const float* const* A_in, const float* const* B_
 
 int ftk_set_sampling(ftk_ctx* c, int rule) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     if (rule != FTK_SAMPLE_ENTRIES && rule != FTK_SAMPLE_TILES) return fail(c, FTK_EINVAL, "unknown sampling rule %d", rule);
     if (rule == FTK_SAMPLE_TILES && !c->d_rec_tiles) {
         // first use: the order pi(q) = (a q + b) mod nnz and a second copy of the records in it
