@@ -77,6 +77,7 @@ struct ftk_ctx {
     bool tiled_ok = false;    // general matrix-core kernel: J_n, R <= 64
     int tiled_P = 1;          // ranks padded to 16 * tiled_P
     int tiled_waves = 8;
+    bool tiled_x4 = false;    // every J_n is a multiple of four: rows are fetched 16 bytes per lane
     size_t tiled_lds_bytes = 0;
     int sampling = FTK_SAMPLE_ENTRIES;
     uint32_t* d_rec_tiles = nullptr;   // the records in the order of the tile-sampling rule (built on first use)
@@ -283,15 +284,20 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
     }
 }
 
-template <int N, int P, int WAVES>
-int launch_tiled_npw(ftk_ctx* c, const TiledArgs& g) {
-    FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES>),
+template <int N, int P, int WAVES, bool X4>
+int launch_tiled_npwx(ftk_ctx* c, const TiledArgs& g) {
+    FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->tiled_lds_bytes));
     Bracket t(c, FTK_K_GRAD);
-    hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
+    hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES, X4>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
                        c->stream, g);
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;
+}
+
+template <int N, int P, int WAVES>
+int launch_tiled_npw(ftk_ctx* c, const TiledArgs& g) {
+    return c->tiled_x4 ? launch_tiled_npwx<N, P, WAVES, true>(c, g) : launch_tiled_npwx<N, P, WAVES, false>(c, g);
 }
 
 template <int N>
@@ -386,23 +392,26 @@ void launch_errors_mfma16_n(ftk_ctx* c, const Coo& coo, long long nnz) {
                        (const float*)c->d_A, (const float*)c->d_B, c->L, row_bytes, c->d_sums);
 }
 
-template <int N, int P>
-void launch_errors_tiled_np(ftk_ctx* c, const Coo& coo, long long nnz) {
+template <int N, int P, bool X4>
+void launch_errors_tiled_npx(ftk_ctx* c, const Coo& coo, long long nnz) {
     const long long groups = (nnz + 63) / 64;
     const int grid = blocks_for(groups, 4, c->num_cu * 8);
     const size_t lds = 4 * ((size_t)N * 256 * P * P + 4 * (size_t)tiled_wave_scratch(N));
-    hipFuncSetAttribute(reinterpret_cast<const void*>(errors_tiled_kernel<N, P>),
+    TiledModeBytes mode_bytes = {};
+    for (int n = 0; n < N; ++n) mode_bytes.v[n] = (unsigned int)(c->dims[n] * c->L.J[n] * 4);
+    hipFuncSetAttribute(reinterpret_cast<const void*>(errors_tiled_kernel<N, P, X4>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((errors_tiled_kernel<N, P>), dim3(grid), dim3(256), lds, c->stream, coo, (uint64_t)nnz,
-                       (const float*)c->d_A, (const float*)c->d_B, c->L, c->d_sums);
+    hipLaunchKernelGGL((errors_tiled_kernel<N, P, X4>), dim3(grid), dim3(256), lds, c->stream, coo, (uint64_t)nnz,
+                       (const float*)c->d_A, (const float*)c->d_B, c->L, mode_bytes, c->d_sums);
 }
 
 template <int N>
 void launch_errors_tiled_n(ftk_ctx* c, const Coo& coo, long long nnz) {
+    const bool x4 = c->tiled_x4;
     switch (c->tiled_P) {
-        case 1: launch_errors_tiled_np<N, 1>(c, coo, nnz); break;
-        case 2: launch_errors_tiled_np<N, 2>(c, coo, nnz); break;
-        default: launch_errors_tiled_np<N, 4>(c, coo, nnz); break;
+        case 1: x4 ? launch_errors_tiled_npx<N, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 1, false>(c, coo, nnz); break;
+        case 2: x4 ? launch_errors_tiled_npx<N, 2, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 2, false>(c, coo, nnz); break;
+        default: x4 ? launch_errors_tiled_npx<N, 4, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 4, false>(c, coo, nnz); break;
     }
 }
 
@@ -549,8 +558,10 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     {
         int pm = c->L.R;
         c->tiled_ok = N <= 8 && c->L.R <= 64 && c->max_lds >= 131072;
+        c->tiled_x4 = true;
         for (int n = 0; n < N; ++n) {
             pm = std::max(pm, c->L.J[n]);
+            c->tiled_x4 = c->tiled_x4 && c->L.J[n] % 4 == 0;
             c->tiled_ok = c->tiled_ok && c->L.J[n] <= 64 && dims[n] * c->L.J[n] < (1LL << 29);   // 32-bit byte offsets
         }
         c->tiled_P = pm <= 16 ? 1 : pm <= 32 ? 2 : 4;

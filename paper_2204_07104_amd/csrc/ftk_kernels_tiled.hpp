@@ -10,7 +10,12 @@
 //   top rows       TOP[jb] [row x j]     += ONEHOT [row x sample] . GRAD[jb] [sample x j]
 //
 // One wave owns 64 sampled entries at a time (four tiles of 16), draws their positions with Philox
-// in registers and parks the records in a private LDS buffer.  Factor-row gradients take the same
+// in registers and parks the records in a private LDS buffer (two of them, used in turn, so the
+// rows of a group's first tile can be requested while the group before it is still being worked
+// on).  The factor rows of a tile are requested one tile ahead.  Where every J_n is a multiple of
+// four (X4) a lane fetches 16 bytes of its sample's row, which is the operand layout of the
+// projections, and the other layout comes from an LDS transpose; otherwise lanes fetch single
+// floats in the layout of the gradient and the transpose runs the other way.  Factor-row gradients take the same
 // three routes as in the J = R = 16 kernel: rows 0..15 of a mode through the one-hot product, rows
 // [16, K_n) into an LDS table per workgroup (compare-and-swap adds), all other rows through float
 // atomics issued by every lane with out-of-range offsets for lanes that have nothing to add.
@@ -23,6 +28,15 @@
 #include "ftk_kernels_mfma16.hpp"
 
 namespace ftk {
+
+// Where element (k, m) of a zero-padded 16 P x 16 P matrix of mode n sits in LDS so that the lane
+// (c, g) of a wave finds the four values (k = 16 kb + 4 g + 0..3, m = 16 mb + c) it feeds to four
+// consecutive 16x16x4 products in one 16-byte read, and a wave's read covers 1 KB without gaps.
+template <int P>
+__device__ __forceinline__ int operand_slot(int n, int k, int m) {
+    const int kb = k >> 4, g = (k >> 2) & 3, kk = k & 3, mb = m >> 4, c = m & 15;
+    return ((n * P + kb) * P + mb) * 256 + (16 * g + c) * 4 + kk;
+}
 
 struct TiledArgs {
     Coo coo;                     // records in the order the sampling rule reads them
@@ -48,12 +62,13 @@ struct TiledArgs {
     float scale;                 // 1, or -lr_A in in-place mode
 };
 
-__host__ __device__ constexpr int tiled_wave_scratch(int order) { return (order + 1) * 64 + kTransposeFloats; }
+__host__ __device__ constexpr int tiled_park_words(int order) { return (order + 1) * 64; }
+__host__ __device__ constexpr int tiled_wave_scratch(int order) { return 2 * tiled_park_words(order) + kTransposeFloats + 64; }
 __host__ __device__ constexpr size_t tiled_lds_floats(int order, int P, int waves, int H) {
     return (size_t)2 * order * 256 * P * P + (size_t)H * 16 * P + (size_t)waves * tiled_wave_scratch(order);
 }
 
-template <int N, int P, int WAVES>
+template <int N, int P, int WAVES, bool X4>
 __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;
@@ -61,19 +76,22 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     constexpr int THREADS = WAVES * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g4 = lane >> 4;
-    float* Bl = lds;                                 // [N][D][D]   Bl[n][j][r] = B^(n)[j][r] (zero padded)
-    float* Bt = Bl + N * D * D;                      // [N][D][D]   Bt[n][r][j]
+    float* Bl = lds;                                 // B^(n) (zero padded) as operands of the projections, see operand_slot
+    float* Bt = Bl + N * D * D;                      // its transpose as operands of the A gradient
     float* hot = Bt + N * D * D;                     // [H][D]
     float* wave_lds = hot + (size_t)g.H * D + wave * tiled_wave_scratch(N);
-    int* sidx = reinterpret_cast<int*>(wave_lds);    // [N][64]
-    float* sval = wave_lds + N * 64;                 // [64]
-    float* tbuf = wave_lds + (N + 1) * 64;           // [16][20]
+    // two parked groups, each [N][64] row numbers then [64] values; tbuf [16][20]
+    float* tbuf = wave_lds + 2 * tiled_park_words(N);
+    // one word per lane that stays +0: where the table update of a lane with nothing to add aims
+    float* sink = tbuf + kTransposeFloats;
+    sink[lane] = 0.0f;
+    const unsigned int sink_addr = lds_address(sink + lane), hot_addr = lds_address(hot);
 
     for (int q = tid; q < N * D * D; q += THREADS) {
         const int n = q / (D * D), rem = q - n * D * D, j = rem / D, r = rem - j * D;
         const float b = (j < g.J[n] && r < g.R) ? g.B[g.B_off[n] + j * g.R + r] : 0.0f;
-        Bl[q] = b;
-        Bt[n * D * D + r * D + j] = b;
+        Bl[operand_slot<P>(n, j, r)] = b;
+        Bt[operand_slot<P>(n, r, j)] = b;
     }
     for (int q = tid; q < g.H * D; q += THREADS) hot[q] = 0.0f;
 
@@ -107,41 +125,99 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
 
+    // Park a group's records: row numbers and values of inactive lanes are zero.
+    auto park_record = [&](long long grp, const uint4 (&rec)[W4], float* park) {
+        const bool act = grp * 64 + lane < M;
+        uint32_t flat[4 * W4];
+#pragma unroll
+        for (int q = 0; q < W4; ++q) {
+            flat[4 * q + 0] = rec[q].x;
+            flat[4 * q + 1] = rec[q].y;
+            flat[4 * q + 2] = rec[q].z;
+            flat[4 * q + 3] = rec[q].w;
+        }
+        int* sidx = reinterpret_cast<int*>(park);
+#pragma unroll
+        for (int n = 0; n < N; ++n) sidx[n * 64 + lane] = act ? (int)flat[n] : 0;
+        park[N * 64 + lane] = act ? __uint_as_float(flat[N]) : 0.0f;
+    };
+    // Request the factor rows of tile `sub` of a parked group whose first sample is number `first`.
+    //   X4: rows[n][jb] = components 16 jb + 4g .. +3 of the row of sample c           (layout X)
+    //  !X4: rows[n][jb][v] = component 16 jb + c of the row of sample 4g + v            (layout Y)
+    // Components past J_n and samples past the end of Psi read as zero (out-of-range offset).
+    auto gather_rows = [&](const float* park, int sub, long long first, floatx4 (&rows)[N][P]) {
+        const int* sidx = reinterpret_cast<const int*>(park);
+        if constexpr (X4) {
+            const bool act = first + sub * 16 + c < M;
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const int row = sidx[n * 64 + sub * 16 + c];
+#pragma unroll
+                for (int jb = 0; jb < P; ++jb) {
+                    const int col = 16 * jb + 4 * g4;
+                    const int off = (col < g.J[n] && act) ? (row * g.J[n] + col) * 4 : (int)g.mode_bytes[n];
+                    rows[n][jb] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_A[n], off, 0, 0));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const int4 r = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
+                const int rr[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                for (int jb = 0; jb < P; ++jb) {
+                    const int col = 16 * jb + c;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const bool ok = col < g.J[n] && first + sub * 16 + 4 * g4 + v < M;
+                        const int off = ok ? (rr[v] * g.J[n] + col) * 4 : (int)g.mode_bytes[n];
+                        rows[n][jb][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_A[n], off, 0, 0));
+                    }
+                }
+            }
+        }
+    };
+
     uint4 rec[W4];
     long long group = (long long)blockIdx.x * WAVES + wave;
-    if (group < n_groups) load_record(group, rec);
-
-#pragma unroll 1
-    for (; group < n_groups; group += group_stride) {
-        {
-            const bool act = group * 64 + lane < M;
-            uint32_t flat[4 * W4];
-#pragma unroll
-            for (int q = 0; q < W4; ++q) {
-                flat[4 * q + 0] = rec[q].x;
-                flat[4 * q + 1] = rec[q].y;
-                flat[4 * q + 2] = rec[q].z;
-                flat[4 * q + 3] = rec[q].w;
-            }
-#pragma unroll
-            for (int n = 0; n < N; ++n) sidx[n * 64 + lane] = act ? (int)flat[n] : 0;
-            sval[lane] = act ? __uint_as_float(flat[N]) : 0.0f;
-        }
+    floatx4 cur[N][P];
+    int buf = 0;
+    if (group < n_groups) {
+        load_record(group, rec);
+        park_record(group, rec, wave_lds);
         lds_wave_sync();
         if (group + group_stride < n_groups) load_record(group + group_stride, rec);
+        gather_rows(wave_lds, 0, group * 64, cur);
+    }
+
+#pragma unroll 1
+    for (; group < n_groups; group += group_stride, buf ^= 1) {
+        const float* park = wave_lds + buf * tiled_park_words(N);
+        float* park_next = wave_lds + (buf ^ 1) * tiled_park_words(N);
+        const int* sidx = reinterpret_cast<const int*>(park);
+        const float* sval = park + N * 64;
 
 #pragma unroll 1
         for (int sub = 0; sub < 4; ++sub) {
+            // the next tile's rows (past the last group every lane is past the end of Psi and nothing is read)
+            floatx4 nxt[N][P];
+            if (sub < 3) {
+                gather_rows(park, sub + 1, group * 64, nxt);
+            } else {
+                if (group + group_stride < n_groups) {
+                    park_record(group + group_stride, rec, park_next);
+                    lds_wave_sync();
+                    if (group + 2 * group_stride < n_groups) load_record(group + 2 * group_stride, rec);
+                }
+                gather_rows(park_next, 0, (group + group_stride) * 64, nxt);
+            }
+
             const long long base = group * 64 + sub * 16;
             bool actY[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) actY[v] = base + 4 * g4 + v < M;
-
-            // rows in layout Y: aY[n][jb][v] = component 16 jb + c of the row of sample 4g + v
-            // (components past J_n and samples past the end of Psi read as zero: out-of-range offset)
-            float aY[N][P][4];
-            int iY[N][4];
             const float x = sval[sub * 16 + c];
+            int iY[N][4];
 #pragma unroll
             for (int n = 0; n < N; ++n) {
                 const int4 r = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
@@ -149,18 +225,11 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 iY[n][1] = r.y;
                 iY[n][2] = r.z;
                 iY[n][3] = r.w;
-#pragma unroll
-                for (int jb = 0; jb < P; ++jb) {
-                    const int col = 16 * jb + c;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const bool ok = col < g.J[n] && actY[v];
-                        const int off = ok ? (iY[n][v] * g.J[n] + col) * 4 : (int)g.mode_bytes[n];
-                        aY[n][jb][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_A[n], off, 0, 0));
-                    }
-                }
             }
 
+            // both layouts of the tile's rows: aX[k] = component 16 jb + 4g + k of sample c (only used
+            // by the projections), aY[n][jb][v] = component 16 jb + c of sample 4g + v
+            float aY[N][P][4];
             // projections (layout X): s[n][rb][v] = c^(n)_{r = 16 rb + 4g + v} of sample c
             floatx4 s[N][P];
 #pragma unroll
@@ -169,18 +238,37 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 for (int rb = 0; rb < P; ++rb) s[n][rb] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
+                    float ax[4];
+                    if constexpr (X4) {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) tbuf[(4 * g4 + v) * 20 + c] = aY[n][jb][v];
-                    lds_wave_sync();
-                    const float4 ax4 = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
-                    lds_wave_sync();
-                    const float ax[4] = {ax4.x, ax4.y, ax4.z, ax4.w};
-                    const float* Bn = Bl + n * D * D + (16 * jb + 4 * g4) * D + c;
+                        for (int k = 0; k < 4; ++k) ax[k] = cur[n][jb][k];
+                        *reinterpret_cast<float4*>(tbuf + c * 20 + 4 * g4) = make_float4(ax[0], ax[1], ax[2], ax[3]);
+                        lds_wave_sync();
 #pragma unroll
-                    for (int rb = 0; rb < P; ++rb)
+                        for (int v = 0; v < 4; ++v) aY[n][jb][v] = tbuf[(4 * g4 + v) * 20 + c];
+                        lds_wave_sync();
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            aY[n][jb][v] = cur[n][jb][v];
+                            tbuf[(4 * g4 + v) * 20 + c] = aY[n][jb][v];
+                        }
+                        lds_wave_sync();
+                        const float4 ax4 = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
+                        lds_wave_sync();
+                        ax[0] = ax4.x;
+                        ax[1] = ax4.y;
+                        ax[2] = ax4.z;
+                        ax[3] = ax4.w;
+                    }
+#pragma unroll
+                    for (int rb = 0; rb < P; ++rb) {
+                        const float4 b4 = *reinterpret_cast<const float4*>(Bl + ((n * P + jb) * P + rb) * 256 + lane * 4);
+                        const float bk[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            s[n][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(Bn[k * D + 16 * rb], ax[k], s[n][rb], 0, 0, 0);
+                            s[n][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk[k], ax[k], s[n][rb], 0, 0, 0);
+                    }
                 }
             }
 
@@ -218,12 +306,14 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 for (int rb = 0; rb < P; ++rb) {
                     const floatx4 wp = w[n][rb] * neg_e;
                     *reinterpret_cast<float4*>(tbuf + c * 20 + 4 * g4) = make_float4(wp[0], wp[1], wp[2], wp[3]);
-                    const float* Btn = Bt + n * D * D + (16 * rb + 4 * g4) * D + c;
 #pragma unroll
-                    for (int jb = 0; jb < P; ++jb)
+                    for (int jb = 0; jb < P; ++jb) {
+                        const float4 t4 = *reinterpret_cast<const float4*>(Bt + ((n * P + rb) * P + jb) * 256 + lane * 4);
+                        const float tk[4] = {t4.x, t4.y, t4.z, t4.w};
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            gs[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(wp[k], Btn[k * D + 16 * jb], gs[jb], 0, 0, 0);
+                            gs[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(wp[k], tk[k], gs[jb], 0, 0, 0);
+                    }
                     lds_wave_sync();
 #pragma unroll
                     for (int v = 0; v < 4; ++v) wY[rb][v] = tbuf[(4 * g4 + v) * 20 + c];
@@ -231,6 +321,8 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 }
 
                 // factor-row gradients: three routes by row number (see the header comment)
+                unsigned int cell[4 * P];   // table route: LDS address and addend of each of the lane's elements
+                float tval[4 * P];
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
                     const int col = 16 * jb + c;
@@ -243,8 +335,9 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                         const bool cold = ok && row >= g.K[n];
                         __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(
                             grad[v], rsrc_dA[n], cold ? (row * g.J[n] + col) * 4 : (int)g.mode_bytes[n] + c * 4, 0, 0);
-                        if (ok && row < g.K[n] && row >= g.top[n])
-                            lds_float_add(hot + (size_t)(g.hot_off[n] + row) * D + col, grad[v]);
+                        const bool tab = ok && row < g.K[n] && row >= g.top[n];
+                        cell[4 * jb + v] = tab ? hot_addr + (unsigned int)(((g.hot_off[n] + row) * D + col) * 4) : sink_addr;
+                        tval[4 * jb + v] = tab ? grad[v] : 0.0f;
                     }
                     if (g.top[n] > 0) {
 #pragma unroll
@@ -261,7 +354,37 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                             GBacc[n][jb][rb] =
                                 __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][jb][v], wY[rb][v], GBacc[n][jb][rb], 0, 0, 0);
                 }
+                // Table rows: compare-and-swap adds, all reads of the mode's elements first, then all swaps,
+                // so their round trips overlap.  A swap loses when another wave, another lane of the same
+                // instruction or an earlier element of this lane changed the word in between: those go round again.
+                if (g.K[n] > g.top[n]) {
+                    unsigned int seen[4 * P], got[4 * P];
+#pragma unroll
+                    for (int i = 0; i < 4 * P; ++i) seen[i] = *(lds_u32*)(uintptr_t)cell[i];
+#pragma unroll
+                    for (int i = 0; i < 4 * P; ++i)
+                        got[i] = lds_cas(cell[i], seen[i], __float_as_uint(__uint_as_float(seen[i]) + tval[i]));
+                    __builtin_amdgcn_sched_barrier(0);
+                    bool lost = false;
+#pragma unroll
+                    for (int i = 0; i < 4 * P; ++i) lost = lost || got[i] != seen[i];
+                    if (__builtin_amdgcn_ballot_w64(lost) != 0) {
+#pragma unroll
+                        for (int i = 0; i < 4 * P; ++i) {
+                            bool again = got[i] != seen[i];
+                            while (again) {
+                                const unsigned int expect = got[i];
+                                got[i] = lds_cas(cell[i], expect, __float_as_uint(__uint_as_float(expect) + tval[i]));
+                                again = got[i] != expect;
+                            }
+                        }
+                    }
+                }
             }
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+#pragma unroll
+                for (int jb = 0; jb < P; ++jb) cur[n][jb] = nxt[n][jb];
         }
     }
 
@@ -295,11 +418,17 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 
 // ---------------------------------------------------------------------------------------------
 // Evaluation pass over all stored entries (RMSE / MAE) for the same shapes: records streamed,
-// rows gathered 16 lanes per 64 bytes, projections on the matrix core, errors summed in double.
+// rows gathered 16 bytes per lane in the operand layout (X4) or 16 lanes per 64 bytes and
+// transposed in LDS, projections on the matrix core, errors summed in double.
 // ---------------------------------------------------------------------------------------------
-template <int N, int P>
+constexpr int kTiledMaxOrder = 8;
+struct TiledModeBytes {
+    unsigned int v[kTiledMaxOrder];   // I_n * J_n * 4: size of mode n's rows in A
+};
+
+template <int N, int P, bool X4>
 __global__ void __launch_bounds__(256) errors_tiled_kernel(Coo coo, uint64_t nnz, const float* __restrict__ A,
-                                                           const float* __restrict__ B, Layout L,
+                                                           const float* __restrict__ B, Layout L, TiledModeBytes mode_bytes,
                                                            double* __restrict__ sums /* [2]: sse, sae */) {
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;
@@ -307,65 +436,142 @@ __global__ void __launch_bounds__(256) errors_tiled_kernel(Coo coo, uint64_t nnz
     __shared__ double red[2][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g4 = lane >> 4;
-    float* Bl = lds;                                                    // [N][D][D]
-    float* wave_lds = lds + N * D * D + wave * tiled_wave_scratch(N);
-    int* sidx = reinterpret_cast<int*>(wave_lds);
-    float* tbuf = wave_lds + (N + 1) * 64;
+    float* Bl = lds;                                                    // [N][D][D], see operand_slot
+    float* wave_lds = lds + N * D * D + wave * tiled_wave_scratch(N);   // two parked groups, then tbuf
+    float* tbuf = wave_lds + 2 * tiled_park_words(N);
     for (int q = tid; q < N * D * D; q += 256) {
         const int n = q / (D * D), rem = q - n * D * D, j = rem / D, r = rem - j * D;
-        Bl[q] = (j < L.J[n] && r < L.R) ? B[L.B_off[n] + j * L.R + r] : 0.0f;
+        Bl[operand_slot<P>(n, j, r)] = (j < L.J[n] && r < L.R) ? B[L.B_off[n] + j * L.R + r] : 0.0f;
     }
     __syncthreads();
 
     const uint4* rec4 = reinterpret_cast<const uint4*>(coo.rec);
     const uint64_t n_groups = (nnz + 63) / 64;
-    double sse = 0.0, sae = 0.0;
-#pragma unroll 1
-    for (uint64_t group = (uint64_t)blockIdx.x * 4 + wave; group < n_groups; group += (uint64_t)gridDim.x * 4) {
-        const uint64_t p = group * 64 + lane;
-        const bool act = p < nnz;
+    const uint64_t group_stride = (uint64_t)gridDim.x * 4;
+    __amdgpu_buffer_rsrc_t rsrc_A[N];
+#pragma unroll
+    for (int n = 0; n < N; ++n) rsrc_A[n] = make_rsrc(A + L.A_off[n], mode_bytes.v[n]);
+
+    auto load_record = [&](uint64_t grp, uint4 (&rec)[W4]) {
+        const uint64_t p = grp * 64 + lane;
+#pragma unroll
+        for (int q = 0; q < W4; ++q) rec[q] = rec4[(p < nnz ? p : 0) * W4 + q];
+    };
+    // row numbers and values of a group, zero for lanes past the end
+    auto park_record = [&](uint64_t grp, const uint4 (&rec)[W4], float* park) {
+        const bool act = grp * 64 + lane < nnz;
         uint32_t flat[4 * W4];
 #pragma unroll
         for (int q = 0; q < W4; ++q) {
-            const uint4 r = rec4[(act ? p : 0) * W4 + q];
-            flat[4 * q + 0] = r.x;
-            flat[4 * q + 1] = r.y;
-            flat[4 * q + 2] = r.z;
-            flat[4 * q + 3] = r.w;
+            flat[4 * q + 0] = rec[q].x;
+            flat[4 * q + 1] = rec[q].y;
+            flat[4 * q + 2] = rec[q].z;
+            flat[4 * q + 3] = rec[q].w;
         }
+        int* sidx = reinterpret_cast<int*>(park);
 #pragma unroll
         for (int n = 0; n < N; ++n) sidx[n * 64 + lane] = act ? (int)flat[n] : 0;
-        const float xval = act ? __uint_as_float(flat[N]) : 0.0f;
+        park[N * 64 + lane] = act ? __uint_as_float(flat[N]) : 0.0f;
+    };
+    // the rows of tile `sub` of a parked group, in the layouts of the gradient kernel's gather_rows;
+    // entries past the end read row 0 (they are left out of the sums below)
+    auto gather_rows = [&](const float* park, int sub, floatx4 (&rows)[N][P]) {
+        const int* sidx = reinterpret_cast<const int*>(park);
+        if constexpr (X4) {
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const int row = sidx[n * 64 + sub * 16 + c];
+#pragma unroll
+                for (int jb = 0; jb < P; ++jb) {
+                    const int col = 16 * jb + 4 * g4;
+                    const int off = col < L.J[n] ? (row * L.J[n] + col) * 4 : (int)mode_bytes.v[n];
+                    rows[n][jb] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_A[n], off, 0, 0));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const int4 r = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
+                const int rr[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                for (int jb = 0; jb < P; ++jb) {
+                    const int col = 16 * jb + c;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int off = col < L.J[n] ? (rr[v] * L.J[n] + col) * 4 : (int)mode_bytes.v[n];
+                        rows[n][jb][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_A[n], off, 0, 0));
+                    }
+                }
+            }
+        }
+    };
+
+    double sse = 0.0, sae = 0.0;
+    uint4 rec[W4];
+    floatx4 cur[N][P];
+    uint64_t group = (uint64_t)blockIdx.x * 4 + wave;
+    int buf = 0;
+    if (group < n_groups) {
+        load_record(group, rec);
+        park_record(group, rec, wave_lds);
         lds_wave_sync();
+        if (group + group_stride < n_groups) load_record(group + group_stride, rec);
+        gather_rows(wave_lds, 0, cur);
+    }
+#pragma unroll 1
+    for (; group < n_groups; group += group_stride, buf ^= 1) {
+        const float* park = wave_lds + buf * tiled_park_words(N);
+        float* park_next = wave_lds + (buf ^ 1) * tiled_park_words(N);
 #pragma unroll 1
         for (int sub = 0; sub < 4; ++sub) {
+            floatx4 nxt[N][P];
+            if (sub < 3) {
+                gather_rows(park, sub + 1, nxt);
+            } else if (group + group_stride < n_groups) {
+                park_record(group + group_stride, rec, park_next);
+                lds_wave_sync();
+                if (group + 2 * group_stride < n_groups) load_record(group + 2 * group_stride, rec);
+                gather_rows(park_next, 0, nxt);
+            } else {
+#pragma unroll
+                for (int n = 0; n < N; ++n)
+#pragma unroll
+                    for (int jb = 0; jb < P; ++jb) nxt[n][jb] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+
             floatx4 prod[P];
 #pragma unroll
             for (int rb = 0; rb < P; ++rb) prod[rb] = floatx4{1.0f, 1.0f, 1.0f, 1.0f};
 #pragma unroll
             for (int n = 0; n < N; ++n) {
-                const int4 r = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
-                const int rows[4] = {r.x, r.y, r.z, r.w};
-                const float* An = A + L.A_off[n];
                 floatx4 sacc[P];
 #pragma unroll
                 for (int rb = 0; rb < P; ++rb) sacc[rb] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
-                    const int col = 16 * jb + c;
+                    float ax[4];   // components 16 jb + 4g .. +3 of the row of sample c
+                    if constexpr (X4) {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        tbuf[(4 * g4 + v) * 20 + c] = col < L.J[n] ? An[(size_t)rows[v] * L.J[n] + col] : 0.0f;
-                    lds_wave_sync();
-                    const float4 ax4 = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
-                    lds_wave_sync();
-                    const float ax[4] = {ax4.x, ax4.y, ax4.z, ax4.w};
-                    const float* Bn = Bl + n * D * D + (16 * jb + 4 * g4) * D + c;
+                        for (int k = 0; k < 4; ++k) ax[k] = cur[n][jb][k];
+                    } else {
 #pragma unroll
-                    for (int rb = 0; rb < P; ++rb)
+                        for (int v = 0; v < 4; ++v) tbuf[(4 * g4 + v) * 20 + c] = cur[n][jb][v];
+                        lds_wave_sync();
+                        const float4 ax4 = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
+                        lds_wave_sync();
+                        ax[0] = ax4.x;
+                        ax[1] = ax4.y;
+                        ax[2] = ax4.z;
+                        ax[3] = ax4.w;
+                    }
+#pragma unroll
+                    for (int rb = 0; rb < P; ++rb) {
+                        const float4 b4 = *reinterpret_cast<const float4*>(Bl + ((n * P + jb) * P + rb) * 256 + lane * 4);
+                        const float bk[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            sacc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(Bn[k * D + 16 * rb], ax[k], sacc[rb], 0, 0, 0);
+                            sacc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk[k], ax[k], sacc[rb], 0, 0, 0);
+                    }
                 }
 #pragma unroll
                 for (int rb = 0; rb < P; ++rb) prod[rb] *= sacc[rb];
@@ -376,12 +582,16 @@ __global__ void __launch_bounds__(256) errors_tiled_kernel(Coo coo, uint64_t nnz
             for (int rb = 0; rb < P; ++rb) xhat += (prod[rb][0] + prod[rb][1]) + (prod[rb][2] + prod[rb][3]);
             xhat += __shfl_xor(xhat, 16);
             xhat += __shfl_xor(xhat, 32);
-            const float x = __shfl(xval, sub * 16 + c);
+            const float x = park[N * 64 + sub * 16 + c];
             if (g4 == 0 && group * 64 + sub * 16 + c < nnz) {
                 const double e = (double)x - (double)xhat;
                 sse += e * e;
                 sae += fabs(e);
             }
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+#pragma unroll
+                for (int jb = 0; jb < P; ++jb) cur[n][jb] = nxt[n][jb];
         }
     }
     sse = wave_sum(sse);
