@@ -396,7 +396,7 @@ template <int N, int P, bool X4>
 void launch_errors_tiled_npx(ftk_ctx* c, const Coo& coo, long long nnz) {
     const long long groups = (nnz + 63) / 64;
     const int grid = blocks_for(groups, 4, c->num_cu * 8);
-    const size_t lds = 4 * ((size_t)N * 256 * P * P + 4 * (size_t)tiled_wave_scratch(N));
+    const size_t lds = 4 * ((size_t)N * 256 * P * P + 4 * (size_t)tiled_wave_scratch(N, P));
     TiledModeBytes mode_bytes = {};
     for (int n = 0; n < N; ++n) mode_bytes.v[n] = (unsigned int)(c->dims[n] * c->L.J[n] * 4);
     hipFuncSetAttribute(reinterpret_cast<const void*>(errors_tiled_kernel<N, P, X4>),
@@ -562,7 +562,7 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
         for (int n = 0; n < N; ++n) {
             pm = std::max(pm, c->L.J[n]);
             c->tiled_x4 = c->tiled_x4 && c->L.J[n] % 4 == 0;
-            c->tiled_ok = c->tiled_ok && c->L.J[n] <= 64 && dims[n] * c->L.J[n] < (1LL << 29);   // 32-bit byte offsets
+            c->tiled_ok = c->tiled_ok && c->L.J[n] <= 64 && dims[n] * c->L.J[n] < (1LL << 28);   // a mode's rows end below 2^30 bytes
         }
         c->tiled_P = pm <= 16 ? 1 : pm <= 32 ? 2 : 4;
         c->tiled_waves = c->tiled_P == 4 ? 4 : 8;

@@ -63,9 +63,12 @@ struct TiledArgs {
 };
 
 __host__ __device__ constexpr int tiled_park_words(int order) { return (order + 1) * 64; }
-__host__ __device__ constexpr int tiled_wave_scratch(int order) { return 2 * tiled_park_words(order) + kTransposeFloats + 64; }
+// per wave: two parked groups, the transpose buffer, and 4 x 16 P words nobody reads (see `sink`)
+__host__ __device__ constexpr int tiled_wave_scratch(int order, int P) {
+    return 2 * tiled_park_words(order) + kTransposeFloats + 64 * P;
+}
 __host__ __device__ constexpr size_t tiled_lds_floats(int order, int P, int waves, int H) {
-    return (size_t)2 * order * 256 * P * P + (size_t)H * 16 * P + (size_t)waves * tiled_wave_scratch(order);
+    return (size_t)2 * order * 256 * P * P + (size_t)H * 16 * P + (size_t)waves * tiled_wave_scratch(order, P);
 }
 
 template <int N, int P, int WAVES, bool X4>
@@ -79,13 +82,16 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     float* Bl = lds;                                 // B^(n) (zero padded) as operands of the projections, see operand_slot
     float* Bt = Bl + N * D * D;                      // its transpose as operands of the A gradient
     float* hot = Bt + N * D * D;                     // [H][D]
-    float* wave_lds = hot + (size_t)g.H * D + wave * tiled_wave_scratch(N);
+    float* wave_lds = hot + (size_t)g.H * D + wave * tiled_wave_scratch(N, P);
     // two parked groups, each [N][64] row numbers then [64] values; tbuf [16][20]
     float* tbuf = wave_lds + 2 * tiled_park_words(N);
-    // one word per lane that stays +0: where the table update of a lane with nothing to add aims
+    // Table updates are issued for every element; those of samples that take another route aim at a
+    // row of their own that nobody reads (one per 16-lane group, so they never collide).
     float* sink = tbuf + kTransposeFloats;
-    sink[lane] = 0.0f;
-    const unsigned int sink_addr = lds_address(sink + lane), hot_addr = lds_address(hot);
+    const unsigned int sink_addr = lds_address(sink + g4 * D), hot_addr = lds_address(hot);
+    // Out-of-range marker for buffer offsets: added to anything below 2^30 (every mode is smaller,
+    // checked by the host) or to itself it stays beyond the end of the buffer as an unsigned offset.
+    constexpr unsigned int kDropped = 0x40000000u;
 
     for (int q = tid; q < N * D * D; q += THREADS) {
         const int n = q / (D * D), rem = q - n * D * D, j = rem / D, r = rem - j * D;
@@ -199,18 +205,24 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 
 #pragma unroll 1
         for (int sub = 0; sub < 4; ++sub) {
-            // the next tile's rows (past the last group every lane is past the end of Psi and nothing is read)
-            floatx4 nxt[N][P];
-            if (sub < 3) {
-                gather_rows(park, sub + 1, group * 64, nxt);
-            } else {
-                if (group + group_stride < n_groups) {
-                    park_record(group + group_stride, rec, park_next);
-                    lds_wave_sync();
-                    if (group + 2 * group_stride < n_groups) load_record(group + 2 * group_stride, rec);
+            // Request the next tile's rows (past the last group every lane is past the end of Psi and
+            // nothing is read).  X4: into the registers of this tile's rows as soon as the projections
+            // have consumed them; otherwise those registers stay in use as the gradient's layout, and
+            // the request goes out at the top of the tile into registers of its own.
+            auto request_next = [&](floatx4 (&rows)[N][P]) {
+                if (sub < 3) {
+                    gather_rows(park, sub + 1, group * 64, rows);
+                } else {
+                    if (group + group_stride < n_groups) {
+                        park_record(group + group_stride, rec, park_next);
+                        lds_wave_sync();
+                        if (group + 2 * group_stride < n_groups) load_record(group + 2 * group_stride, rec);
+                    }
+                    gather_rows(park_next, 0, (group + group_stride) * 64, rows);
                 }
-                gather_rows(park_next, 0, (group + group_stride) * 64, nxt);
-            }
+            };
+            floatx4 nxt[X4 ? 1 : N][X4 ? 1 : P];
+            if constexpr (!X4) request_next(nxt);
 
             const long long base = group * 64 + sub * 16;
             bool actY[4];
@@ -272,6 +284,8 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 }
             }
 
+            if constexpr (X4) request_next(cur);
+
             // leave-one-out products, prediction, error
             floatx4 w[N][P];
             float xhat = 0.0f;
@@ -320,31 +334,70 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     lds_wave_sync();
                 }
 
-                // factor-row gradients: three routes by row number (see the header comment)
-                unsigned int cell[4 * P];   // table route: LDS address and addend of each of the lane's elements
-                float tval[4 * P];
+                // factor-row gradients: three routes by row number (see the header comment).  Padding
+                // columns and samples past the end of Psi have a = 0 and -e GS = 0, so their gradient is
+                // zero without a test; what keeps them out of dA is the offset.
+                unsigned int abase[4];      // byte offset of the sample's row in dA, or the marker
+                unsigned int tbase[4];      // LDS address of its table row, or of the row nobody reads
+                bool tab[4];
+                float onehot[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = iY[n][v];
+                    abase[v] = (actY[v] && row >= g.K[n]) ? (unsigned int)(row * g.J[n] * 4) : kDropped;
+                    tab[v] = actY[v] && row < g.K[n] && row >= g.top[n];
+                    tbase[v] = tab[v] ? hot_addr + (unsigned int)((g.hot_off[n] + row) * D * 4) : sink_addr;
+                    onehot[v] = row == c ? 1.0f : 0.0f;
+                }
+                // Table rows: compare-and-swap adds, all reads of a batch of the lane's elements first, then all
+                // swaps, so their round trips overlap.  A swap loses when another wave, another lane of the same
+                // instruction or an earlier element of this lane changed the word in between: those go round
+                // again (swaps that aimed at the unread rows are not looked at).  A batch is the whole mode, or
+                // one block of 16 columns where registers are short (P = 4).
+                constexpr int BATCH = P == 4 ? 4 : 4 * P;
+                unsigned int cell[BATCH];
+                float tval[BATCH];
+                auto table_batch = [&]() {
+                    unsigned int seen[BATCH], got[BATCH];
+#pragma unroll
+                    for (int i = 0; i < BATCH; ++i) seen[i] = *(lds_u32*)(uintptr_t)cell[i];
+#pragma unroll
+                    for (int i = 0; i < BATCH; ++i)
+                        got[i] = lds_cas(cell[i], seen[i], __float_as_uint(__uint_as_float(seen[i]) + tval[i]));
+                    __builtin_amdgcn_sched_barrier(0);
+                    bool lost = false;
+#pragma unroll
+                    for (int i = 0; i < BATCH; ++i) lost = lost || (got[i] != seen[i] && tab[i & 3]);
+                    if (__builtin_amdgcn_ballot_w64(lost) != 0) {
+#pragma unroll
+                        for (int i = 0; i < BATCH; ++i) {
+                            bool again = got[i] != seen[i] && tab[i & 3];
+                            while (again) {
+                                const unsigned int expect = got[i];
+                                got[i] = lds_cas(cell[i], expect, __float_as_uint(__uint_as_float(expect) + tval[i]));
+                                again = got[i] != expect;
+                            }
+                        }
+                    }
+                };
+                const bool any_table = g.K[n] > g.top[n];
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
-                    const int col = 16 * jb + c;
+                    // byte offset of the lane's column inside a row, or the marker for columns past J_n
+                    const unsigned int col4 = 16 * jb + c < g.J[n] ? (unsigned int)((16 * jb + c) * 4) : kDropped;
                     float grad[4];
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int row = iY[n][v];
-                        const bool ok = col < g.J[n] && actY[v];
-                        grad[v] = ok ? g.scale * fmaf(g.lambda_A, aY[n][jb][v], gs[jb][v]) : 0.0f;
-                        const bool cold = ok && row >= g.K[n];
-                        __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(
-                            grad[v], rsrc_dA[n], cold ? (row * g.J[n] + col) * 4 : (int)g.mode_bytes[n] + c * 4, 0, 0);
-                        const bool tab = ok && row < g.K[n] && row >= g.top[n];
-                        cell[4 * jb + v] = tab ? hot_addr + (unsigned int)(((g.hot_off[n] + row) * D + col) * 4) : sink_addr;
-                        tval[4 * jb + v] = tab ? grad[v] : 0.0f;
+                        grad[v] = g.scale * fmaf(g.lambda_A, aY[n][jb][v], gs[jb][v]);
+                        __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[v], rsrc_dA[n], (int)(abase[v] + col4), 0, 0);
+                        const int e = BATCH == 4 ? v : 4 * jb + v;
+                        cell[e] = tbase[v] + (unsigned int)((16 * jb + c) * 4);
+                        tval[e] = grad[v];
                     }
                     if (g.top[n] > 0) {
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            const float onehot = (iY[n][k] == c && actY[k]) ? 1.0f : 0.0f;
-                            Top[n][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot, grad[k], Top[n][jb], 0, 0, 0);
-                        }
+                        for (int k = 0; k < 4; ++k)
+                            Top[n][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot[k], grad[k], Top[n][jb], 0, 0, 0);
                     }
                     // core gradient block: GB[j = 16 jb + 4g + v'][r = 16 rb + c]
 #pragma unroll
@@ -353,38 +406,16 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                         for (int v = 0; v < 4; ++v)
                             GBacc[n][jb][rb] =
                                 __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][jb][v], wY[rb][v], GBacc[n][jb][rb], 0, 0, 0);
+                    if (BATCH == 4 && any_table) table_batch();
                 }
-                // Table rows: compare-and-swap adds, all reads of the mode's elements first, then all swaps,
-                // so their round trips overlap.  A swap loses when another wave, another lane of the same
-                // instruction or an earlier element of this lane changed the word in between: those go round again.
-                if (g.K[n] > g.top[n]) {
-                    unsigned int seen[4 * P], got[4 * P];
-#pragma unroll
-                    for (int i = 0; i < 4 * P; ++i) seen[i] = *(lds_u32*)(uintptr_t)cell[i];
-#pragma unroll
-                    for (int i = 0; i < 4 * P; ++i)
-                        got[i] = lds_cas(cell[i], seen[i], __float_as_uint(__uint_as_float(seen[i]) + tval[i]));
-                    __builtin_amdgcn_sched_barrier(0);
-                    bool lost = false;
-#pragma unroll
-                    for (int i = 0; i < 4 * P; ++i) lost = lost || got[i] != seen[i];
-                    if (__builtin_amdgcn_ballot_w64(lost) != 0) {
-#pragma unroll
-                        for (int i = 0; i < 4 * P; ++i) {
-                            bool again = got[i] != seen[i];
-                            while (again) {
-                                const unsigned int expect = got[i];
-                                got[i] = lds_cas(cell[i], expect, __float_as_uint(__uint_as_float(expect) + tval[i]));
-                                again = got[i] != expect;
-                            }
-                        }
-                    }
-                }
+                if (BATCH != 4 && any_table) table_batch();
             }
+            if constexpr (!X4) {
 #pragma unroll
-            for (int n = 0; n < N; ++n)
+                for (int n = 0; n < N; ++n)
 #pragma unroll
-                for (int jb = 0; jb < P; ++jb) cur[n][jb] = nxt[n][jb];
+                    for (int jb = 0; jb < P; ++jb) cur[n][jb] = nxt[n][jb];
+            }
         }
     }
 
@@ -437,7 +468,7 @@ __global__ void __launch_bounds__(256) errors_tiled_kernel(Coo coo, uint64_t nnz
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g4 = lane >> 4;
     float* Bl = lds;                                                    // [N][D][D], see operand_slot
-    float* wave_lds = lds + N * D * D + wave * tiled_wave_scratch(N);   // two parked groups, then tbuf
+    float* wave_lds = lds + N * D * D + wave * tiled_wave_scratch(N, P);   // two parked groups, then tbuf
     float* tbuf = wave_lds + 2 * tiled_park_words(N);
     for (int q = tid; q < N * D * D; q += 256) {
         const int n = q / (D * D), rem = q - n * D * D, j = rem / D, r = rem - j * D;
