@@ -243,13 +243,37 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             // by the projections), aY[n][jb][v] = component 16 jb + c of sample 4g + v
             float aY[N][P][4];
             // projections (layout X): s[n][rb][v] = c^(n)_{r = 16 rb + 4g + v} of sample c
+            // The core-factor operands of a block of products are read from LDS one block ahead of the
+            // products that use them (the scheduling barrier keeps the reads where they are written).
+            // (Not for P = 4, where the registers are all taken: there each block reads its own.)
+            constexpr bool AHEAD = P < 4;
             floatx4 s[N][P];
+            float4 bop[P];
+            if constexpr (AHEAD) {
+#pragma unroll
+                for (int rb = 0; rb < P; ++rb) bop[rb] = *reinterpret_cast<const float4*>(Bl + rb * 256 + lane * 4);
+            }
 #pragma unroll
             for (int n = 0; n < N; ++n) {
 #pragma unroll
                 for (int rb = 0; rb < P; ++rb) s[n][rb] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
+                    float4 bcur[P];
+                    if constexpr (AHEAD) {
+#pragma unroll
+                        for (int rb = 0; rb < P; ++rb) bcur[rb] = bop[rb];
+                        if (n * P + jb + 1 < N * P) {
+#pragma unroll
+                            for (int rb = 0; rb < P; ++rb)
+                                bop[rb] = *reinterpret_cast<const float4*>(Bl + ((n * P + jb + 1) * P + rb) * 256 + lane * 4);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    } else {
+#pragma unroll
+                        for (int rb = 0; rb < P; ++rb)
+                            bcur[rb] = *reinterpret_cast<const float4*>(Bl + ((n * P + jb) * P + rb) * 256 + lane * 4);
+                    }
                     float ax[4];
                     if constexpr (X4) {
 #pragma unroll
@@ -275,8 +299,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     }
 #pragma unroll
                     for (int rb = 0; rb < P; ++rb) {
-                        const float4 b4 = *reinterpret_cast<const float4*>(Bl + ((n * P + jb) * P + rb) * 256 + lane * 4);
-                        const float bk[4] = {b4.x, b4.y, b4.z, b4.w};
+                        const float bk[4] = {bcur[rb].x, bcur[rb].y, bcur[rb].z, bcur[rb].w};
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
                             s[n][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk[k], ax[k], s[n][rb], 0, 0, 0);
@@ -309,6 +332,11 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             xhat += __shfl_xor(xhat, 32);
             const float neg_e = xhat - x;
 
+            float4 top_[P];   // operands of the next block of the A-gradient products, read one block ahead
+            if constexpr (AHEAD) {
+#pragma unroll
+                for (int jb = 0; jb < P; ++jb) top_[jb] = *reinterpret_cast<const float4*>(Bt + jb * 256 + lane * 4);
+            }
 #pragma unroll
             for (int n = 0; n < N; ++n) {
                 // -e w^(n) (layout X), -e GS^(n) (layout Y), and -e w^(n) in layout Y through LDS
@@ -318,12 +346,26 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 for (int jb = 0; jb < P; ++jb) gs[jb] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int rb = 0; rb < P; ++rb) {
+                    float4 tcur[P];
+                    if constexpr (AHEAD) {
+#pragma unroll
+                        for (int jb = 0; jb < P; ++jb) tcur[jb] = top_[jb];
+                        if (n * P + rb + 1 < N * P) {
+#pragma unroll
+                            for (int jb = 0; jb < P; ++jb)
+                                top_[jb] = *reinterpret_cast<const float4*>(Bt + ((n * P + rb + 1) * P + jb) * 256 + lane * 4);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    } else {
+#pragma unroll
+                        for (int jb = 0; jb < P; ++jb)
+                            tcur[jb] = *reinterpret_cast<const float4*>(Bt + ((n * P + rb) * P + jb) * 256 + lane * 4);
+                    }
                     const floatx4 wp = w[n][rb] * neg_e;
                     *reinterpret_cast<float4*>(tbuf + c * 20 + 4 * g4) = make_float4(wp[0], wp[1], wp[2], wp[3]);
 #pragma unroll
                     for (int jb = 0; jb < P; ++jb) {
-                        const float4 t4 = *reinterpret_cast<const float4*>(Bt + ((n * P + rb) * P + jb) * 256 + lane * 4);
-                        const float tk[4] = {t4.x, t4.y, t4.z, t4.w};
+                        const float tk[4] = {tcur[jb].x, tcur[jb].y, tcur[jb].z, tcur[jb].w};
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
                             gs[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(wp[k], tk[k], gs[jb], 0, 0, 0);
@@ -573,6 +615,13 @@ __global__ void __launch_bounds__(256) errors_tiled_kernel(Coo coo, uint64_t nnz
             floatx4 prod[P];
 #pragma unroll
             for (int rb = 0; rb < P; ++rb) prod[rb] = floatx4{1.0f, 1.0f, 1.0f, 1.0f};
+            // core-factor operands: read one block of products ahead (P < 4), as in the gradient kernel
+            constexpr bool AHEAD = P < 4;
+            float4 bop[P];
+            if constexpr (AHEAD) {
+#pragma unroll
+                for (int rb = 0; rb < P; ++rb) bop[rb] = *reinterpret_cast<const float4*>(Bl + rb * 256 + lane * 4);
+            }
 #pragma unroll
             for (int n = 0; n < N; ++n) {
                 floatx4 sacc[P];
@@ -580,6 +629,21 @@ __global__ void __launch_bounds__(256) errors_tiled_kernel(Coo coo, uint64_t nnz
                 for (int rb = 0; rb < P; ++rb) sacc[rb] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
+                    float4 bcur[P];
+                    if constexpr (AHEAD) {
+#pragma unroll
+                        for (int rb = 0; rb < P; ++rb) bcur[rb] = bop[rb];
+                        if (n * P + jb + 1 < N * P) {
+#pragma unroll
+                            for (int rb = 0; rb < P; ++rb)
+                                bop[rb] = *reinterpret_cast<const float4*>(Bl + ((n * P + jb + 1) * P + rb) * 256 + lane * 4);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    } else {
+#pragma unroll
+                        for (int rb = 0; rb < P; ++rb)
+                            bcur[rb] = *reinterpret_cast<const float4*>(Bl + ((n * P + jb) * P + rb) * 256 + lane * 4);
+                    }
                     float ax[4];   // components 16 jb + 4g .. +3 of the row of sample c
                     if constexpr (X4) {
 #pragma unroll
@@ -597,8 +661,7 @@ __global__ void __launch_bounds__(256) errors_tiled_kernel(Coo coo, uint64_t nnz
                     }
 #pragma unroll
                     for (int rb = 0; rb < P; ++rb) {
-                        const float4 b4 = *reinterpret_cast<const float4*>(Bl + ((n * P + jb) * P + rb) * 256 + lane * 4);
-                        const float bk[4] = {b4.x, b4.y, b4.z, b4.w};
+                        const float bk[4] = {bcur[rb].x, bcur[rb].y, bcur[rb].z, bcur[rb].w};
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
                             sacc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk[k], ax[k], sacc[rb], 0, 0, 0);
