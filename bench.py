@@ -54,8 +54,8 @@ def main() -> int:
     ap.add_argument("--kernel", default="auto")
     ap.add_argument("--sampling", default="entries", choices=["entries", "tiles"],
                     help="rule Psi is drawn by; 'tiles' is the library's variant rule (not the headline metric)")
-    ap.add_argument("--mode", default="sync", choices=["sync", "hogwild"],
-                    help="'hogwild' times the in-place mode (not the headline metric)")
+    ap.add_argument("--mode", default="sync", choices=["sync", "hogwild", "modewise"],
+                    help="'hogwild' / 'modewise' time the in-place modes (not the headline metric)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target wall time of the CPU-oracle leg (0: skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -87,7 +87,11 @@ def main() -> int:
         ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
     if args.mode == "hogwild":
         ft.ftk_set_mode(binding.FTK_HOGWILD)
-    print("[bench] context ready, gradient kernel = %s" % ft.ftk_kernel_name(), file=sys.stderr, flush=True)
+    elif args.mode == "modewise":
+        ft.ftk_set_mode(binding.FTK_HOGWILD_MODEWISE)
+    # the mode-by-mode in-place order runs on the one-lane-per-sample kernels whatever the shape
+    kernel_label = "generic, factor phase + core phase" if args.mode == "modewise" else ft.ftk_kernel_name()
+    print("[bench] context ready, gradient kernel = %s" % kernel_label, file=sys.stderr, flush=True)
 
     def run_steps(first: int, count: int) -> None:
         for t in range(first, first + count):
@@ -130,8 +134,8 @@ def main() -> int:
         head = {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved_gbs / HBM_PEAK_GBS}
     roofline = {
-        **head, "kernel": dominant + ":" + ft.ftk_kernel_name(),
-        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant + ":" + ft.ftk_kernel_name())),
+        **head, "kernel": dominant + ":" + kernel_label,
+        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant + ":" + kernel_label)),
         "hbm_gbs_in_kernel": achieved_gbs, "hbm_frac_in_kernel": achieved_gbs / HBM_PEAK_GBS,
         "bytes_per_sample": algorithmic_bytes_per_sample(w), "avg_kernel_ms": dom_ms,
         "whole_step_gbs": bytes_per_launch / (ms_per_step * 1e-3) / 1e9,
@@ -184,7 +188,8 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: order-%d COO %s, nnz=%d, J=%s, R=%d, |Psi|=%d per step, %s step%s"
                                % (w.name, w.order, "x".join(str(d) for d in w.dims), w.nnz, list(w.J), w.R, w.n_samples,
-                                  "synchronous" if args.mode == "sync" else "in-place (Hogwild)",
+                                  {"sync": "synchronous", "hogwild": "in-place (Hogwild)",
+                                   "modewise": "in-place, mode by mode (Algorithm 1 as printed)"}[args.mode],
                                   "" if args.sampling == "entries" else ", tile-sampling variant"),
                    "kernel": roofline["kernel"], "rmse_after": rmse_after, "datagen_s": round(t_gen, 1)},
         "roofline": roofline,

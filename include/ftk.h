@@ -70,7 +70,8 @@ enum {
 /* ftk_set_mode */
 enum {
     FTK_SYNC = 0,          /* all gradients at the step's starting parameters, then one update */
-    FTK_HOGWILD = 1        /* in-place factor rows (Algorithm 1's order, run concurrently): see ftk_sgd_step */
+    FTK_HOGWILD = 1,       /* in-place factor rows, one fused pass (run concurrently): see ftk_sgd_step */
+    FTK_HOGWILD_MODEWISE = 2   /* in-place, Algorithm 1 as printed: modes of a sample in turn, then the core: see ftk_sgd_step */
 };
 
 #define FTK_MAX_ORDER 10
@@ -124,6 +125,15 @@ int ftk_get_samples(ftk_ctx* ctx, int64_t* pos_out);
  * accumulated per workgroup and added at the end of the step.  The core factors are updated once
  * per step from the accumulated gradient, M = |Psi| (Section 4.2).  Results depend on scheduling;
  * this mode is meant to be judged by its RMSE curve.
+ * FTK_HOGWILD_MODEWISE removes the first two deviations at the price of a second pass: a factor
+ * phase in which every sample takes its modes one after the other, mode n using what modes < n of
+ * the same sample have just written (Algorithm 1 lines 1-16), every row update a float atomic add
+ * into A^(n), no per-workgroup accumulation; then a core phase over the same Psi that takes the
+ * core gradient at the updated rows (lines 17-39) and updates every B^(n) once.  Samples still
+ * run concurrently, so samples that share a row see each other's updates in no fixed order; on a
+ * Psi whose samples share no row the result is that of the printed order up to fp32 rounding.
+ * It runs on the one-lane-per-sample kernels only (FTK_EUNSUPPORTED where they do not fit the
+ * shape) and is not tuned.
  */
 int ftk_sgd_step(ftk_ctx* ctx, float lr_A, float lr_B, float lambda_A, float lambda_B);
 
@@ -183,7 +193,7 @@ int ftk_set_factors(ftk_ctx* ctx, const float* const* A_in, const float* const* 
 enum { FTK_SAMPLE_ENTRIES = 0, FTK_SAMPLE_TILES = 1 };
 int ftk_set_sampling(ftk_ctx* ctx, int rule);
 
-/* FTK_SYNC (default) or FTK_HOGWILD. */
+/* FTK_SYNC (default), FTK_HOGWILD or FTK_HOGWILD_MODEWISE. */
 int ftk_set_mode(ftk_ctx* ctx, int mode);
 
 /* Use this hipStream_t (passed as void*) for all later work; NULL = the null stream.

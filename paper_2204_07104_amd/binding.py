@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("FTK_LIB") or os.path.join(HERE, "libftk.so")
 
 FTK_OK, FTK_EINVAL, FTK_ENOMEM, FTK_EDEVICE, FTK_ESTATE, FTK_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 FTK_PTRS_HOST, FTK_PTRS_DEVICE = 0, 1
-FTK_SYNC, FTK_HOGWILD = 0, 1
+FTK_SYNC, FTK_HOGWILD, FTK_HOGWILD_MODEWISE = 0, 1, 2
 FTK_SAMPLE_ENTRIES, FTK_SAMPLE_TILES = 0, 1
 FTK_K_SAMPLE, FTK_K_GRAD, FTK_K_APPLY, FTK_K_COUNT = 0, 1, 2, 3
 FTK_MAX_ORDER = 10

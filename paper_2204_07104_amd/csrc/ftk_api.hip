@@ -208,7 +208,7 @@ Coo sampled_records(const ftk_ctx* c) {
     return Coo{c->sampling == FTK_SAMPLE_TILES ? c->d_rec_tiles : c->d_rec, c->rec_words};
 }
 
-int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A) {
+int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = false) {
     const bool in_place = c->mode == FTK_HOGWILD;
     GradArgs g;
     g.L = c->L;
@@ -220,15 +220,25 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A) {
     g.lambda_A = lambda_A;
     g.scale = in_place ? -lr_A : 1.0f;
     g.b_in_lds = c->gen_b_in_lds;
+    g.core_only = modewise ? 1 : 0;
     if (c->gen_threads == 0)
         return fail(c, FTK_EUNSUPPORTED, "generic gradient kernel: N*R = %d and sum J_n R = %d exceed the LDS budget",
                     c->order * c->L.R, c->L.B_total);
     const int T = c->gen_threads;
     const int grid = blocks_for(c->n_samples, T, c->num_cu * 4);
-    if (c->gen_lds_bytes > 65536)
+    if (c->gen_lds_bytes > 65536) {
         FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_generic_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->gen_lds_bytes));
+        FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(factor_phase_generic_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->gen_lds_bytes));
+    }
     Bracket t(c, FTK_K_GRAD);
+    if (modewise) {
+        // Algorithm 1 as printed: the factor phase changes A in place, then the core gradient is
+        // taken over the same samples at the rows it left
+        hipLaunchKernelGGL(factor_phase_generic_kernel, dim3(grid), dim3(T), c->gen_lds_bytes, c->stream, g, c->d_A, lr_A);
+        FTK_HIP(c, hipGetLastError());
+    }
     hipLaunchKernelGGL(grad_generic_kernel, dim3(grid), dim3(T), c->gen_lds_bytes, c->stream, g);
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;
@@ -757,13 +767,15 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
     if (!c) return FTK_EINVAL;
     if (const int rc_dev = check_device(c)) return rc_dev;
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step before ftk_sample");
-    const bool mfma = c->variant != V_GENERIC;     // a matrix-core variant: per-workgroup tables
-    const bool tiled = c->variant == V_TILED;
-    const bool in_place = c->mode == FTK_HOGWILD;
+    // the mode-by-mode in-place order exists for the one-lane-per-sample kernels only
+    const bool modewise = c->mode == FTK_HOGWILD_MODEWISE;
+    const bool mfma = c->variant != V_GENERIC && !modewise;   // a matrix-core variant: per-workgroup tables
+    const bool tiled = c->variant == V_TILED && !modewise;
+    const bool in_place = c->mode != FTK_SYNC;
     int rc = mfma ? FTK_OK : ensure_batch(c);
     if (rc != FTK_OK) return rc;
     rc = tiled ? launch_grad_tiled(c, lambda_A, lr_A)
-               : mfma ? launch_grad_mfma16(c, lambda_A, lr_A) : launch_grad_generic(c, lambda_A, lr_A);
+               : mfma ? launch_grad_mfma16(c, lambda_A, lr_A) : launch_grad_generic(c, lambda_A, lr_A, modewise);
     if (rc != FTK_OK) return rc;
     {
         ApplyArgs p = {};
@@ -956,7 +968,10 @@ int ftk_set_sampling(ftk_ctx* c, int rule) {
 
 int ftk_set_mode(ftk_ctx* c, int mode) {
     if (!c) return FTK_EINVAL;
-    if (mode != FTK_SYNC && mode != FTK_HOGWILD) return fail(c, FTK_EINVAL, "unknown mode %d", mode);
+    if (mode != FTK_SYNC && mode != FTK_HOGWILD && mode != FTK_HOGWILD_MODEWISE)
+        return fail(c, FTK_EINVAL, "unknown mode %d", mode);
+    if (mode == FTK_HOGWILD_MODEWISE && c->gen_threads == 0)
+        return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the one-lane-per-sample kernels, which do not fit this shape");
     c->mode = mode;
     return FTK_OK;
 }

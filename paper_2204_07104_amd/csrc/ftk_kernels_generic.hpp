@@ -93,6 +93,7 @@ struct GradArgs {
     float lambda_A;
     float scale;       // 1 (synchronous: the update pass applies -lr_A) or -lr_A (in-place mode)
     int b_in_lds;
+    int core_only;     // 1: accumulate the core gradient only, leave the factor rows alone
 };
 
 __global__ void grad_generic_kernel(GradArgs g) {
@@ -144,7 +145,7 @@ __global__ void grad_generic_kernel(GradArgs g) {
             }
             e = g.batch.val[k] - xhat;
             // factor-row gradient: -e GS^(n) + lambda_A a^(n), accumulated into dA
-            for (int n = 0; n < N; ++n) {
+            for (int n = 0; n < N && !g.core_only; ++n) {
                 const int Jn = g.L.J[n];
                 const long long roff = g.L.A_off[n] + (long long)g.batch.idx[(long long)n * cap + k] * Jn;
                 const float* Bn = Bm + g.L.B_off[n];
@@ -174,6 +175,68 @@ __global__ void grad_generic_kernel(GradArgs g) {
     for (int q = lane; q < BT; q += 64) {
         const float v = gb_w[q];
         if (v != 0.0f) atomicAdd(g.GB + q, v);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Factor phase of Algorithm 1 in the order it is printed (lines 1-16), one lane per sampled entry,
+// all lanes running at once: inside a sample the modes are taken one after the other, and mode n
+// already sees what modes < n of the same sample have just done to their rows (their projections
+// c^(m) are advanced by the change, c^(m)_r += sum_j delta_j B^(m)[j,r], which is the projection
+// of the row the lane has just written).  Each row is changed in place with M = 1,
+//     a <- a - lr_A ( -e GS^(n) + lambda_A a ),
+// as a float atomic add of the difference, so that samples which share a row do not lose each
+// other's updates.  The core phase (lines 17-39) is a second launch of grad_generic_kernel with
+// core_only set, over the same samples and the rows this kernel leaves.
+//   LDS: c[N*R][T] | w[R][T] | (optional) B [B_total]; the launch reserves grad_generic's layout.
+// ---------------------------------------------------------------------------------------------
+__global__ void factor_phase_generic_kernel(GradArgs g, float* A_rw, float lr_A) {
+    extern __shared__ float lds[];
+    const int N = g.L.order, R = g.L.R, T = blockDim.x, tid = threadIdx.x;
+    const int BT = g.L.B_total;
+    float* c_l = lds;
+    float* w_l = c_l + (size_t)N * R * T;
+    float* b_l = w_l + (size_t)N * R * T + (size_t)(T >> 6) * BT;
+    if (g.b_in_lds)
+        for (int q = tid; q < BT; q += T) b_l[q] = g.B[q];
+    __syncthreads();
+    const float* Bm = g.b_in_lds ? b_l : g.B;
+
+    const long long M = g.batch.count, cap = g.batch.cap;
+    for (long long k = (long long)blockIdx.x * T + tid; k < M; k += (long long)gridDim.x * T) {
+        const float x = g.batch.val[k];
+        for (int m = 0; m < N; ++m) {
+            const int Jm = g.L.J[m];
+            const float* row = A_rw + g.L.A_off[m] + (long long)g.batch.idx[(long long)m * cap + k] * Jm;
+            const float* Bn = Bm + g.L.B_off[m];
+            for (int r = 0; r < R; ++r) {
+                float acc = 0.0f;
+                for (int j = 0; j < Jm; ++j) acc = fmaf(row[j], Bn[j * R + r], acc);
+                c_l[(size_t)(m * R + r) * T + tid] = acc;
+            }
+        }
+        for (int n = 0; n < N; ++n) {
+            float xhat = 0.0f;
+            for (int r = 0; r < R; ++r) {
+                float prod = 1.0f;
+                for (int m = 0; m < N; ++m)
+                    if (m != n) prod *= c_l[(size_t)(m * R + r) * T + tid];
+                w_l[(size_t)r * T + tid] = prod;
+                xhat = fmaf(prod, c_l[(size_t)(n * R + r) * T + tid], xhat);
+            }
+            const float e = x - xhat;
+            const int Jn = g.L.J[n];
+            float* row = A_rw + g.L.A_off[n] + (long long)g.batch.idx[(long long)n * cap + k] * Jn;
+            const float* Bn = Bm + g.L.B_off[n];
+            for (int j = 0; j < Jn; ++j) {
+                float gs = 0.0f;
+                for (int r = 0; r < R; ++r) gs = fmaf(Bn[j * R + r], w_l[(size_t)r * T + tid], gs);
+                const float delta = -lr_A * fmaf(-e, gs, g.lambda_A * row[j]);
+                atomicAdd(row + j, delta);
+                if (n + 1 < N)
+                    for (int r = 0; r < R; ++r) c_l[(size_t)(n * R + r) * T + tid] += delta * Bn[j * R + r];
+            }
+        }
     }
 }
 

@@ -549,23 +549,25 @@ def test_other_workloads_full_size_one_step(name):
 # ------------------------------------------------------------------------------------------------
 # in-place (Hogwild) mode: judged on its RMSE curve
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("name,nnz,M,dims,lr_A,lr_B,kernel", [
-    ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "auto"),
-    ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "auto"),
-    ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "generic"),
+@pytest.mark.parametrize("name,nnz,M,dims,lr_A,lr_B,kernel,mode", [
+    ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "auto", binding.FTK_HOGWILD),
+    ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "auto", binding.FTK_HOGWILD),
+    ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "generic", binding.FTK_HOGWILD),
+    ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "auto", binding.FTK_HOGWILD_MODEWISE),
+    ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "auto", binding.FTK_HOGWILD_MODEWISE),
 ])
-def test_hogwild_mode_rmse_curve(name, nnz, M, dims, lr_A, lr_B, kernel):
+def test_hogwild_mode_rmse_curve(name, nnz, M, dims, lr_A, lr_B, kernel, mode):
     """10 steps with factor rows updated in place.  The result depends on scheduling, so it is held
     to the sequential in-place oracle (Algorithm 1's printed order) only through the RMSE after every
     step (3 % relative: concurrent samples see rows a little staler than the sequential order does,
     most visibly on the rows a tenth of all samples hit), and it has to learn."""
-    announce("hogwild %s kernel=%s" % (name, kernel))
+    announce("hogwild %s kernel=%s mode=%d" % (name, kernel, mode))
     w = synth.replace(synth.WORKLOADS[name].scaled(nnz=nnz, n_samples=M, dims=dims), lr_A=lr_A, lr_B=lr_B)
     idx, vals = synth.make_tensor(w)
     A, B = oracle_state(w)
     with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
         ft.ftk_set_kernel(kernel)
-        ft.ftk_set_mode(binding.FTK_HOGWILD)
+        ft.ftk_set_mode(mode)
         start = ft.ftk_rmse()
         prev = start
         for t in range(10):
@@ -587,3 +589,40 @@ def test_hogwild_mode_rmse_curve(name, nnz, M, dims, lr_A, lr_B, kernel):
     oracle.sgd_step_sync(w.dims, idx, vals, A0, B0, pos, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
     assert_params_close(gA, A0, "A")
     assert_params_close(gB, B0, "B")
+
+
+def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared():
+    """Every stored entry has rows of its own in every mode, and Psi holds no position twice: then
+    no two samples touch the same row, running them at once changes nothing, and one step in
+    FTK_HOGWILD_MODEWISE has to give what Algorithm 1 gives when its lines are followed one sample
+    after the other -- parameter by parameter.  The step is large enough that following the modes in
+    turn matters: the same step with all gradients taken at the starting rows lands elsewhere."""
+    announce("modewise in-place, conflict-free")
+    nnz, N, J, R = 6000, 3, (16, 8, 12), 8
+    rng = np.random.default_rng(11)
+    dims = (nnz, nnz, nnz)
+    idx = [rng.permutation(nnz).astype(np.int32) for _ in range(N)]
+    vals = rng.uniform(1.0, 5.0, nnz).astype(np.float32)
+    M, seed = 60, 0
+    while True:   # a sample set without repeated positions (about three in four seeds at this size)
+        pos = oracle.sample_positions(seed, M, nnz)
+        if len(set(pos.tolist())) == M:
+            break
+        seed += 1
+    lr_A, lr_B, lam_A, lam_B = 5e-2, 1e-2, 1e-2, 1e-2
+    A, B = oracle.init_factors(3, dims, J, R)
+    A_sync, B_sync = [a.copy() for a in A], [b.copy() for b in B]
+    with binding.FastTucker(dims, idx, vals, J, R, 3) as ft:
+        ft.ftk_set_mode(binding.FTK_HOGWILD_MODEWISE)
+        ft.ftk_sample(seed, M)
+        assert np.array_equal(ft.ftk_get_samples(), pos)
+        ft.ftk_sgd_step(lr_A, lr_B, lam_A, lam_B)
+        gA, gB = ft.ftk_get_factors()
+    oracle.sgd_step_hogwild(dims, idx, vals, A, B, pos, lr_A, lr_B, lam_A, lam_B)
+    oracle.sgd_step_sync(dims, idx, vals, A_sync, B_sync, pos, lr_A, lr_B, lam_A, lam_B)
+    assert_params_close(gA, A, "A")
+    assert_params_close(gB, B, "B")
+    # teeth: the order is visible at this step size
+    far = max(float(np.max(np.abs(A[n] - A_sync[n]) / (np.abs(A[n]) + 1e-6))) for n in range(1, N))
+    assert far > 1e-3, far
+    assert max(float(np.max(np.abs(B[n] - B_sync[n]))) for n in range(N)) > 1e-5
