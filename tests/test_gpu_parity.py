@@ -324,6 +324,26 @@ def test_rows_whose_length_is_no_multiple_of_four_next_to_table_rows():
         one_step_case(w, idx, vals)
 
 
+@pytest.mark.parametrize("order,dims,J,R,zipf", [
+    (3, (2_000, 700, 90), (20, 28, 12), 20, (1.2, 1.1, None)),          # 32-wide blocks, ranks off the block size
+    (3, (2_000, 700, 90), (20, 36, 52), 24, (1.2, 1.1, None)),          # 64-wide blocks
+    (4, (900, 500, 300, 60), (4, 8, 12, 16), 8, (1.1, None, 1.3, None)),   # 16-wide, order 4
+    (3, (2_000, 700, 90), (18, 36, 50), 24, (1.2, 1.1, None)),          # the same with rows that are no multiple of 16 bytes
+])
+def test_matrix_core_kernel_with_ranks_off_the_block_size(order, dims, J, R, zipf):
+    """The general matrix-core kernel on ranks that are multiples of four but not of 16 (rows fetched 16
+    bytes per lane, blocks partly padding) and on ranks that are not (rows fetched float by float), with
+    skewed modes so that all three routes of the factor-row gradients carry rows, over several groups and a
+    ragged last one; both sampling rules."""
+    w = synth.tiny_workload(order, dims, 60_000, J, R, 5_003, seed=411, values="normal", zipf=zipf)
+    scale = max(1.0, float(R) * float(np.prod([j / 16.0 for j in J])))
+    w = synth.replace(w, lr_A=1e-4 / scale ** 2, lr_B=1e-4 / scale ** 2)
+    idx, vals = synth.make_tensor(w)
+    for tiles in (False, True):
+        announce("ranks off the block size: J=%r R=%d%s" % (J, R, ", tiles" if tiles else ""))
+        one_step_case(w, idx, vals, kernel="tiled", tiles=tiles)
+
+
 @pytest.mark.parametrize("name,nnz,M,dims", [
     ("C2", 200_000, 20_000, (4_800, 1_777, 220)),
     ("C3", 100_000, 5_000, (10_000, 6_250, 300)),
