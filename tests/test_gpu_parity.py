@@ -646,3 +646,27 @@ def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared()
     far = max(float(np.max(np.abs(A[n] - A_sync[n]) / (np.abs(A[n]) + 1e-6))) for n in range(1, N))
     assert far > 1e-3, far
     assert max(float(np.max(np.abs(B[n] - B_sync[n]))) for n in range(N)) > 1e-5
+
+
+# ------------------------------------------------------------------------------------------------
+# the training loop of the paper's experiments, end to end: decaying step sizes, held-out Gamma
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("mode,sampling", [("sync", "entries"), ("sync", "tiles"), ("hogwild", "entries"),
+                                           ("modewise", "entries")])
+def test_training_driver_learns_a_planted_tensor(mode, sampling):
+    """paper_2204_07104_amd.train on a small planted tensor: RMSE and MAE on the held-out entries (never
+    sampled) fall to a fifth of where they start, in every mode and under both sampling rules."""
+    import io
+    from paper_2204_07104_amd import train
+    announce("training driver, %s step, %s sampling" % (mode, sampling))
+    out = io.StringIO()
+    hist = train.train((300, 200, 100), 66_000, (8, 8, 8), 8, n_samples=6_000, steps=200,
+                       alpha_A=5e-3, beta_A=0.05, alpha_B=1.0, beta_B=0.05, lambda_A=1e-3, lambda_B=1e-3,
+                       holdout=0.1, planted_rank=4, noise=0.05, seed=1, mode=mode, sampling=sampling,
+                       report_every=50, out=out)
+    assert [h[0] for h in hist] == [0, 50, 100, 150, 200]
+    (_, rmse0, mae0), (_, rmse1, mae1) = hist[0], hist[-1]
+    assert np.isfinite([rmse1, mae1]).all()
+    assert rmse1 < 0.2 * rmse0, out.getvalue()
+    assert mae1 < 0.2 * mae0, out.getvalue()
+    assert mae1 <= rmse1
