@@ -218,9 +218,14 @@ int ftk_get_timing(ftk_ctx* ctx, int which, double* total_ms, int64_t* launches,
 
 /*
  * Gradient-kernel variant.  ftk_create picks the fastest variant built for (N, J_n, R)
- * ("auto").  ftk_set_kernel forces one by name: "generic" (any shape within the limits, one
- * lane per sample) or one of the specialised names ftk_kernel_name can return; "auto" restores
- * the default.  FTK_EUNSUPPORTED if the named variant is not built for this shape.
+ * ("auto").  ftk_set_kernel forces one by name; "auto" restores the default.
+ * FTK_EUNSUPPORTED if the named variant is not built for this shape.  The variants:
+ *   "mfma16"   J_n = R = 16 for every mode, order <= 6, I_n < 2^24, all A^(n) together below 2 GB
+ *   "tiled"    order <= 8, J_n <= 64, R <= 64, I_n * J_n < 2^28, and room in LDS for the core
+ *              factors padded to multiples of 16 (twice)
+ *   "generic"  one lane per sample: any order <= FTK_MAX_ORDER and any ranks for which
+ *              512 * order * R + 4 * sum_n J_n R bytes fit in LDS
+ * All three compute the same step (same Psi, same formulas); they differ in speed only.
  * ftk_kernel_name: the variant in use (static string, never NULL).
  */
 int ftk_set_kernel(ftk_ctx* ctx, const char* name);
