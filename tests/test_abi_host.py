@@ -96,3 +96,26 @@ def test_step_size_schedule_values():
     assert all(a > b > 0.0 for a, b in zip(seq, seq[1:]))                    # strictly decreasing, positive
     assert math.isnan(binding.ftk_step_size(1.0, 1.0, -1))
     assert math.isnan(binding.ftk_step_size(1.0, -1.0, 1))                   # denominator 0
+
+
+def test_plain_c_program_builds_against_the_header_and_links_the_library(tmp_path):
+    """include/ftk.h is C99 (-pedantic -Werror), and a C program linked against libftk.so plus the HIP
+    runtime gets the documented behaviour from the calls that need no device."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    hip_dir = os.path.dirname(binding.hip_runtime_path())
+    if gcc is None:
+        pytest.skip("no gcc")
+    lib_dir = os.path.dirname(binding.LIB_PATH)
+    exe = str(tmp_path / "abi_smoke")
+    subprocess.check_call([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                           "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "abi_smoke.c"), "-o", exe,
+                           "-L", lib_dir, "-lftk", "-L", hip_dir, "-lamdhip64",
+                           "-Wl,-rpath," + lib_dir, "-Wl,-rpath," + hip_dir])
+    done = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert done.returncode == 0, done.stdout + done.stderr
+    lines = done.stdout.strip().splitlines()
+    assert lines[0] == 'create rc=-1 ctx_is_null=1 error="order 0 outside 1..10"'
+    assert lines[1] == "null ctx: sample=-1 step=-1 rmse=-1 kernel=none"
+    assert float(lines[2].split("=")[1]) == 0.5 / (1.0 + 0.25 * 8.0)
