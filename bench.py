@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--kernel", default="auto")
     ap.add_argument("--sampling", default="entries", choices=["entries", "tiles"],
                     help="rule Psi is drawn by; 'tiles' is the library's variant rule (not the headline metric)")
+    ap.add_argument("--layout", default="padded", choices=["padded", "exact"],
+                    help="'exact' keeps rows at J_n floats (ftk_create flag FTK_LAYOUT_EXACT); by default ranks up to 16 "
+                         "are held padded to 16 for orders 2..5.  No effect on C2 (J = R = 16).")
     ap.add_argument("--mode", default="sync", choices=["sync", "hogwild", "modewise"],
                     help="'hogwild' / 'modewise' time the in-place modes (not the headline metric)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target wall time of the CPU-oracle leg (0: skip)")
@@ -79,7 +82,8 @@ def main() -> int:
     print("[bench] %s generated in %.1f s (nnz=%d)" % (w.name, t_gen, w.nnz), file=sys.stderr, flush=True)
 
     stream = torch.cuda.Stream()
-    ft = binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed)
+    ft = binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed,
+                            flags=binding.FTK_LAYOUT_EXACT if args.layout == "exact" else 0)
     ft.ftk_set_stream(stream.cuda_stream)
     if args.kernel != "auto":
         ft.ftk_set_kernel(args.kernel)

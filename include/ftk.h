@@ -64,7 +64,10 @@ enum {
 /* ftk_create flags */
 enum {
     FTK_PTRS_HOST = 0u,    /* idx[n] and vals point to host memory (default) */
-    FTK_PTRS_DEVICE = 1u   /* idx[n] and vals point to device memory (the idx array itself is host) */
+    FTK_PTRS_DEVICE = 1u,  /* idx[n] and vals point to device memory (the idx array itself is host) */
+    FTK_LAYOUT_EXACT = 2u  /* keep the library's copy of A^(n), B^(n) at J_n and R floats per row.  Without it
+                              ranks up to 16 (order 2..5) are held zero-padded to 16, which costs memory (rows of
+                              64 bytes) and buys the fastest kernel; results are the same either way. */
 };
 
 /* ftk_set_mode */

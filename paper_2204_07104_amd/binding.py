@@ -19,7 +19,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("FTK_LIB") or os.path.join(HERE, "libftk.so")
 
 FTK_OK, FTK_EINVAL, FTK_ENOMEM, FTK_EDEVICE, FTK_ESTATE, FTK_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
-FTK_PTRS_HOST, FTK_PTRS_DEVICE = 0, 1
+FTK_PTRS_HOST, FTK_PTRS_DEVICE, FTK_LAYOUT_EXACT = 0, 1, 2
 FTK_SYNC, FTK_HOGWILD, FTK_HOGWILD_MODEWISE = 0, 1, 2
 FTK_SAMPLE_ENTRIES, FTK_SAMPLE_TILES = 0, 1
 FTK_K_SAMPLE, FTK_K_GRAD, FTK_K_APPLY, FTK_K_COUNT = 0, 1, 2, 3
@@ -133,7 +133,8 @@ def _ptr_list(ptrs: Sequence[Optional[int]]):
 class FastTucker:
     """One tensor + its parameters + the current sample set (an ftk_ctx)."""
 
-    def __init__(self, dims: Sequence[int], idx: Sequence, vals, J: Sequence[int], R: int, init_seed: int = 1):
+    def __init__(self, dims: Sequence[int], idx: Sequence, vals, J: Sequence[int], R: int, init_seed: int = 1,
+                 flags: int = 0):
         L = load()
         self._L = L
         self._ctx = C.c_void_p(None)
@@ -155,14 +156,14 @@ class FastTucker:
             nnz = int(vals.numel())
             ptrs = [int(a.data_ptr()) for a in idx]
             vptr = int(vals.data_ptr())
-            flags = FTK_PTRS_DEVICE
+            flags = int(flags) | FTK_PTRS_DEVICE
         else:
             idx = [np.ascontiguousarray(a, dtype=np.int32) for a in idx]
             vals = np.ascontiguousarray(vals, dtype=np.float32)
             nnz = int(vals.shape[0])
             ptrs = [a.ctypes.data for a in idx]
             vptr = vals.ctypes.data
-            flags = FTK_PTRS_HOST
+            flags = int(flags) & ~FTK_PTRS_DEVICE
         for a in idx:
             if int(a.shape[0]) != nnz:
                 raise ValueError("idx[n] and vals must all have nnz entries")

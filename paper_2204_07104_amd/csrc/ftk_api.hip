@@ -39,7 +39,9 @@ struct ftk_ctx {
     int order = 0;
     int64_t dims[kMaxOrder] = {};
     int64_t nnz = 0;
-    Layout L = {};
+    Layout L = {};           // the library's own copy of the parameters: J[n], R are the PADDED ranks
+    int J_user[kMaxOrder] = {};   // ranks as the caller gave them (equal to L.J / L.R unless padded)
+    int R_user = 0;
     long long A_total = 0;   // floats in the packed A (and dA) allocation, multiple of 64
 
     uint32_t* d_rec = nullptr;               // the tensor: one record per stored entry (see struct Coo)
@@ -555,7 +557,7 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
         c->L.B_off[n] = b_off;
         a_off += ((dims[n] * c->L.J[n] + 16 + 63) / 64) * 64;   // >= 16 floats of slack after every mode
         b_off += c->L.J[n] * c->L.R;
-        stage = std::max(stage, (long long)dims[n] * c->L.J[n]);
+        stage = std::max(stage, (long long)dims[n] * c->J_user[n]);
     }
     c->A_total = a_off;
     c->L.B_total = b_off;
@@ -658,14 +660,15 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     FTK_HIP(c, hipMalloc(&c->d_sums, 2 * sizeof(double)));
     FTK_HIP(c, hipMemset(c->d_A, 0, (size_t)c->A_total * sizeof(float)));
     FTK_HIP(c, hipMemset(c->d_dA, 0, (size_t)c->A_total * sizeof(float)));
+    FTK_HIP(c, hipMemset(c->d_B, 0, (size_t)c->L.B_total * sizeof(float)));
     FTK_HIP(c, hipMemset(c->d_GB, 0, (size_t)c->L.B_total * sizeof(float)));
     for (int n = 0; n < N; ++n) {
-        const long long na = dims[n] * c->L.J[n], nb = (long long)c->L.J[n] * c->L.R;
+        const long long na = dims[n] * c->J_user[n], nb = (long long)c->J_user[n] * c->R_user;
         hipLaunchKernelGGL(init_factor_kernel, dim3(blocks_for(na, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
-                           c->d_A + c->L.A_off[n], (long long)dims[n], c->L.J[n], (const int32_t*)c->d_new_of_old[n],
-                           init_seed, (uint32_t)n);
+                           c->d_A + c->L.A_off[n], (long long)dims[n], c->J_user[n], c->L.J[n],
+                           (const int32_t*)c->d_new_of_old[n], init_seed, (uint32_t)n);
         hipLaunchKernelGGL(init_uniform_kernel, dim3(blocks_for(nb, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
-                           c->d_B + c->L.B_off[n], nb, init_seed, (uint32_t)(N + n));
+                           c->d_B + c->L.B_off[n], (long long)c->J_user[n], c->R_user, c->L.R, init_seed, (uint32_t)(N + n));
     }
     FTK_HIP(c, hipGetLastError());
 
@@ -696,7 +699,7 @@ int ftk_create(ftk_ctx** out, int32_t order, const int64_t* dims, int64_t nnz, c
     if (!dims || !idx || !vals || !J) return fail(nullptr, FTK_EINVAL, "NULL argument");
     if (nnz < 1 || nnz >= (1LL << 32)) return fail(nullptr, FTK_EINVAL, "nnz %lld outside 1..2^32-1", (long long)nnz);
     if (R < 1 || R > 1024) return fail(nullptr, FTK_EINVAL, "R %d outside 1..1024", R);
-    if (flags & ~(uint32_t)FTK_PTRS_DEVICE) return fail(nullptr, FTK_EINVAL, "unknown flag bits 0x%x", flags);
+    if (flags & ~(uint32_t)(FTK_PTRS_DEVICE | FTK_LAYOUT_EXACT)) return fail(nullptr, FTK_EINVAL, "unknown flag bits 0x%x", flags);
     for (int n = 0; n < order; ++n) {
         if (dims[n] < 1 || dims[n] >= (1LL << 31))
             return fail(nullptr, FTK_EINVAL, "dims[%d] = %lld outside 1..2^31-1", n, (long long)dims[n]);
@@ -709,9 +712,31 @@ int ftk_create(ftk_ctx** out, int32_t order, const int64_t* dims, int64_t nnz, c
     c->nnz = nnz;
     c->L.order = order;
     c->L.R = R;
+    c->R_user = R;
     for (int n = 0; n < order; ++n) {
         c->dims[n] = dims[n];
         c->L.J[n] = J[n];
+        c->J_user[n] = J[n];
+    }
+    // Ranks up to 16 are held zero-padded to 16 (rows of 64 bytes, 16 x 16 core factors) where that
+    // puts the shape on the J_n = R = 16 kernel.  Padding is inert: a padded component of a row is 0
+    // and meets a zero row of B^(n), so its gradient is 0; a padded r has c^(k)_r = 0 in every mode,
+    // so with two or more modes its leave-one-out products, its share of the prediction and its core
+    // gradient are 0.
+    // Up to order 5, where that kernel is the faster one (measured: order 5 0.28 ms against 0.32 ms per step on
+    // the general matrix-core kernel, order 6 0.44 ms against 0.37 ms: its register tiles spill there).
+    if (!(flags & FTK_LAYOUT_EXACT) && order >= 2 && order <= 5 && R <= 16) {
+        bool pad = true, all16 = R == 16;
+        long long bytes = 0;
+        for (int n = 0; n < order; ++n) {
+            pad = pad && J[n] <= 16 && dims[n] < (1LL << 24);
+            all16 = all16 && J[n] == 16;
+            bytes += ((dims[n] * 16 + 16 + 63) / 64) * 64 * 4;
+        }
+        if (pad && !all16 && bytes < 0x7fffffc0LL) {
+            c->L.R = 16;
+            for (int n = 0; n < order; ++n) c->L.J[n] = 16;
+        }
     }
     int rc;
     try {
@@ -902,17 +927,18 @@ int ftk_get_factors(ftk_ctx* c, float* const* A_out, float* const* B_out) {
     if (const int rc_dev = check_device(c)) return rc_dev;
     for (int n = 0; n < c->order; ++n) {
         if (A_out && A_out[n]) {
-            const long long na = c->dims[n] * c->L.J[n];
+            const long long na = c->dims[n] * c->J_user[n];
             hipLaunchKernelGGL(permute_rows_kernel, dim3(blocks_for(na, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
                                (const float*)(c->d_A + c->L.A_off[n]), c->d_stage, (const int32_t*)c->d_new_of_old[n],
-                               (long long)c->dims[n], c->L.J[n], 0);
+                               (long long)c->dims[n], c->J_user[n], c->L.J[n], 0);
             FTK_HIP(c, hipGetLastError());
             FTK_HIP(c, hipMemcpyAsync(A_out[n], c->d_stage, (size_t)na * sizeof(float), hipMemcpyDeviceToHost, c->stream));
             FTK_HIP(c, hipStreamSynchronize(c->stream));
         }
-        if (B_out && B_out[n])
-            FTK_HIP(c, hipMemcpyAsync(B_out[n], c->d_B + c->L.B_off[n], (size_t)c->L.J[n] * c->L.R * sizeof(float),
-                                      hipMemcpyDeviceToHost, c->stream));
+        if (B_out && B_out[n])   // J_n rows of R floats out of rows of (padded) L.R floats
+            FTK_HIP(c, hipMemcpy2DAsync(B_out[n], (size_t)c->R_user * sizeof(float), c->d_B + c->L.B_off[n],
+                                        (size_t)c->L.R * sizeof(float), (size_t)c->R_user * sizeof(float),
+                                        (size_t)c->J_user[n], hipMemcpyDeviceToHost, c->stream));
     }
     FTK_HIP(c, hipStreamSynchronize(c->stream));
     return FTK_OK;
@@ -923,17 +949,18 @@ int ftk_set_factors(ftk_ctx* c, const float* const* A_in, const float* const* B_
     if (const int rc_dev = check_device(c)) return rc_dev;
     for (int n = 0; n < c->order; ++n) {
         if (A_in && A_in[n]) {
-            const long long na = c->dims[n] * c->L.J[n];
+            const long long na = c->dims[n] * c->J_user[n];
             FTK_HIP(c, hipMemcpyAsync(c->d_stage, A_in[n], (size_t)na * sizeof(float), hipMemcpyHostToDevice, c->stream));
             hipLaunchKernelGGL(permute_rows_kernel, dim3(blocks_for(na, 256, c->num_cu * 8)), dim3(256), 0, c->stream,
                                (const float*)c->d_stage, c->d_A + c->L.A_off[n], (const int32_t*)c->d_new_of_old[n],
-                               (long long)c->dims[n], c->L.J[n], 1);
+                               (long long)c->dims[n], c->J_user[n], c->L.J[n], 1);
             FTK_HIP(c, hipGetLastError());
             FTK_HIP(c, hipStreamSynchronize(c->stream));
         }
         if (B_in && B_in[n])
-            FTK_HIP(c, hipMemcpyAsync(c->d_B + c->L.B_off[n], B_in[n], (size_t)c->L.J[n] * c->L.R * sizeof(float),
-                                      hipMemcpyHostToDevice, c->stream));
+            FTK_HIP(c, hipMemcpy2DAsync(c->d_B + c->L.B_off[n], (size_t)c->L.R * sizeof(float), B_in[n],
+                                        (size_t)c->R_user * sizeof(float), (size_t)c->R_user * sizeof(float),
+                                        (size_t)c->J_user[n], hipMemcpyHostToDevice, c->stream));
     }
     FTK_HIP(c, hipStreamSynchronize(c->stream));
     return FTK_OK;

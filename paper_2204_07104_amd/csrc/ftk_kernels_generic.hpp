@@ -296,14 +296,18 @@ __global__ void __launch_bounds__(256) errors_generic_kernel(Coo coo, Layout L, 
 // ---------------------------------------------------------------------------------------------
 // set-up kernels
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) init_uniform_kernel(float* __restrict__ out, long long count,
+// Initial values are a function of the element's position in the CALLER's arrays (row-major, J or R
+// floats per row); `stride` is the row length of the library's own copy, whose padding stays zero.
+__global__ void __launch_bounds__(256) init_uniform_kernel(float* __restrict__ out, long long rows, int cols, int stride,
                                                            uint64_t init_seed, uint32_t array_id) {
-    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < count;
-         q += (long long)gridDim.x * blockDim.x)
-        out[q] = init_value(init_seed, array_id, (uint64_t)q);
+    const long long total = rows * cols;
+    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < total;
+         q += (long long)gridDim.x * blockDim.x) {
+        const long long i = q / cols;
+        out[i * stride + (q - i * cols)] = init_value(init_seed, array_id, (uint64_t)q);
+    }
 }
 
-// counts entries outside [0, dim)
 __global__ void __launch_bounds__(256) check_range_kernel(const int32_t* __restrict__ idx, uint64_t nnz, int32_t dim,
                                                           unsigned int* __restrict__ bad) {
     unsigned int mine = 0;
@@ -345,9 +349,11 @@ __global__ void __launch_bounds__(256) reorder_records_kernel(const uint32_t* __
 
 // Parameter rows between the caller's numbering and the internal one:
 // to_internal:  dst[new_of_old[i]][:] = src[i][:]      from_internal:  dst[i][:] = src[new_of_old[i]][:]
+// Rows between the caller's numbering (J floats per row) and the library's (renumbered, `stride`
+// floats per row, padding untouched).
 __global__ void __launch_bounds__(256) permute_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                            const int32_t* __restrict__ new_of_old, long long rows,
-                                                           int J, int to_internal) {
+                                                           int J, int stride, int to_internal) {
     const long long total = rows * J;
     for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < total;
          q += (long long)gridDim.x * blockDim.x) {
@@ -355,14 +361,13 @@ __global__ void __launch_bounds__(256) permute_rows_kernel(const float* __restri
         const int j = (int)(q - i * J);
         const long long m = new_of_old[i];
         if (to_internal)
-            dst[m * J + j] = src[q];
+            dst[m * stride + j] = src[q];
         else
-            dst[q] = src[m * J + j];
+            dst[q] = src[m * stride + j];
     }
 }
 
-// A^(n) initial values, written at the internal row of every caller-numbered row
-__global__ void __launch_bounds__(256) init_factor_kernel(float* __restrict__ out, long long rows, int J,
+__global__ void __launch_bounds__(256) init_factor_kernel(float* __restrict__ out, long long rows, int J, int stride,
                                                           const int32_t* __restrict__ new_of_old, uint64_t init_seed,
                                                           uint32_t array_id) {
     const long long total = rows * J;
@@ -370,7 +375,7 @@ __global__ void __launch_bounds__(256) init_factor_kernel(float* __restrict__ ou
          q += (long long)gridDim.x * blockDim.x) {
         const long long i = q / J;
         const int j = (int)(q - i * J);
-        out[(long long)new_of_old[i] * J + j] = init_value(init_seed, array_id, (uint64_t)q);
+        out[(long long)new_of_old[i] * stride + j] = init_value(init_seed, array_id, (uint64_t)q);
     }
 }
 

@@ -42,10 +42,10 @@ def oracle_state(w):
     return oracle.init_factors(w.init_seed, w.dims, w.J, w.R)
 
 
-def one_step_case(w, idx, vals, A0=None, B0=None, seed=None, kernel=None, tiles=False):
+def one_step_case(w, idx, vals, A0=None, B0=None, seed=None, kernel=None, tiles=False, flags=0):
     seed = w.sample_seed0 if seed is None else seed
     draw = oracle.sample_positions_tiles if tiles else oracle.sample_positions
-    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed, flags=flags) as ft:
         if tiles:
             ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
         if kernel:
@@ -220,21 +220,24 @@ TINY = [
 ]
 
 
+@pytest.mark.parametrize("layout", ["padded", "exact"])
 @pytest.mark.parametrize("kernel", ["auto", "generic", "tiled"])
 @pytest.mark.parametrize("order,dims,nnz,J,R,M", TINY)
-def test_one_step_small_shapes(order, dims, nnz, J, R, M, kernel):
+def test_one_step_small_shapes(order, dims, nnz, J, R, M, kernel, layout):
     """Every gradient-kernel variant on every small shape: "auto" is the specialised J = R = 16 kernel
-    where it applies and the tiled matrix-core kernel elsewhere."""
-    announce("tiny order=%d dims=%r J=%r R=%d M=%d kernel=%s" % (order, dims, J, R, M, kernel))
+    where it applies (ranks up to 16 are held padded to 16 for it unless the exact layout is asked for)
+    and the tiled matrix-core kernel elsewhere."""
+    flags = binding.FTK_LAYOUT_EXACT if layout == "exact" else 0
+    announce("tiny order=%d dims=%r J=%r R=%d M=%d kernel=%s layout=%s" % (order, dims, J, R, M, kernel, layout))
     w = synth.tiny_workload(order, dims, nnz, J, R, M, seed=11 + order, values="normal")
     w = synth.replace(w, lr_A=1e-2, lr_B=1e-2)
     idx, vals = synth.make_tensor(w)
     if kernel == "tiled" and order > 8:      # built for orders up to 8: must say so, not misbehave
         with pytest.raises(binding.FtkError) as e:
-            one_step_case(w, idx, vals, kernel=kernel)
+            one_step_case(w, idx, vals, kernel=kernel, flags=flags)
         assert e.value.code == binding.FTK_EUNSUPPORTED
         return
-    one_step_case(w, idx, vals, kernel=kernel)
+    one_step_case(w, idx, vals, kernel=kernel, flags=flags)
 
 
 def _random_case(case_seed):
@@ -271,9 +274,13 @@ def test_one_step_random_shapes(case_seed):
     # (high orders with ranks above 32 do not fit), the one-lane-per-sample kernel keeps N R columns per lane
     # there; a shape none of them takes is refused by ftk_create with FTK_EUNSUPPORTED
     ran = []
-    for kernel, tiles in ((None, False), ("generic", False), ("tiled", case_seed % 2 == 1)):
+    # the default layout (ranks up to 16 padded to 16) with the kernel the library picks, the exact layout
+    # with every variant
+    exact = binding.FTK_LAYOUT_EXACT
+    for kernel, tiles, flags in ((None, False, 0), (None, case_seed % 2 == 0, exact), ("generic", False, exact),
+                                 ("tiled", case_seed % 2 == 1, exact)):
         try:
-            gA, gB, A, B = one_step_case(w, idx, vals, kernel=kernel, tiles=tiles)
+            gA, gB, A, B = one_step_case(w, idx, vals, kernel=kernel, tiles=tiles, flags=flags)
             assert all(np.isfinite(x).all() for x in A + B)
             ran.append(kernel or "auto")
         except binding.FtkError as e:
@@ -341,7 +348,7 @@ def test_matrix_core_kernel_with_ranks_off_the_block_size(order, dims, J, R, zip
     idx, vals = synth.make_tensor(w)
     for tiles in (False, True):
         announce("ranks off the block size: J=%r R=%d%s" % (J, R, ", tiles" if tiles else ""))
-        one_step_case(w, idx, vals, kernel="tiled", tiles=tiles)
+        one_step_case(w, idx, vals, kernel="tiled", tiles=tiles, flags=binding.FTK_LAYOUT_EXACT)
 
 
 @pytest.mark.parametrize("name,nnz,M,dims", [
