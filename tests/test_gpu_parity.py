@@ -213,6 +213,7 @@ TINY = [
     (4, (9, 8, 7, 6), 1500, (2, 2, 2, 2), 3, 777),
     (5, (6, 5, 4, 3, 7), 800, (2, 1, 3, 2, 2), 5, 129),
     (6, (50,) * 6, 4000, (8,) * 6, 16, 2049),
+    (6, (40, 30, 20, 10, 12, 9), 4000, (16,) * 6, 16, 1500),  # J = R = 16 at order 6: "auto" is the tiled kernel there
     (8, (5,) * 8, 600, (2,) * 8, 2, 65),
     (3, (10, 10, 10), 100, (5, 7, 3), 11, 1),
     (3, (300, 200, 100), 3000, (32, 32, 32), 32, 513),
@@ -221,7 +222,7 @@ TINY = [
 
 
 @pytest.mark.parametrize("layout", ["padded", "exact"])
-@pytest.mark.parametrize("kernel", ["auto", "generic", "tiled"])
+@pytest.mark.parametrize("kernel", ["auto", "generic", "tiled", "mfma16"])
 @pytest.mark.parametrize("order,dims,nnz,J,R,M", TINY)
 def test_one_step_small_shapes(order, dims, nnz, J, R, M, kernel, layout):
     """Every gradient-kernel variant on every small shape: "auto" is the specialised J = R = 16 kernel
@@ -237,6 +238,16 @@ def test_one_step_small_shapes(order, dims, nnz, J, R, M, kernel, layout):
             one_step_case(w, idx, vals, kernel=kernel, flags=flags)
         assert e.value.code == binding.FTK_EUNSUPPORTED
         return
+    if kernel == "mfma16":
+        # by name: where the (possibly padded) ranks are all 16 and the order is at most 6, also at order 6,
+        # which "auto" gives to the tiled kernel; refused elsewhere
+        fits = 2 <= order <= 6 and ((set(J) == {16} and R == 16) or (layout == "padded" and order <= 5 and max(J) <= 16 and R <= 16))
+        fits = fits or (order == 1 and J == (16,) and R == 16)
+        if not fits:
+            with pytest.raises(binding.FtkError) as e:
+                one_step_case(w, idx, vals, kernel=kernel, flags=flags)
+            assert e.value.code == binding.FTK_EUNSUPPORTED
+            return
     one_step_case(w, idx, vals, kernel=kernel, flags=flags)
 
 
