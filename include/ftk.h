@@ -224,7 +224,7 @@ int ftk_get_timing(ftk_ctx* ctx, int which, double* total_ms, int64_t* launches,
  * ("auto").  ftk_set_kernel forces one by name; "auto" restores the default.
  * FTK_EUNSUPPORTED if the named variant is not built for this shape.  The variants:
  *   "mfma16"   J_n = R = 16 for every mode, order <= 6, I_n < 2^24, all A^(n) together below 2 GB
- *   "tiled"    order <= 8, J_n <= 64, R <= 64, I_n * J_n < 2^28, and room in LDS for the core
+ *   "tiled"    order <= 8 with J_n <= 64, R <= 64 (order 9 and 10: J_n <= 16, R <= 16), I_n * J_n < 2^28, and room in LDS for the core
  *              factors padded to multiples of 16 (twice)
  *   "generic"  one lane per sample: any order <= FTK_MAX_ORDER and any ranks for which
  *              512 * order * R + 4 * sum_n J_n R bytes fit in LDS

@@ -360,7 +360,10 @@ int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
         case 5: return launch_tiled_n<5>(c, g);
         case 6: return launch_tiled_n<6>(c, g);
         case 7: return launch_tiled_n<7>(c, g);
-        default: return launch_tiled_n<8>(c, g);
+        case 8: return launch_tiled_n<8>(c, g);
+        // orders 9 and 10 (the paper's sweep ends at 10) are built for ranks up to 16 only
+        case 9: return launch_tiled_npw<9, 1, 8>(c, g);
+        default: return launch_tiled_npw<10, 1, 8>(c, g);
     }
 }
 
@@ -448,7 +451,13 @@ int launch_errors(ftk_ctx* c, Coo coo, long long nnz, double* host_sums) {
             case 5: launch_errors_tiled_n<5>(c, coo, nnz); break;
             case 6: launch_errors_tiled_n<6>(c, coo, nnz); break;
             case 7: launch_errors_tiled_n<7>(c, coo, nnz); break;
-            default: launch_errors_tiled_n<8>(c, coo, nnz); break;
+            case 8: launch_errors_tiled_n<8>(c, coo, nnz); break;
+            case 9:
+                c->tiled_x4 ? launch_errors_tiled_npx<9, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<9, 1, false>(c, coo, nnz);
+                break;
+            default:
+                c->tiled_x4 ? launch_errors_tiled_npx<10, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<10, 1, false>(c, coo, nnz);
+                break;
         }
     } else {
         const int b_in_lds = (size_t)c->L.B_total * 4 <= 65536 - 256;
@@ -569,7 +578,7 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     c->mfma16_ok = c->mfma16_ok && c->A_total * 4 < 0x7fffffc0LL;
     {
         int pm = c->L.R;
-        c->tiled_ok = N <= 8 && c->L.R <= 64 && c->max_lds >= 131072;
+        c->tiled_ok = N <= kTiledMaxOrder && c->L.R <= 64 && c->max_lds >= 131072;
         c->tiled_x4 = true;
         for (int n = 0; n < N; ++n) {
             pm = std::max(pm, c->L.J[n]);
@@ -577,6 +586,7 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
             c->tiled_ok = c->tiled_ok && c->L.J[n] <= 64 && dims[n] * c->L.J[n] < (1LL << 28);   // a mode's rows end below 2^30 bytes
         }
         c->tiled_P = pm <= 16 ? 1 : pm <= 32 ? 2 : 4;
+        if (N > 8 && c->tiled_P != 1) c->tiled_ok = false;   // orders 9, 10: instances for ranks up to 16 only
         c->tiled_waves = c->tiled_P == 4 ? 4 : 8;
         if (4LL * (long long)tiled_lds_floats(N, c->tiled_P, c->tiled_waves, 16) + 1024 > c->max_lds) c->tiled_ok = false;
     }
@@ -1069,7 +1079,7 @@ int ftk_set_kernel(ftk_ctx* c, const char* name) {
         return FTK_OK;
     }
     if (!strcmp(name, "tiled")) {
-        if (!c->tiled_ok) return fail(c, FTK_EUNSUPPORTED, "tiled needs order <= 8, J_n <= 64, R <= 64 and padded core factors that fit LDS twice");
+        if (!c->tiled_ok) return fail(c, FTK_EUNSUPPORTED, "tiled needs order <= 8 with J_n, R <= 64 (order 9, 10: <= 16) and padded core factors that fit LDS twice");
         c->variant = V_TILED;
         pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
         return FTK_OK;

@@ -1,4 +1,4 @@
-// Shape-generic kernels: any order N <= 8, any J_n, any R within the LDS budget.
+// Shape-generic kernels: any order N <= 10, any J_n, any R within the LDS budget.
 // One lane owns one sampled nonzero.  These are the reference-speed path; shapes with a
 // specialised kernel never run grad_generic in the default configuration.
 #pragma once

@@ -1,4 +1,4 @@
-// Matrix-core gradient and evaluation kernels for general shapes: any order N <= 8, any J_n <= 16 P,
+// Matrix-core gradient and evaluation kernels for general shapes: any order N <= 8 (N <= 10 at P = 1), any J_n <= 16 P,
 // any R <= 16 P with P in {1, 2, 4} (ranks are zero-padded to 16 P).  Same method as the J = R = 16
 // kernel (see ftk_kernels_mfma16.hpp for the operand layouts), with every 16 P x 16 P contraction
 // cut into P x P blocks of v_mfma_f32_16x16x4_f32 and the core factors B^(n) (and their
@@ -494,7 +494,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 // rows gathered 16 bytes per lane in the operand layout (X4) or 16 lanes per 64 bytes and
 // transposed in LDS, projections on the matrix core, errors summed in double.
 // ---------------------------------------------------------------------------------------------
-constexpr int kTiledMaxOrder = 8;
+constexpr int kTiledMaxOrder = 10;   // orders 9 and 10 are instantiated for P = 1 only
 struct TiledModeBytes {
     unsigned int v[kTiledMaxOrder];   // I_n * J_n * 4: size of mode n's rows in A
 };
