@@ -229,16 +229,6 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) actY[v] = base + 4 * g4 + v < M;
             const float x = sval[sub * 16 + c];
-            int iY[N][4];
-#pragma unroll
-            for (int n = 0; n < N; ++n) {
-                const int4 r = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
-                iY[n][0] = r.x;
-                iY[n][1] = r.y;
-                iY[n][2] = r.z;
-                iY[n][3] = r.w;
-            }
-
             // both layouts of the tile's rows: aX[k] = component 16 jb + 4g + k of sample c (only used
             // by the projections), aY[n][jb][v] = component 16 jb + c of sample 4g + v
             float aY[N][P][4];
@@ -383,9 +373,12 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 unsigned int tbase[4];      // LDS address of its table row, or of the row nobody reads
                 bool tab[4];
                 float onehot[4];
+                // row numbers of samples 4g .. 4g+3 in this mode (read here, not kept for all modes at once)
+                const int4 rows4 = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
+                const int rowv[4] = {rows4.x, rows4.y, rows4.z, rows4.w};
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int row = iY[n][v];
+                    const int row = rowv[v];
                     abase[v] = (actY[v] && row >= g.K[n]) ? (unsigned int)(row * g.J[n] * 4) : kDropped;
                     tab[v] = actY[v] && row < g.K[n] && row >= g.top[n];
                     tbase[v] = tab[v] ? hot_addr + (unsigned int)((g.hot_off[n] + row) * D * 4) : sink_addr;
