@@ -15,10 +15,12 @@
 // on).  The factor rows of a tile are requested one tile ahead.  Where every J_n is a multiple of
 // four (X4) a lane fetches 16 bytes of its sample's row, which is the operand layout of the
 // projections, and the other layout comes from an LDS transpose; otherwise lanes fetch single
-// floats in the layout of the gradient and the transpose runs the other way.  Factor-row gradients take the same
-// three routes as in the J = R = 16 kernel: rows 0..15 of a mode through the one-hot product, rows
-// [16, K_n) into an LDS table per workgroup (compare-and-swap adds), all other rows through float
-// atomics issued by every lane with out-of-range offsets for lanes that have nothing to add.
+// floats in the layout of the gradient and the transpose runs the other way.
+// Factor-row gradients take the same three routes as in the J = R = 16 kernel: rows 0..15 of a
+// mode through the one-hot product, rows [16, K_n) into an LDS table per workgroup
+// (compare-and-swap adds), all other rows through float atomics.  Both the atomic and the table
+// swap are issued by every lane for every element, without a test: an element that takes another
+// route gets an out-of-range buffer offset resp. the address of an LDS row nobody reads.
 // The core gradient lives in matrix-core accumulators for the whole kernel and leaves each wave
 // as one table of plain stores.
 #pragma once
