@@ -566,12 +566,17 @@ def test_c2_full_size_one_step():
     assert moved_B > 1e-2, moved_B
 
 
-@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
+@pytest.mark.parametrize("name", ["C3", "C4", "C5", "C2 at J = R = 8"])
 def test_other_workloads_full_size_one_step(name):
     """The other named workloads at full size, on the kernel the library picks for them: the sample
     set bit-exact and every parameter after one synchronous step against the oracle (up to half a
-    minute of one host core for the 4e6 samples of C3 and the 64 x 64 contractions of C5)."""
-    w = synth.replace(synth.WORKLOADS[name], **TEST_STEP_SIZES[name])
+    minute of one host core for the 4e6 samples of C3 and the 64 x 64 contractions of C5).  The C2
+    tensor at J = R = 8, the paper's most used ranks, runs on the J = R = 16 kernel through the padded
+    layout: the same comparison at full size for that route."""
+    if name == "C2 at J = R = 8":
+        w = synth.replace(synth.WORKLOADS["C2"], J=(8, 8, 8), R=8, lr_A=1e-7, lr_B=1e-2)
+    else:
+        w = synth.replace(synth.WORKLOADS[name], **TEST_STEP_SIZES[name])
     announce("%s full size: generating" % name)
     idx, vals = synth.make_tensor(w)
     announce("%s full size: step" % name)
