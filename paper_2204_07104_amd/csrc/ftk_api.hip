@@ -228,11 +228,13 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = 
                     c->order * c->L.R, c->L.B_total);
     const int T = c->gen_threads;
     const int grid = blocks_for(c->n_samples, T, c->num_cu * 4);
+    // The limit is a property of the kernel, shared by every context of the process: always the device's
+    // maximum, so that contexts of different shapes (or on different host threads) cannot lower it for each other.
     if (c->gen_lds_bytes > 65536) {
         FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_generic_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->gen_lds_bytes));
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds));
         FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(factor_phase_generic_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->gen_lds_bytes));
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds));
     }
     Bracket t(c, FTK_K_GRAD);
     if (modewise) {
@@ -249,7 +251,7 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = 
 template <int N>
 int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
     FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_mfma16_kernel<N>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->mfma_lds_bytes));
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds));
     Bracket t(c, FTK_K_GRAD);
     hipLaunchKernelGGL(grad_mfma16_kernel<N>, dim3(c->mfma_grid), dim3(kMfmaThreads), c->mfma_lds_bytes, c->stream, g);
     FTK_HIP(c, hipGetLastError());
@@ -299,7 +301,7 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
 template <int N, int P, int WAVES, bool X4>
 int launch_tiled_npwx(ftk_ctx* c, const TiledArgs& g) {
     FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->tiled_lds_bytes));
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds));
     Bracket t(c, FTK_K_GRAD);
     hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES, X4>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
                        c->stream, g);
@@ -415,7 +417,7 @@ void launch_errors_tiled_npx(ftk_ctx* c, const Coo& coo, long long nnz) {
     TiledModeBytes mode_bytes = {};
     for (int n = 0; n < N; ++n) mode_bytes.v[n] = (unsigned int)(c->dims[n] * c->L.J[n] * 4);
     hipFuncSetAttribute(reinterpret_cast<const void*>(errors_tiled_kernel<N, P, X4>),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                        hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds - 1024);   // the kernel also has 64 bytes of static LDS
     hipLaunchKernelGGL((errors_tiled_kernel<N, P, X4>), dim3(grid), dim3(256), lds, c->stream, coo, (uint64_t)nnz,
                        (const float*)c->d_A, (const float*)c->d_B, c->L, mode_bytes, c->d_sums);
 }
