@@ -694,3 +694,40 @@ def test_training_driver_learns_a_planted_tensor(mode, sampling):
     assert rmse1 < 0.2 * rmse0, out.getvalue()
     assert mae1 < 0.2 * mae0, out.getvalue()
     assert mae1 <= rmse1
+
+
+def test_three_contexts_interleaved():
+    """Three contexts of different shapes alive at once, stepping in turn (the same kernel instantiations with
+    different LDS sizes, tables and grids): each follows its own oracle as if it were alone."""
+    announce("three contexts interleaved")
+    w1 = synth.replace(synth.WORKLOADS["C2"].scaled(nnz=200_000, n_samples=20_000, dims=(4_800, 1_777, 220)), lr_A=2e-7, lr_B=1e-4)
+    w2 = synth.replace(synth.tiny_workload(3, (60, 50, 40), 3_000, (16, 16, 16), 16, 700, seed=5, values="normal"),
+                       lr_A=1e-6, lr_B=1e-6)
+    w3 = synth.replace(synth.tiny_workload(3, (300, 200, 100), 9_000, (32, 20, 32), 24, 2_500, seed=6, values="normal"),
+                       lr_A=1e-8, lr_B=1e-8)
+    cases = []
+    for w in (w1, w2, w3):
+        idx, vals = synth.make_tensor(w)
+        A, B = oracle_state(w)
+        cases.append((w, idx, vals, A, B, binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed)))
+    try:
+        for t in range(3):
+            for w, idx, vals, A, B, ft in cases:
+                ft.ftk_sample(900 + t, w.n_samples)
+            for w, idx, vals, A, B, ft in reversed(cases):
+                ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+            for w, idx, vals, A, B, ft in cases:
+                pos = oracle.sample_positions(900 + t, w.n_samples, w.nnz)
+                oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+        for w, idx, vals, A, B, ft in cases:
+            gA, gB = ft.ftk_get_factors()
+            A0, B0 = oracle_state(w)
+            assert all(np.isfinite(o).all() for o in A + B)
+            assert max(float(np.abs(a - a0).max()) for a, a0 in zip(A, A0)) > 1e-5   # the steps moved something
+            for g, o in zip(gA + gB, A + B):
+                err = np.abs(g.astype(np.float64) - o)
+                assert float((err - 3 * (ATOL + RTOL * np.abs(o))).max()) <= 0.0, w.name
+            assert ft.ftk_rmse() == pytest.approx(oracle.rmse(w.dims, idx, vals, A, B), rel=1e-5)
+    finally:
+        for case in cases:
+            case[-1].close()
