@@ -47,8 +47,10 @@ def algorithmic_flops_per_sample(w) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=5)
+    # 1000 steps are ~0.13 s of GPU time on C2 (about 1 s on C3): long enough for steady state, the first
+    # launches after a synchronisation run into an empty queue and a GPU that has clocked down
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "O5", "O6", "O7", "O8", "O9", "O10"],
                     help="C2 is the headline workload; O5..O10 are the paper's order-scalability sweep")
     ap.add_argument("--kernel", default="auto")
