@@ -234,6 +234,18 @@ int ftk_get_timing(ftk_ctx* ctx, int which, double* total_ms, int64_t* launches,
 int ftk_set_kernel(ftk_ctx* ctx, const char* name);
 const char* ftk_kernel_name(const ftk_ctx* ctx);
 
+/*
+ * Which factor rows the current gradient kernel sums on chip instead of adding them to memory one
+ * sample at a time (the sum over the samples that hit a row in Eq. Gradient_low_rank is the same
+ * either way; this only reports where it is formed).  Rows of a mode are ranked by how often they
+ * occur in Omega, most frequent first, ties by ascending row number; for the sample count of the
+ * last ftk_sample (or a default before the first) the kernel keeps ranks [0, K_out[n]) of mode n
+ * in a per-workgroup table, of which ranks [0, top_out[n]) go through a one-hot matrix product;
+ * all other rows are updated with float atomics.  K_out, top_out: host int32[order], either may be
+ * NULL.  The one-lane-per-sample variant keeps no table: all zeros.  For tests and tuning.
+ */
+int ftk_get_table_rows(ftk_ctx* ctx, int32_t* K_out, int32_t* top_out);
+
 /* Message for the most recent failure on this context (ctx == NULL: of ftk_create on this thread). */
 const char* ftk_last_error(const ftk_ctx* ctx);
 

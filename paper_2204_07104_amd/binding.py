@@ -30,7 +30,7 @@ SYMBOLS = [
     "ftk_create", "ftk_destroy", "ftk_sample", "ftk_get_samples", "ftk_sgd_step", "ftk_rmse", "ftk_mae",
     "ftk_evaluate", "ftk_step_size", "ftk_set_sampling",
     "ftk_get_factors", "ftk_set_factors", "ftk_set_mode", "ftk_set_stream", "ftk_set_timing",
-    "ftk_get_timing", "ftk_set_kernel", "ftk_kernel_name", "ftk_last_error",
+    "ftk_get_timing", "ftk_set_kernel", "ftk_kernel_name", "ftk_get_table_rows", "ftk_last_error",
 ]
 
 
@@ -113,6 +113,8 @@ def load():
     L.ftk_set_kernel.restype = C.c_int
     L.ftk_kernel_name.argtypes = [vp]
     L.ftk_kernel_name.restype = C.c_char_p
+    L.ftk_get_table_rows.argtypes = [vp, vp, vp]
+    L.ftk_get_table_rows.restype = C.c_int
     L.ftk_last_error.argtypes = [vp]
     L.ftk_last_error.restype = C.c_char_p
     _lib = L
@@ -289,3 +291,11 @@ class FastTucker:
 
     def ftk_kernel_name(self) -> str:
         return self._L.ftk_kernel_name(self._ctx).decode()
+
+    def ftk_get_table_rows(self) -> Tuple[np.ndarray, np.ndarray]:
+        """(K, top): per mode, how many of the most frequent rows are summed in the workgroup tables /
+        through the one-hot product for the current |Psi|."""
+        K = np.zeros(self.order, dtype=np.int32)
+        top = np.zeros(self.order, dtype=np.int32)
+        self._check(self._L.ftk_get_table_rows(self._ctx, K.ctypes.data, top.ctypes.data))
+        return K, top

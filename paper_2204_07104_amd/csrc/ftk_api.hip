@@ -99,6 +99,7 @@ struct ftk_ctx {
 
     bool timing = false;
     TimingSlot slots[FTK_K_COUNT];
+    std::vector<const void*> lds_limit_raised;   // kernels whose dynamic-LDS limit this context has raised
 
     std::string err;
 };
@@ -139,6 +140,21 @@ int check_device(ftk_ctx* c) {
     if (hipGetDevice(&dev) != hipSuccess) return fail(c, FTK_EDEVICE, "hipGetDevice failed");
     if (dev != c->device)
         return fail(c, FTK_ESTATE, "current HIP device is %d, the context was created on device %d", dev, c->device);
+    return FTK_OK;
+}
+
+// Raise a kernel's dynamic-LDS limit to the device maximum, once per context and kernel (the limit is
+// a property of the kernel on this device, so raising it again is harmless but costs a runtime call
+// per step).  Always the device's maximum, so that contexts of different shapes cannot lower it for
+// each other.
+int raise_lds_limit(ftk_ctx* c, const void* kernel, int bytes) {
+    for (const void* k : c->lds_limit_raised)
+        if (k == kernel) return FTK_OK;
+    FTK_HIP(c, hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    try {
+        c->lds_limit_raised.push_back(kernel);
+    } catch (...) {   // not remembered: the next launch sets it again
+    }
     return FTK_OK;
 }
 
@@ -228,13 +244,9 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = 
                     c->order * c->L.R, c->L.B_total);
     const int T = c->gen_threads;
     const int grid = blocks_for(c->n_samples, T, c->num_cu * 4);
-    // The limit is a property of the kernel, shared by every context of the process: always the device's
-    // maximum, so that contexts of different shapes (or on different host threads) cannot lower it for each other.
     if (c->gen_lds_bytes > 65536) {
-        FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_generic_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds));
-        FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(factor_phase_generic_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds));
+        if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_generic_kernel), c->max_lds)) return rc;
+        if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(factor_phase_generic_kernel), c->max_lds)) return rc;
     }
     Bracket t(c, FTK_K_GRAD);
     if (modewise) {
@@ -250,8 +262,7 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = 
 
 template <int N>
 int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
-    FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_mfma16_kernel<N>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds));
+    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_mfma16_kernel<N>), c->max_lds)) return rc;
     Bracket t(c, FTK_K_GRAD);
     hipLaunchKernelGGL(grad_mfma16_kernel<N>, dim3(c->mfma_grid), dim3(kMfmaThreads), c->mfma_lds_bytes, c->stream, g);
     FTK_HIP(c, hipGetLastError());
@@ -300,8 +311,7 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
 
 template <int N, int P, int WAVES, bool X4>
 int launch_tiled_npwx(ftk_ctx* c, const TiledArgs& g) {
-    FTK_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds));
+    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4>), c->max_lds)) return rc;
     Bracket t(c, FTK_K_GRAD);
     hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES, X4>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
                        c->stream, g);
@@ -410,25 +420,26 @@ void launch_errors_mfma16_n(ftk_ctx* c, const Coo& coo, long long nnz) {
 }
 
 template <int N, int P, bool X4>
-void launch_errors_tiled_npx(ftk_ctx* c, const Coo& coo, long long nnz) {
+int launch_errors_tiled_npx(ftk_ctx* c, const Coo& coo, long long nnz) {
     const long long groups = (nnz + 63) / 64;
     const int grid = blocks_for(groups, 4, c->num_cu * 8);
     const size_t lds = 4 * ((size_t)N * 256 * P * P + 4 * (size_t)tiled_wave_scratch(N, P));
     TiledModeBytes mode_bytes = {};
     for (int n = 0; n < N; ++n) mode_bytes.v[n] = (unsigned int)(c->dims[n] * c->L.J[n] * 4);
-    hipFuncSetAttribute(reinterpret_cast<const void*>(errors_tiled_kernel<N, P, X4>),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, c->max_lds - 1024);   // the kernel also has 64 bytes of static LDS
+    // the kernel also has 64 bytes of static LDS
+    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(errors_tiled_kernel<N, P, X4>), c->max_lds - 1024)) return rc;
     hipLaunchKernelGGL((errors_tiled_kernel<N, P, X4>), dim3(grid), dim3(256), lds, c->stream, coo, (uint64_t)nnz,
                        (const float*)c->d_A, (const float*)c->d_B, c->L, mode_bytes, c->d_sums);
+    return FTK_OK;
 }
 
 template <int N>
-void launch_errors_tiled_n(ftk_ctx* c, const Coo& coo, long long nnz) {
+int launch_errors_tiled_n(ftk_ctx* c, const Coo& coo, long long nnz) {
     const bool x4 = c->tiled_x4;
     switch (c->tiled_P) {
-        case 1: x4 ? launch_errors_tiled_npx<N, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 1, false>(c, coo, nnz); break;
-        case 2: x4 ? launch_errors_tiled_npx<N, 2, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 2, false>(c, coo, nnz); break;
-        default: x4 ? launch_errors_tiled_npx<N, 4, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 4, false>(c, coo, nnz); break;
+        case 1: return x4 ? launch_errors_tiled_npx<N, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 1, false>(c, coo, nnz);
+        case 2: return x4 ? launch_errors_tiled_npx<N, 2, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 2, false>(c, coo, nnz);
+        default: return x4 ? launch_errors_tiled_npx<N, 4, true>(c, coo, nnz) : launch_errors_tiled_npx<N, 4, false>(c, coo, nnz);
     }
 }
 
@@ -445,22 +456,24 @@ int launch_errors(ftk_ctx* c, Coo coo, long long nnz, double* host_sums) {
             default: launch_errors_mfma16_n<6>(c, coo, nnz); break;
         }
     } else if (c->variant == V_TILED && c->rec_words == 4 * ((c->order + 1 + 3) / 4)) {
+        int rc = FTK_OK;
         switch (c->order) {
-            case 1: launch_errors_tiled_n<1>(c, coo, nnz); break;
-            case 2: launch_errors_tiled_n<2>(c, coo, nnz); break;
-            case 3: launch_errors_tiled_n<3>(c, coo, nnz); break;
-            case 4: launch_errors_tiled_n<4>(c, coo, nnz); break;
-            case 5: launch_errors_tiled_n<5>(c, coo, nnz); break;
-            case 6: launch_errors_tiled_n<6>(c, coo, nnz); break;
-            case 7: launch_errors_tiled_n<7>(c, coo, nnz); break;
-            case 8: launch_errors_tiled_n<8>(c, coo, nnz); break;
+            case 1: rc = launch_errors_tiled_n<1>(c, coo, nnz); break;
+            case 2: rc = launch_errors_tiled_n<2>(c, coo, nnz); break;
+            case 3: rc = launch_errors_tiled_n<3>(c, coo, nnz); break;
+            case 4: rc = launch_errors_tiled_n<4>(c, coo, nnz); break;
+            case 5: rc = launch_errors_tiled_n<5>(c, coo, nnz); break;
+            case 6: rc = launch_errors_tiled_n<6>(c, coo, nnz); break;
+            case 7: rc = launch_errors_tiled_n<7>(c, coo, nnz); break;
+            case 8: rc = launch_errors_tiled_n<8>(c, coo, nnz); break;
             case 9:
-                c->tiled_x4 ? launch_errors_tiled_npx<9, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<9, 1, false>(c, coo, nnz);
+                rc = c->tiled_x4 ? launch_errors_tiled_npx<9, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<9, 1, false>(c, coo, nnz);
                 break;
             default:
-                c->tiled_x4 ? launch_errors_tiled_npx<10, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<10, 1, false>(c, coo, nnz);
+                rc = c->tiled_x4 ? launch_errors_tiled_npx<10, 1, true>(c, coo, nnz) : launch_errors_tiled_npx<10, 1, false>(c, coo, nnz);
                 break;
         }
+        if (rc != FTK_OK) return rc;
     } else {
         const int b_in_lds = (size_t)c->L.B_total * 4 <= 65536 - 256;
         const size_t lds = b_in_lds ? (size_t)c->L.B_total * 4 : 0;
@@ -1020,6 +1033,7 @@ int ftk_set_mode(ftk_ctx* c, int mode) {
 
 int ftk_set_stream(ftk_ctx* c, void* hip_stream) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     FTK_HIP(c, hipStreamSynchronize(c->stream));
     drop_pending(c);
     c->stream = (hipStream_t)hip_stream;
@@ -1028,6 +1042,7 @@ int ftk_set_stream(ftk_ctx* c, void* hip_stream) {
 
 int ftk_set_timing(ftk_ctx* c, int enabled) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     FTK_HIP(c, hipStreamSynchronize(c->stream));
     drop_pending(c);
     for (auto& s : c->slots) {
@@ -1041,6 +1056,7 @@ int ftk_set_timing(ftk_ctx* c, int enabled) {
 int ftk_get_timing(ftk_ctx* c, int which, double* total_ms, int64_t* launches, int reset) {
     if (!c) return FTK_EINVAL;
     if (which < 0 || which >= FTK_K_COUNT) return fail(c, FTK_EINVAL, "unknown kernel slot %d", which);
+    if (const int rc_dev = check_device(c)) return rc_dev;
     FTK_HIP(c, hipStreamSynchronize(c->stream));
     for (auto& s : c->slots) {
         for (auto& p : s.pending) {
@@ -1090,6 +1106,16 @@ int ftk_set_kernel(ftk_ctx* c, const char* name) {
 }
 
 const char* ftk_kernel_name(const ftk_ctx* c) { return c ? kVariantNames[c->variant] : "none"; }
+
+int ftk_get_table_rows(ftk_ctx* c, int32_t* K_out, int32_t* top_out) {
+    if (!c) return FTK_EINVAL;
+    const bool table = c->variant != V_GENERIC;
+    for (int n = 0; n < c->order; ++n) {
+        if (K_out) K_out[n] = table ? c->hot_K[n] : 0;
+        if (top_out) top_out[n] = table ? c->hot_top[n] : 0;
+    }
+    return FTK_OK;
+}
 
 const char* ftk_last_error(const ftk_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
 

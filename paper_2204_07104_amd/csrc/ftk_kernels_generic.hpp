@@ -318,11 +318,37 @@ __global__ void __launch_bounds__(256) check_range_kernel(const int32_t* __restr
     if (mine) atomicAdd(bad, mine);
 }
 
-// per-row occurrence counts of one mode over all stored entries
+// Per-row occurrence counts of one mode over all stored entries.  In a skewed mode a handful of
+// rows hold a tenth of all entries each, and global atomics on one address serialise; so every
+// workgroup counts through a small direct-mapped cache in LDS (a slot belongs to the first row
+// number that hashes there) and only rows that find their slot taken go to memory one by one.
+// The cache is added to the global counters once, when the workgroup is done.
+constexpr int kHistSlots = 4096;
 __global__ void __launch_bounds__(256) histogram_kernel(const int32_t* __restrict__ idx, uint64_t nnz,
                                                         unsigned int* __restrict__ counts) {
-    for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (uint64_t)gridDim.x * blockDim.x)
-        atomicAdd(counts + idx[p], 1u);
+    __shared__ int owner[kHistSlots];
+    __shared__ unsigned int cached[kHistSlots];
+    for (int q = threadIdx.x; q < kHistSlots; q += 256) {
+        owner[q] = -1;
+        cached[q] = 0u;
+    }
+    __syncthreads();
+    for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (uint64_t)gridDim.x * blockDim.x) {
+        const int row = idx[p];
+        const unsigned int slot = ((unsigned int)row * 2654435761u) >> 20;   // top 12 bits of a multiplicative hash
+        int who = owner[slot];
+        if (who == -1) {
+            who = atomicCAS(&owner[slot], -1, row);
+            if (who == -1) who = row;
+        }
+        if (who == row)
+            atomicAdd(&cached[slot], 1u);
+        else
+            atomicAdd(counts + row, 1u);
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < kHistSlots; q += 256)
+        if (cached[q] != 0u) atomicAdd(counts + owner[q], cached[q]);
 }
 
 // word `slot` of every record <- new_of_old[idx[p]]  (or the value's bits when new_of_old == nullptr)

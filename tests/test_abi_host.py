@@ -72,6 +72,7 @@ def test_null_context_is_rejected_everywhere():
     assert L.ftk_set_stream(None, None) == binding.FTK_EINVAL
     assert L.ftk_set_timing(None, 1) == binding.FTK_EINVAL
     assert L.ftk_set_kernel(None, b"auto") == binding.FTK_EINVAL
+    assert L.ftk_get_table_rows(None, None, None) == binding.FTK_EINVAL
     L.ftk_destroy(None)
     assert L.ftk_kernel_name(None) is not None
 

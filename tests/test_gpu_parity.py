@@ -390,6 +390,89 @@ def test_signed_parameters_and_hot_rows():
 
 
 # ------------------------------------------------------------------------------------------------
+# rows that leave the chip one sample at a time: every single update has to be visible
+# ------------------------------------------------------------------------------------------------
+def frequency_rank(col, rows):
+    """Rank of every row of a mode by how often it occurs in Omega: most frequent first, ties by ascending
+    row number (the ranking ftk_get_table_rows refers to)."""
+    counts = np.bincount(col, minlength=rows)
+    by_rank = np.argsort(-counts, kind="stable")
+    rank = np.empty(rows, dtype=np.int64)
+    rank[by_rank] = np.arange(rows)
+    return rank
+
+
+COLD_ROW_CASES = [
+    # kernel, dims, power-law exponent per mode, J, R, stored entries, |Psi| (ragged last group), lr_A
+    ("mfma16", (40_000, 60_000, 1_500), (1.1, None, None), (16, 16, 16), 16, 400_000, 60_013, 1e-2),
+    ("mfma16", (60_000, 30_000), (None, 1.1), (16, 16), 16, 300_000, 50_001, 1e-2),
+    ("mfma16", (20_000, 50_000, 300, 40, 1_200), (1.1, None, None, None, None), (16,) * 5, 16, 300_000, 40_007, 0.3),
+    ("tiled", (30_000, 50_000, 900), (1.1, None, None), (32, 32, 32), 32, 300_000, 40_011, 1e-2),   # 32-wide blocks
+    ("tiled", (40_000, 60_000, 1_500), (1.1, None, None), (16, 16, 16), 16, 400_000, 60_013, 1e-2),
+]
+
+
+def cold_row_inputs(dims, zipf, J, R, nnz, M, lr_A):
+    """Many more rows than any on-chip table holds, most of them hit 0 to 3 times by Psi, and parameters of
+    both signs sized so that ONE hit moves a row's elements by about a hundred tolerances."""
+    w = synth.tiny_workload(len(dims), dims, nnz, J, R, M, seed=613, values="int1to5", zipf=zipf)
+    w = synth.replace(w, lr_A=lr_A, lr_B=1e-2)
+    idx, vals = synth.make_tensor(w)
+    rng = np.random.default_rng(97)
+    A0 = [rng.uniform(-0.5, 0.5, size=(w.dims[n], w.J[n])).astype(np.float32) for n in range(w.order)]
+    B0 = [rng.uniform(-0.5, 0.5, size=(w.J[n], w.R)).astype(np.float32) for n in range(w.order)]
+    return w, idx, vals, A0, B0
+
+
+def single_hit_rows_that_moved(w, idx, pos, K, A0, A1, least=1e-3):
+    """Rows outside the on-chip tables (rank >= K[n]) that exactly one sample of Psi hits and whose largest
+    element change under the oracle's step exceeds `least`; returns their number over all modes."""
+    total = 0
+    for n in range(w.order):
+        hits = np.bincount(idx[n][pos], minlength=w.dims[n])
+        cold = frequency_rank(idx[n], w.dims[n]) >= int(K[n])
+        moved = np.abs(A1[n].astype(np.float64) - A0[n].astype(np.float64)).max(axis=1)
+        total += int(np.count_nonzero((hits == 1) & cold & (moved > least)))
+    return total
+
+
+@pytest.mark.parametrize("tiles", [False, True])
+@pytest.mark.parametrize("kernel,dims,zipf,J,R,nnz,M,lr_A", COLD_ROW_CASES)
+def test_rows_outside_the_tables_hit_once_or_twice(kernel, dims, zipf, J, R, nnz, M, lr_A, tiles):
+    """The route that carries the rows no table holds (compacted lists of float atomics): tens of thousands
+    of rows per mode, far more than fit on chip, most of them hit by a single sample.  The step is sized so
+    that one hit moves an element by ~1e-3 to 1e-2 against a tolerance of ~1e-5: a dropped, doubled or
+    misdirected update of a single row fails the comparison.  The test itself checks that power: at least
+    10 000 rows outside the tables with exactly one hit each move by more than 1e-3 under the oracle's step."""
+    announce("rows outside the tables: kernel=%s dims=%r J=%r%s" % (kernel, dims, J, ", tile sampling" if tiles else ""))
+    w, idx, vals, A0, B0 = cold_row_inputs(dims, zipf, J, R, nnz, M, lr_A)
+    draw = oracle.sample_positions_tiles if tiles else oracle.sample_positions
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed, flags=binding.FTK_LAYOUT_EXACT) as ft:
+        ft.ftk_set_kernel(kernel)
+        assert ft.ftk_kernel_name() == kernel
+        if tiles:
+            ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
+        ft.ftk_set_factors(A0, B0)
+        ft.ftk_sample(w.sample_seed0, w.n_samples)
+        K, top = ft.ftk_get_table_rows()
+        pos = ft.ftk_get_samples()
+        want = draw(w.sample_seed0, w.n_samples, w.nnz)
+        assert np.array_equal(pos, want), "sample set differs from the oracle's"
+        ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+        gA, gB = ft.ftk_get_factors()
+    A, B = [a.copy() for a in A0], [b.copy() for b in B0]
+    oracle.sgd_step_sync(w.dims, idx, vals, A, B, want, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+    # all three routes carry rows: a one-hot mode, table rows, and far more rows than the tables hold
+    assert int(top.max()) == 16 and int(K.sum()) > int(top.sum()), (K, top)
+    assert sum(w.dims) > 20 * int(K.sum()), (K, w.dims)
+    n_single = single_hit_rows_that_moved(w, idx, want, K, A0, A)
+    announce("  tables hold %r rows, %d single-hit rows outside them move by more than 1e-3" % (K.tolist(), n_single))
+    assert n_single >= 10_000, n_single
+    assert_params_close(gA, A, "A")
+    assert_params_close(gB, B, "B")
+
+
+# ------------------------------------------------------------------------------------------------
 # invariants and error paths through the ABI
 # ------------------------------------------------------------------------------------------------
 def test_zero_learning_rate_leaves_parameters_bit_identical():
