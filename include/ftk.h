@@ -141,6 +141,27 @@ int ftk_get_samples(ftk_ctx* ctx, int64_t* pos_out);
 int ftk_sgd_step(ftk_ctx* ctx, float lr_A, float lr_B, float lambda_A, float lambda_B);
 
 /*
+ * ftk_sgd_step for callers that must not allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same step, same arguments, same result up to fp32
+ * summation order; the difference is where the gradient kernel's per-workgroup partial tables
+ * (factor-row sums and core-gradient sums, read back by the update pass of the same call) live:
+ * in a static array in device memory that belongs to the library's code, 32 MiB per GPU, held
+ * until the process ends, instead of the buffers ftk_create allocated.  The call itself performs
+ * no allocation of any kind (no hipMalloc / hipFree, no event creation: per-kernel timing is not
+ * recorded for it) -- it only launches the two kernels of a step on the context's stream.
+ *  - Matrix-core kernels only ("mfma16", "tiled") in FTK_SYNC or FTK_HOGWILD mode; the
+ *    one-lane-per-sample kernels keep Psi in arrays allocated on demand: FTK_EUNSUPPORTED.
+ *  - FTK_EUNSUPPORTED, with the sizes in ftk_last_error, if this shape and |Psi| need more than
+ *    the 32 MiB (workgroups x (table rows x padded rank + core-gradient floats) x 4 bytes; the
+ *    benchmark shape, order 3 with J = R = 16 and |Psi| = 1e6, needs 23 MB).
+ *  - Every context on a GPU shares that GPU's array, and nothing in it has to survive from one
+ *    call to the next (each workgroup overwrites its part before the update pass reads it), but
+ *    two such calls that overlap on one GPU -- different streams, different host threads -- race.
+ *  - Inputs and outputs are the context's, as for ftk_sgd_step; the two calls can be mixed freely.
+ */
+int ftk_sgd_step_noalloc(ftk_ctx* ctx, float lr_A, float lr_B, float lambda_A, float lambda_B);
+
+/*
  * RMSE = sqrt( sum_{Omega} (x - xhat)^2 / |Omega| ) and MAE = sum_{Omega} |x - xhat| / |Omega|
  * over ALL stored entries (Section 5.1 defines both over a test set Gamma; this library's
  * Gamma is Omega).  Squared errors are summed in double.  out: host.  Waits for the stream.

@@ -27,7 +27,7 @@ FTK_MAX_ORDER = 10
 
 # every symbol include/ftk.h declares
 SYMBOLS = [
-    "ftk_create", "ftk_destroy", "ftk_sample", "ftk_get_samples", "ftk_sgd_step", "ftk_rmse", "ftk_mae",
+    "ftk_create", "ftk_destroy", "ftk_sample", "ftk_get_samples", "ftk_sgd_step", "ftk_sgd_step_noalloc", "ftk_rmse", "ftk_mae",
     "ftk_evaluate", "ftk_step_size", "ftk_set_sampling",
     "ftk_get_factors", "ftk_set_factors", "ftk_set_mode", "ftk_set_stream", "ftk_set_timing",
     "ftk_get_timing", "ftk_set_kernel", "ftk_kernel_name", "ftk_get_table_rows", "ftk_last_error",
@@ -87,6 +87,8 @@ def load():
     L.ftk_get_samples.restype = C.c_int
     L.ftk_sgd_step.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float]
     L.ftk_sgd_step.restype = C.c_int
+    L.ftk_sgd_step_noalloc.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float]
+    L.ftk_sgd_step_noalloc.restype = C.c_int
     L.ftk_rmse.argtypes = [vp, C.POINTER(C.c_double)]
     L.ftk_rmse.restype = C.c_int
     L.ftk_mae.argtypes = [vp, C.POINTER(C.c_double)]
@@ -215,6 +217,9 @@ class FastTucker:
 
     def ftk_sgd_step(self, lr_A: float, lr_B: float, lambda_A: float, lambda_B: float) -> None:
         self._check(self._L.ftk_sgd_step(self._ctx, lr_A, lr_B, lambda_A, lambda_B))
+
+    def ftk_sgd_step_noalloc(self, lr_A: float, lr_B: float, lambda_A: float, lambda_B: float) -> None:
+        self._check(self._L.ftk_sgd_step_noalloc(self._ctx, lr_A, lr_B, lambda_A, lambda_B))
 
     def ftk_rmse(self) -> float:
         out = C.c_double(0.0)

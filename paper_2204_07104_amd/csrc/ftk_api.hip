@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <utility>
@@ -19,6 +20,13 @@
 #include "ftk_kernels_tiled.hpp"
 
 using namespace ftk;
+
+// Scratch memory of ftk_sgd_step_noalloc: the per-workgroup partial tables of one step (factor-row sums,
+// then core-gradient sums).  A device global, so no allocation call is ever needed for it; every GPU the
+// library's code is loaded on holds its own copy until the process ends.  Host code never uses this name
+// as an address: the per-device address comes from hipGetSymbolAddress (scratch_address below).
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) float scratch[kScratchBytes / sizeof(float)];
 
 namespace {
 
@@ -96,8 +104,12 @@ struct ftk_ctx {
     size_t mfma_lds_bytes = 0;
     float* d_hot_partial = nullptr;   // [mfma_grid][hot_H][16]
     float* d_gb_partial = nullptr;    // [mfma_grid][B_total]
+    float* use_hot_partial = nullptr; // the partial tables of the step being enqueued: the two above, or the
+    float* use_gb_partial = nullptr;  // library's static scratch array (ftk_sgd_step_noalloc)
 
     bool timing = false;
+    bool no_events = false;   // set while ftk_sgd_step_noalloc enqueues: no event is created even if timing is on
+    bool prepare_only = false;   // the launch functions stop after raising the kernel's LDS limit
     TimingSlot slots[FTK_K_COUNT];
     std::vector<const void*> lds_limit_raised;   // kernels whose dynamic-LDS limit this context has raised
 
@@ -118,6 +130,9 @@ int fail(ftk_ctx* c, int code, const char* fmt, ...) {
         g_create_error = buf;
     return code;
 }
+
+int step_impl(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B);
+int prepare_variant(ftk_ctx* c);
 
 #define FTK_HIP(c, call)                                                                         \
     do {                                                                                         \
@@ -143,6 +158,29 @@ int check_device(ftk_ctx* c) {
     return FTK_OK;
 }
 
+// Address of the static scratch array on the current device (which must be c->device): looked up once
+// per device, at the first ftk_create on it.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_setup(ftk_ctx* c) {
+    if (c->device < 0 || c->device >= kMaxDevices) return FTK_OK;   // ftk_sgd_step_noalloc will refuse
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[c->device]) return FTK_OK;
+    float* ptr = nullptr;
+    FTK_HIP(c, hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(c, FTK_EDEVICE, "hipGetSymbolAddress returned no address for the scratch array");
+    g_scratch_ptr[c->device] = ptr;
+    return FTK_OK;
+}
+
+float* scratch_address(const ftk_ctx* c) {
+    if (c->device < 0 || c->device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    return g_scratch_ptr[c->device];
+}
+
 // Raise a kernel's dynamic-LDS limit to the device maximum, once per context and kernel (the limit is
 // a property of the kernel on this device, so raising it again is harmless but costs a runtime call
 // per step).  Always the device's maximum, so that contexts of different shapes cannot lower it for
@@ -165,7 +203,7 @@ struct Bracket {
     hipEvent_t a = nullptr, b = nullptr;
     bool on = false;
     Bracket(ftk_ctx* ctx, int s) : c(ctx), slot(s) {
-        if (!c->timing) return;
+        if (!c->timing || c->no_events) return;
         if (hipEventCreate(&a) != hipSuccess) return;
         if (hipEventCreate(&b) != hipSuccess) {
             hipEventDestroy(a);
@@ -248,6 +286,7 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = 
         if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_generic_kernel), c->max_lds)) return rc;
         if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(factor_phase_generic_kernel), c->max_lds)) return rc;
     }
+    if (c->prepare_only) return FTK_OK;
     Bracket t(c, FTK_K_GRAD);
     if (modewise) {
         // Algorithm 1 as printed: the factor phase changes A in place, then the core gradient is
@@ -263,6 +302,7 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = 
 template <int N>
 int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
     if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_mfma16_kernel<N>), c->max_lds)) return rc;
+    if (c->prepare_only) return FTK_OK;
     Bracket t(c, FTK_K_GRAD);
     hipLaunchKernelGGL(grad_mfma16_kernel<N>, dim3(c->mfma_grid), dim3(kMfmaThreads), c->mfma_lds_bytes, c->stream, g);
     FTK_HIP(c, hipGetLastError());
@@ -291,12 +331,12 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
     }
     g.all_bytes = (unsigned int)(c->A_total * 4);
     g.H = c->hot_H;
-    g.hot_partial = c->d_hot_partial;
-    g.gb_partial = c->d_gb_partial;
+    g.hot_partial = c->use_hot_partial;
+    g.gb_partial = c->use_gb_partial;
     g.lambda_A = lambda_A;
     // what the kernel assumes: 16-float rows, records of 4 * ceil((N + 1) / 4) words, partial
     // tables sized for the grid, an LDS table of hot_H rows
-    if (!c->mfma16_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->d_hot_partial || !c->d_gb_partial)
+    if (!c->mfma16_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->use_hot_partial || !c->use_gb_partial)
         return fail(c, FTK_EUNSUPPORTED, "mfma16 kernel is not available for this shape");
     switch (c->order) {
         case 1: return launch_mfma16_n<1>(c, g);
@@ -312,6 +352,7 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
 template <int N, int P, int WAVES, bool X4>
 int launch_tiled_npwx(ftk_ctx* c, const TiledArgs& g) {
     if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4>), c->max_lds)) return rc;
+    if (c->prepare_only) return FTK_OK;
     Bracket t(c, FTK_K_GRAD);
     hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES, X4>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
                        c->stream, g);
@@ -355,13 +396,13 @@ int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
         g.mode_bytes[n] = (unsigned int)(c->dims[n] * c->L.J[n] * 4);
     }
     g.H = c->hot_H;
-    g.hot_partial = c->d_hot_partial;
-    g.gb_partial = c->d_gb_partial;
+    g.hot_partial = c->use_hot_partial;
+    g.gb_partial = c->use_gb_partial;
     g.B_total = c->L.B_total;
     g.lambda_A = lambda_A;
     // what the kernel assumes: padded ranks 16 P, records of 4 * ceil((N + 1) / 4) words, an LDS
     // table that fits, partial tables sized for grid x waves
-    if (!c->tiled_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->d_hot_partial || !c->d_gb_partial ||
+    if (!c->tiled_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->use_hot_partial || !c->use_gb_partial ||
         c->tiled_lds_bytes > (size_t)c->max_lds || (size_t)c->hot_H * 64 * c->tiled_P > (size_t)c->max_lds)
         return fail(c, FTK_EUNSUPPORTED, "tiled kernel is not available for this shape");
     switch (c->order) {
@@ -711,6 +752,8 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
         FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid_max * 8 * c->L.B_total * sizeof(float)));
         pick_hot_rows(c, 1LL << 20);
     }
+    if (const int rc = scratch_setup(c)) return rc;
+    if (const int rc = prepare_variant(c)) return rc;
     FTK_HIP(c, hipStreamSynchronize(c->stream));
     return FTK_OK;
 }
@@ -820,6 +863,42 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
     if (!c) return FTK_EINVAL;
     if (const int rc_dev = check_device(c)) return rc_dev;
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step before ftk_sample");
+    c->use_hot_partial = c->d_hot_partial;
+    c->use_gb_partial = c->d_gb_partial;
+    return step_impl(c, lr_A, lr_B, lambda_A, lambda_B);
+}
+
+int ftk_sgd_step_noalloc(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
+    if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
+    if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step_noalloc before ftk_sample");
+    if (c->variant == V_GENERIC || c->mode == FTK_HOGWILD_MODEWISE)
+        return fail(c, FTK_EUNSUPPORTED, "ftk_sgd_step_noalloc runs on the matrix-core kernels only: the one-lane-per-sample "
+                                         "kernels keep Psi in arrays that are allocated on demand");
+    float* base = scratch_address(c);
+    if (!base) return fail(c, FTK_EUNSUPPORTED, "no static scratch array on device %d", c->device);
+    // the partial tables of this step: [grid][H][row floats], then [grid x parts][B_total]
+    const bool tiled = c->variant == V_TILED;
+    const size_t hot_floats = (((size_t)c->mfma_grid * c->hot_H * (tiled ? 16 * c->tiled_P : 16)) + 63) / 64 * 64;
+    const size_t gb_floats = (size_t)c->mfma_grid * (tiled ? c->tiled_waves : 1) * c->L.B_total;
+    const size_t need = (hot_floats + gb_floats) * sizeof(float);
+    if (need > kScratchBytes)
+        return fail(c, FTK_EUNSUPPORTED, "this shape and |Psi| need %zu bytes of partial tables, the static scratch array holds %zu",
+                    need, kScratchBytes);
+    c->use_hot_partial = base;
+    c->use_gb_partial = base + hot_floats;
+    c->no_events = true;
+    const int rc = step_impl(c, lr_A, lr_B, lambda_A, lambda_B);
+    c->no_events = false;
+    return rc;
+}
+
+}  // extern "C"
+
+namespace {
+
+// One step over the current Psi with the partial tables c->use_hot_partial / c->use_gb_partial.
+int step_impl(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
     // the mode-by-mode in-place order exists for the one-lane-per-sample kernels only
     const bool modewise = c->mode == FTK_HOGWILD_MODEWISE;
     const bool mfma = c->variant != V_GENERIC && !modewise;   // a matrix-core variant: per-workgroup tables
@@ -839,7 +918,7 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
         // tables), so there is no accumulator to scan and the tables are added as they are
         p.dense_blocks = in_place ? 0 : blocks_for(p.n4, 256, c->num_cu * 16);
         if (mfma) {
-            p.hot_partial = c->d_hot_partial;
+            p.hot_partial = c->use_hot_partial;
             p.hot_parts = c->mfma_grid;
             p.H = c->hot_H;
             p.J = tiled ? 16 * c->tiled_P : 16;
@@ -853,7 +932,7 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
             }
         }
         p.B = c->d_B;
-        p.GB = mfma ? c->d_gb_partial : c->d_GB;
+        p.GB = mfma ? c->use_gb_partial : c->d_GB;
         p.B_total = c->L.B_total;
         p.gb_parts = tiled ? c->mfma_grid * c->tiled_waves : mfma ? c->mfma_grid : 1;
         p.gb_clear = mfma ? 0 : 1;
@@ -868,6 +947,24 @@ int ftk_sgd_step(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambd
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;
 }
+
+// Everything a step of the current variant and mode needs set up on the host side, so that the step
+// itself only launches: today, the kernels' dynamic-LDS limits.
+int prepare_variant(ftk_ctx* c) {
+    c->prepare_only = true;
+    c->use_hot_partial = c->d_hot_partial;
+    c->use_gb_partial = c->d_gb_partial;
+    const bool modewise = c->mode == FTK_HOGWILD_MODEWISE;
+    const int rc = (c->variant == V_TILED && !modewise) ? launch_grad_tiled(c, 0.0f, 0.0f)
+                   : (c->variant == V_MFMA16 && !modewise) ? launch_grad_mfma16(c, 0.0f, 0.0f)
+                                                           : launch_grad_generic(c, 0.0f, 0.0f, modewise);
+    c->prepare_only = false;
+    return rc;
+}
+
+}  // namespace
+
+extern "C" {
 
 int ftk_rmse(ftk_ctx* c, double* out) {
     if (!c) return FTK_EINVAL;
@@ -1023,12 +1120,13 @@ int ftk_set_sampling(ftk_ctx* c, int rule) {
 
 int ftk_set_mode(ftk_ctx* c, int mode) {
     if (!c) return FTK_EINVAL;
+    if (const int rc_dev = check_device(c)) return rc_dev;
     if (mode != FTK_SYNC && mode != FTK_HOGWILD && mode != FTK_HOGWILD_MODEWISE)
         return fail(c, FTK_EINVAL, "unknown mode %d", mode);
     if (mode == FTK_HOGWILD_MODEWISE && c->gen_threads == 0)
         return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the one-lane-per-sample kernels, which do not fit this shape");
     c->mode = mode;
-    return FTK_OK;
+    return prepare_variant(c);
 }
 
 int ftk_set_stream(ftk_ctx* c, void* hip_stream) {
@@ -1082,25 +1180,26 @@ int ftk_get_timing(ftk_ctx* c, int which, double* total_ms, int64_t* launches, i
 int ftk_set_kernel(ftk_ctx* c, const char* name) {
     if (!c) return FTK_EINVAL;
     if (!name) return fail(c, FTK_EINVAL, "name is NULL");
+    if (const int rc_dev = check_device(c)) return rc_dev;
     // the accumulators of both variants are clean between steps, so switching is always safe
     if (!strcmp(name, "auto"))
         name = (c->mfma16_ok && (c->order <= 5 || !c->tiled_ok)) ? "mfma16" : c->tiled_ok ? "tiled" : c->mfma16_ok ? "mfma16" : "generic";
     if (!strcmp(name, "generic")) {
         if (c->gen_threads == 0) return fail(c, FTK_EUNSUPPORTED, "the generic kernel does not fit this shape");
         c->variant = V_GENERIC;
-        return FTK_OK;
+        return prepare_variant(c);
     }
     if (!strcmp(name, "mfma16")) {
         if (!c->mfma16_ok) return fail(c, FTK_EUNSUPPORTED, "mfma16 needs J_n = R = 16 and order <= 6");
         c->variant = V_MFMA16;
         pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
-        return FTK_OK;
+        return prepare_variant(c);
     }
     if (!strcmp(name, "tiled")) {
         if (!c->tiled_ok) return fail(c, FTK_EUNSUPPORTED, "tiled needs order <= 8 with J_n, R <= 64 (order 9, 10: <= 16) and padded core factors that fit LDS twice");
         c->variant = V_TILED;
         pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
-        return FTK_OK;
+        return prepare_variant(c);
     }
     return fail(c, FTK_EUNSUPPORTED, "no kernel variant named '%s'", name);
 }

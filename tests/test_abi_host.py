@@ -62,6 +62,7 @@ def test_null_context_is_rejected_everywhere():
     d = C.c_double(0.0)
     assert L.ftk_sample(None, 1, 1) == binding.FTK_EINVAL
     assert L.ftk_sgd_step(None, 0.0, 0.0, 0.0, 0.0) == binding.FTK_EINVAL
+    assert L.ftk_sgd_step_noalloc(None, 0.0, 0.0, 0.0, 0.0) == binding.FTK_EINVAL
     assert L.ftk_rmse(None, C.byref(d)) == binding.FTK_EINVAL
     assert L.ftk_mae(None, C.byref(d)) == binding.FTK_EINVAL
     assert L.ftk_evaluate(None, 1, None, None, 0, C.byref(d), C.byref(d)) == binding.FTK_EINVAL
