@@ -299,14 +299,22 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = 
     return FTK_OK;
 }
 
-template <int N>
-int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
-    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_mfma16_kernel<N>), c->max_lds)) return rc;
+template <int N, bool TILES, bool INPLACE>
+int launch_mfma16_nti(ftk_ctx* c, const Mfma16Args& g) {
+    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_mfma16_kernel<N, TILES, INPLACE>), c->max_lds)) return rc;
     if (c->prepare_only) return FTK_OK;
     Bracket t(c, FTK_K_GRAD);
-    hipLaunchKernelGGL(grad_mfma16_kernel<N>, dim3(c->mfma_grid), dim3(kMfmaThreads), c->mfma_lds_bytes, c->stream, g);
+    hipLaunchKernelGGL((grad_mfma16_kernel<N, TILES, INPLACE>), dim3(c->mfma_grid), dim3(kMfmaThreads), c->mfma_lds_bytes,
+                       c->stream, g);
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;
+}
+
+template <int N>
+int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
+    const bool tiles = c->sampling == FTK_SAMPLE_TILES, in_place = c->mode == FTK_HOGWILD;
+    if (tiles) return in_place ? launch_mfma16_nti<N, true, true>(c, g) : launch_mfma16_nti<N, true, false>(c, g);
+    return in_place ? launch_mfma16_nti<N, false, true>(c, g) : launch_mfma16_nti<N, false, false>(c, g);
 }
 
 int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
@@ -549,9 +557,12 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     // One workgroup per CU, but no more than there are groups of 64 samples to give every wave
     // one: every workgroup writes (and the update pass reads) a whole partial table.
     {
+        // a wave's unit of work: 64 samples, or 128 (two turns that share their Philox blocks) in the
+        // J = R = 16 kernel under the entry-sampling rule
         const long long waves = c->variant == V_TILED ? c->tiled_waves : kMfmaWaves;
-        const long long groups = (n_samples + 63) / 64;
-        c->mfma_grid = (int)std::max<long long>(1, std::min<long long>(c->mfma_grid_max, (groups + waves - 1) / waves));
+        const long long unit = (c->variant == V_MFMA16 && c->sampling == FTK_SAMPLE_ENTRIES) ? 128 : 64;
+        const long long units = (n_samples + unit - 1) / unit;
+        c->mfma_grid = (int)std::max<long long>(1, std::min<long long>(c->mfma_grid_max, (units + waves - 1) / waves));
     }
     long long rows_total = 0;
     for (int n = 0; n < N; ++n) rows_total += c->dims[n];
@@ -1115,7 +1126,8 @@ int ftk_set_sampling(ftk_ctx* c, int rule) {
     }
     if (rule != c->sampling) c->batch_valid = false;
     c->sampling = rule;
-    return FTK_OK;
+    if (c->variant != V_GENERIC) pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
+    return prepare_variant(c);
 }
 
 int ftk_set_mode(ftk_ctx* c, int mode) {

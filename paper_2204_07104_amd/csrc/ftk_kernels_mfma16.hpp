@@ -163,20 +163,18 @@ __device__ __forceinline__ void gather_rows(const __amdgpu_buffer_rsrc_t (&rsrc_
     }
 }
 
-// One group of 64 samples parked at `scur` (row words, LDS-cell words, values, pending masks):
-// four tiles of 16.  While tile t is computed, the rows of tile t + 3 are requested: tile 3 of
-// this group during tile 0, then tiles 0..2 of the wave's next group (parked at `snxt`).  The
-// requests are unconditional, so that the compiler's count of outstanding memory operations is
-// exact; behind a wave's last group the next group is parked as all row 0 and its (unused) rows
-// cost one cached line.
-// `lim` (1..64) is the number of samples of the group that exist: only the last group of Psi can
-// have fewer than 64.  The others were parked as row 0 / value 0; they run through the arithmetic
-// like any sample, with their error and their regulariser weight forced to zero, so that each of
-// their contributions is an exact zero (added to row 0, wherever row 0 is accumulated).
-template <int N>
-__device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, int lim, unsigned int hot_addr,
-                                              const unsigned int* scur, const unsigned int* snxt, float* tbuf, int c,
-                                              int g4) {
+// One group of 64 samples parked at `scur` (row words, values, scatter lists): four tiles of 16.
+// While tile t is computed, the rows of tile t + 3 are requested: tile 3 of this group during
+// tile 0, then tiles 0..2 of the wave's next group (parked at `snxt`).  The requests are
+// unconditional, so that the compiler's count of outstanding memory operations is exact.
+// A sample slot with no sample behind it (the ragged end of Psi, or a whole group past it) is
+// parked as value 0 and, in every mode, as the row just past the mode's last one: the buffer
+// range check makes that row read as zeros, so the slot's projections, prediction, error and
+// gradients are all exact zeros, and it is on neither scatter list.  No masks in the arithmetic.
+template <int N, bool INPLACE>
+__device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, unsigned int hot_addr,
+                                              unsigned int top_key, const unsigned int* scur, const unsigned int* snxt,
+                                              float* tbuf, int c, int g4) {
     __amdgpu_buffer_rsrc_t rsrc_A[N];
 #pragma unroll
     for (int n = 0; n < N; ++n) rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
@@ -186,10 +184,18 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
     const unsigned int* table_list = atomic_list + mfma16_list_words(N);
     const unsigned int* list_len = table_list + mfma16_list_words(N);
     const unsigned int c4 = (unsigned int)c * 4u;
-    const unsigned int top_key = (2u << kRouteShift) + (unsigned int)c * 64u;   // row word of "row c, one of the top 16"
 
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
+        // The tile's scatter lists were written when the group was parked: their first batches and
+        // lengths are asked for now, long before they are used.
+        const unsigned int* alist = atomic_list + sub * (16 * N) + g4 * (4 * N);
+        const unsigned int* tlist = table_list + sub * (16 * N) + g4 * (4 * N);
+        const uint4 a_first = *reinterpret_cast<const uint4*>(alist);
+        const uint4 a_second = N > 1 ? *reinterpret_cast<const uint4*>(alist + 4) : a_first;
+        const uint4 t_first = *reinterpret_cast<const uint4*>(tlist);
+        const unsigned int len_atomic = list_len[sub], len_table = list_len[4 + sub];
+
         if (sub == 0)
             gather_rows<N>(rsrc_A, scur, 3, c, g4, st.ring[3]);
         else
@@ -232,7 +238,7 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
         // every lane of column c, without a trip through LDS.
         const float part = (run[0] + run[1]) + (run[2] + run[3]);
         const floatx4 xsum = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, part, floatx4{0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0);
-        const float neg_e = sub * 16 + c < lim ? xsum[0] - x : 0.0f;
+        const float neg_e = xsum[0] - x;
         run = floatx4{1.0f, 1.0f, 1.0f, 1.0f};
 #pragma unroll
         for (int n = N - 1; n >= 0; --n) {
@@ -273,15 +279,12 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
             for (int v = 0; v < 4; ++v) wY[n][v] = tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c];
 
         // Factor-row gradients -e GS + lambda_A a (layout Y: one 64-byte row per 16 lanes).
-        float lam[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) lam[v] = sub * 16 + 4 * g4 + v < lim ? g.lambda_A : 0.0f;
         float grad[N][4];
 #pragma unroll
         for (int n = 0; n < N; ++n)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) grad[n][v] = fmaf(lam[v], aY[n][v], gs[n][v]);
-        if (g.scale != 1.0f) {   // in-place mode adds -lr_A * gradient
+            for (int v = 0; v < 4; ++v) grad[n][v] = fmaf(g.lambda_A, aY[n][v], gs[n][v]);
+        if constexpr (INPLACE) {   // in-place mode adds -lr_A * gradient
 #pragma unroll
             for (int n = 0; n < N; ++n)
 #pragma unroll
@@ -302,25 +305,45 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 #pragma unroll
             for (int v = 0; v < 4; ++v) tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c] = grad[n][v];
         lds_wave_sync();
+
+        // Everything the scatter reads from the staged rows is asked for in one go: the values of the
+        // first eight atomic-list positions and of the first four table-list positions.
+        const unsigned int ea[8] = {a_first.x, a_first.y, a_first.z, a_first.w, a_second.x, a_second.y, a_second.z, a_second.w};
+        const unsigned int et[4] = {t_first.x, t_first.y, t_first.z, t_first.w};
+        float aval[8], tval[4];
+        unsigned int cell[4], seen[4];
+#pragma unroll
+        for (int i = 0; i < (N > 1 ? 8 : 4); ++i) aval[i] = tbuf[(ea[i] & 127u) * 20u + (unsigned int)c];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tval[i] = tbuf[(et[i] >> 20) * 20u + (unsigned int)c];
+        // one-hot operands of the 16 most frequent rows: all compares first, then the products
+        float onehot[N][4];
 #pragma unroll
         for (int n = 0; n < N; ++n)
             if (g.top[n] > 0) {
                 const uint4 r = *reinterpret_cast<const uint4*>(scur + n * 64 + sub * 16 + 4 * g4);
-                const unsigned int rw[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float onehot = rw[k] == top_key ? 1.0f : 0.0f;
-                    st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot, grad[n][k], st.Top[n], 0, 0, 0);
-                }
+                onehot[n][0] = r.x == top_key ? 1.0f : 0.0f;
+                onehot[n][1] = r.y == top_key ? 1.0f : 0.0f;
+                onehot[n][2] = r.z == top_key ? 1.0f : 0.0f;
+                onehot[n][3] = r.w == top_key ? 1.0f : 0.0f;
             }
-        const int n_atomic = __builtin_amdgcn_readfirstlane((int)list_len[sub]);
-        const int n_table = __builtin_amdgcn_readfirstlane((int)list_len[4 + sub]);
+        const int n_atomic = __builtin_amdgcn_readfirstlane((int)len_atomic);
+        const int n_table = __builtin_amdgcn_readfirstlane((int)len_table);
 
         // Global atomics.  Eight instructions go out whatever the list holds (entries past its end
         // aim beyond the array and are dropped by the hardware, cheaply): a fixed count lets the
         // compiler wait for prefetched rows without waiting for atomics issued after them.
+#pragma unroll
+        for (int i = 0; i < (N > 1 ? 8 : 4); ++i)
+            __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(aval[i], rsrc_dA, (int)(((ea[i] >> 1) & ~63u) | c4), 0, 0);
+        // the table cells of the first batch are read while the matrix core is busy below
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            cell[i] = hot_addr + (et[i] & 0xfffffu) + c4;
+            seen[i] = *(lds_u32*)(uintptr_t)cell[i];
+        }
         auto atomics4 = [&](int first) {
-            const uint4 e4 = *reinterpret_cast<const uint4*>(atomic_list + sub * (16 * N) + g4 * (4 * N) + first);
+            const uint4 e4 = *reinterpret_cast<const uint4*>(alist + first);
             const unsigned int e[4] = {e4.x, e4.y, e4.z, e4.w};
             float val[4];
 #pragma unroll
@@ -329,12 +352,17 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
             for (int i = 0; i < 4; ++i)
                 __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val[i], rsrc_dA, (int)(((e[i] >> 1) & ~63u) | c4), 0, 0);
         };
-        atomics4(0);
-        if (N > 1) atomics4(4);
 #pragma unroll
         for (int b = 2; b < N; ++b)
             if (n_atomic > 16 * b) atomics4(4 * b);
 
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+            if (g.top[n] > 0) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot[n][k], grad[n][k], st.Top[n], 0, 0, 0);
+            }
         // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
@@ -344,46 +372,53 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 
         // LDS table, four list positions (16 rows) per batch.  Entries past the end of the list aim
         // at a row of +inf, which absorbs any finite addend: their swaps succeed and change nothing.
-        auto table4 = [&](int first) {
-            const uint4 e4 = *reinterpret_cast<const uint4*>(table_list + sub * (16 * N) + g4 * (4 * N) + first);
-            const unsigned int e[4] = {e4.x, e4.y, e4.z, e4.w};
-            float val[4];
-            unsigned int cell[4], seen[4], got[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                val[i] = tbuf[(e[i] >> 20) * 20u + (unsigned int)c];
-                cell[i] = hot_addr + (e[i] & 0xfffffu) + c4;
-                seen[i] = *(lds_u32*)(uintptr_t)cell[i];
-            }
+        auto swap4 = [&](int first, const float (&val)[4], const unsigned int (&cl)[4], const unsigned int (&sn)[4]) {
+            unsigned int got[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                got[i] = lds_cas(cell[i], seen[i], __float_as_uint(__uint_as_float(seen[i]) + val[i]));
+                got[i] = lds_cas(cl[i], sn[i], __float_as_uint(__uint_as_float(sn[i]) + val[i]));
             __builtin_amdgcn_sched_barrier(0);   // all four swaps go out before the first result is waited for
             bool lost = false;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) lost = lost || got[i] != seen[i];
+            for (int i = 0; i < 4; ++i) lost = lost || got[i] != sn[i];
             // Rarely, another wave (or another quarter of this instruction) changed a word between
             // the read and the swap: the lanes that lost go round again for their listed rows.
             if (__builtin_amdgcn_ballot_w64(lost) != 0) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    bool again = got[i] != seen[i] && (first + i) * 4 + g4 < n_table;
+                    bool again = got[i] != sn[i] && (first + i) * 4 + g4 < n_table;
                     while (again) {
                         const unsigned int expect = got[i];
-                        got[i] = lds_cas(cell[i], expect, __float_as_uint(__uint_as_float(expect) + val[i]));
+                        got[i] = lds_cas(cl[i], expect, __float_as_uint(__uint_as_float(expect) + val[i]));
                         again = got[i] != expect;
                     }
                 }
             }
         };
+        if (n_table > 0) swap4(0, tval, cell, seen);
 #pragma unroll
-        for (int b = 0; b < N; ++b)
-            if (n_table > 16 * b) table4(4 * b);
+        for (int b = 1; b < N; ++b)
+            if (n_table > 16 * b) {
+                const uint4 e4 = *reinterpret_cast<const uint4*>(tlist + 4 * b);
+                const unsigned int e[4] = {e4.x, e4.y, e4.z, e4.w};
+                float val[4];
+                unsigned int cl[4], sn[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    val[i] = tbuf[(e[i] >> 20) * 20u + (unsigned int)c];
+                    cl[i] = hot_addr + (e[i] & 0xfffffu) + c4;
+                    sn[i] = *(lds_u32*)(uintptr_t)cl[i];
+                }
+                swap4(4 * b, val, cl, sn);
+            }
         lds_wave_sync();   // the next tile overwrites the staged rows
     }
 }
 
-template <int N>
+// TILES: Psi is drawn by the tile-sampling rule (runs of 64 neighbouring records) instead of entry
+// by entry.  INPLACE: the gradients are scaled by g.scale = -lr_A and rows outside the tables are
+// added straight into A (g.dA is A); otherwise g.scale is 1 and not looked at.
+template <int N, bool TILES, bool INPLACE>
 __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g) {
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;   // 16-byte words per record
@@ -418,17 +453,51 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     __syncthreads();
 
     const long long M = g.M;
-    const long long n_groups = (M + 63) / 64;
-    const long long group_stride = (long long)gridDim.x * kMfmaWaves;
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
     const unsigned int hot_addr = lds_address(hot);
+    // row word of "row c, one of the 16 most frequent" (kept opaque so that the match below is one compare)
+    unsigned int top_key = (2u << kRouteShift) + (unsigned int)c * 64u;
+    asm volatile("" : "+v"(top_key));
 
-    // record of sample (group * 64 + lane): N row numbers and the value's bits.  A group past
-    // the end of Psi (and a lane past the end of the last group) reads record 0 and is parked
-    // as row 0 / value 0.
-    auto load_record = [&](long long grp, uint4 (&rec)[W4]) {
-        const long long k = grp * 64 + lane;
-        const uint32_t p = k < M ? sample_place(g.seed, (uint64_t)k, g.rule) : 0u;
+    // Which samples a wave takes.  Its turns are numbered t = 0, 1, 2, ...; the wave is number
+    // `wave_id` of `n_waves` in the launch.
+    //   entry rule: turns 2u and 2u + 1 share the 128 samples [128 q, 128 q + 128), q = wave_id +
+    //     u * n_waves: lane l takes sample 128 q + 2 l in the even turn and 128 q + 2 l + 1 in the odd
+    //     one.  Both come out of ONE Philox block (counter 64 q + l, low and high pair of words), which is
+    //     evaluated in the even turn only.
+    //   tile rule: turn t is run t * n_waves + wave_id, lane l its l-th record.
+    // Which lane and turn a sample lands in changes the order of the sums only.
+    const long long wave_id = (long long)blockIdx.x * kMfmaWaves + wave;
+    const long long n_waves = (long long)gridDim.x * kMfmaWaves;
+    const long long n_turns_all = TILES ? (M + 63) / 64 : 2 * ((M + 127) / 128);   // over all waves
+    auto sample_of = [&](long long t) -> long long {   // this lane's sample number in turn t
+        if constexpr (TILES) return (t * n_waves + wave_id) * 64 + lane;
+        return ((t >> 1) * n_waves + wave_id) * 128 + 2 * lane + (t & 1);
+    };
+    auto turn_exists = [&](long long t) -> bool {      // wave-uniform: the turn holds at least one sample slot below M's last group
+        if constexpr (TILES) return t * n_waves + wave_id < n_turns_all;
+        return 2 * ((t >> 1) * n_waves + wave_id) < n_turns_all;
+    };
+    uint32_t odd_place = 0u;   // entry rule: where the odd turn's sample is read, kept from the even turn
+
+    // record of this lane's sample in turn t: N row numbers and the value's bits.  A slot with no
+    // sample behind it reads record 0 and is parked as an empty slot.
+    auto load_record = [&](long long t, uint4 (&rec)[W4]) {
+        const long long k = sample_of(t);
+        uint32_t p;
+        if constexpr (TILES) {
+            p = tile_place(g.seed, (uint64_t)k, g.rule);
+        } else {
+            if ((t & 1) == 0) {
+                const uint64_t ctr = (uint64_t)k >> 1;
+                const U4 o = philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)g.seed, (uint32_t)(g.seed >> 32));
+                p = (uint32_t)__umul64hi(((uint64_t)o.y << 32) | (uint64_t)o.x, g.rule.nnz);
+                odd_place = (uint32_t)__umul64hi(((uint64_t)o.w << 32) | (uint64_t)o.z, g.rule.nnz);
+            } else {
+                p = odd_place;
+            }
+        }
+        if (k >= M) p = 0u;
 #pragma unroll
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
@@ -436,8 +505,8 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     const int my_tile = lane >> 4, my_s = lane & 15;
     const unsigned long long tile_lanes = 0xffffull << (16 * my_tile);
     const unsigned long long lanes_below = tile_lanes & ((1ull << lane) - 1ull);   // of my tile
-    auto park_record = [&](long long grp, const uint4 (&rec)[W4], unsigned int* dst) {
-        const bool act = grp * 64 + lane < M;
+    auto park_record = [&](long long t, const uint4 (&rec)[W4], unsigned int* dst) {
+        const bool act = sample_of(t) < M;
         uint32_t flat[4 * W4];
 #pragma unroll
         for (int q = 0; q < W4; ++q) {
@@ -462,10 +531,11 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
         int n_atomic = 0, n_table = 0;   // entries of my tile's lists so far
 #pragma unroll
         for (int n = 0; n < N; ++n) {
-            const int row = act ? (int)flat[n] : 0;
-            const bool to_table = row >= g.top[n] && row < g.K[n];
-            const bool to_atomic = row >= g.K[n];
-            const unsigned int route = to_atomic ? 0u : to_table ? 1u : 2u;
+            // an empty slot: the row just past the mode's last one (reads as zeros), on no list
+            const int row = act ? (int)flat[n] : (int)(g.row_bytes[n] >> 6);
+            const bool to_table = act && row >= g.top[n] && row < g.K[n];
+            const bool to_atomic = act && row >= g.K[n];
+            const unsigned int route = (to_atomic || !act) ? 0u : to_table ? 1u : 2u;
             dst[n * 64 + lane] = (unsigned int)row * 64u + (route << kRouteShift);
             const unsigned long long atomic_lanes = __builtin_amdgcn_ballot_w64(to_atomic);
             const unsigned long long table_lanes = __builtin_amdgcn_ballot_w64(to_table);
@@ -488,41 +558,40 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
         }
     };
 
-    long long group = (long long)blockIdx.x * kMfmaWaves + wave;
-    if (group < n_groups) {
+    if (turn_exists(0)) {
         __amdgpu_buffer_rsrc_t rsrc_A[N];
 #pragma unroll
         for (int n = 0; n < N; ++n) rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
 
-        // fill the pipeline: records of this wave's first two groups, rows of the first three tiles
+        // fill the pipeline: records of this wave's first two turns, rows of the first three tiles
         uint4 rec[W4];
         {
             uint4 rec0[W4];
-            load_record(group, rec0);
-            load_record(group + group_stride, rec);
-            park_record(group, rec0, sbuf);
+            load_record(0, rec0);
+            load_record(1, rec);
+            park_record(0, rec0, sbuf);
         }
         lds_wave_sync();
 #pragma unroll
         for (int t = 0; t < 3; ++t) gather_rows<N>(rsrc_A, sbuf, t, c, g4, st.ring[t]);
 
-        // One group: park the next group's records (requested a whole group ago), request the
-        // records of the group after it, then the four tiles.
-        auto one_group = [&](long long grp, int parity) {
+        // One turn: park the next turn's records (requested a whole turn ago), request the
+        // records of the turn after it, then the four tiles.  Turns past the wave's last one hold
+        // only empty slots.
+        auto one_turn = [&](long long t, int parity) {
             unsigned int* scur = sbuf + parity * kGroupWords;
             unsigned int* snxt = sbuf + (parity ^ 1) * kGroupWords;
-            park_record(grp + group_stride, rec, snxt);
-            load_record(grp + 2 * group_stride, rec);
+            park_record(t + 1, rec, snxt);
+            load_record(t + 2, rec);
             lds_wave_sync();
-            const long long left = M - grp * 64;
-            process_group<N>(g, st, left < 64 ? (int)left : 64, hot_addr, scur, snxt, tbuf, c, g4);
+            process_group<N, INPLACE>(g, st, hot_addr, top_key, scur, snxt, tbuf, c, g4);
         };
-        // The first group is peeled off the loop: the loop proper is then entered with the same
+        // The first turn is peeled off the loop: the loop proper is then entered with the same
         // sequence of outstanding memory operations as its own back edge, and the compiler's
         // wait counts in the steady state are exact instead of the minimum over both entries.
-        one_group(group, 0);
-        group += group_stride;
-        for (int parity = 1; group < n_groups; group += group_stride, parity ^= 1) one_group(group, parity);
+        one_turn(0, 0);
+        long long t = 1;
+        for (int parity = 1; turn_exists(t); ++t, parity ^= 1) one_turn(t, parity);
     }
 
     // rows 0..15 of each mode: from the wave's accumulators into the workgroup's LDS table
