@@ -249,7 +249,18 @@ int ftk_get_timing(ftk_ctx* ctx, int which, double* total_ms, int64_t* launches,
  *              factors padded to multiples of 16 (twice)
  *   "generic"  one lane per sample: any order <= FTK_MAX_ORDER and any ranks for which
  *              512 * order * R + 4 * sum_n J_n R bytes fit in LDS
- * All three compute the same step (same Psi, same formulas); they differ in speed only.
+ *   "rows"     the "tiled" kernel with the factor-row update done by row owners, the first of the two
+ *              thread-block strategies of Section 4.2 (the rows of a mode are distributed over thread blocks;
+ *              a row's update is the sum over the samples of Psi that hit it, Eq. Gradient_low_rank): rows
+ *              that are not summed in the on-chip tables are written to per-workgroup lists, one list per
+ *              bucket of rows, and a second kernel gives every bucket to one workgroup, which sums the
+ *              bucket's lists on chip and writes the rows of A^(n): no float atomics on A^(n) or on an
+ *              accumulator.  Never chosen by "auto" (measured slower than "tiled" on this GPU).  Synchronous
+ *              step only; needs the shapes of "tiled" with every J_n a multiple of 4 and at most 4096
+ *              buckets; allocates the lists (sized from |Psi| and the rows' frequencies) on the device.
+ *              "rows:tight" is the same with lists of half the expected length, so that many rows take the
+ *              fallback (a full list sends the row through a float atomic after all): for tests.
+ * All of them compute the same step (same Psi, same formulas); they differ in speed only.
  * ftk_kernel_name: the variant in use (static string, never NULL).
  */
 int ftk_set_kernel(ftk_ctx* ctx, const char* name);

@@ -104,6 +104,24 @@ struct ftk_ctx {
     size_t mfma_lds_bytes = 0;
     float* d_hot_partial = nullptr;   // [mfma_grid][hot_H][16]
     float* d_gb_partial = nullptr;    // [mfma_grid][B_total]
+    // "rows" form of the tiled variant: rows outside the tables are appended to per-workgroup lists and summed by
+    // row-owning workgroups (ftk_kernels_tiled.hpp, ROWS)
+    bool rows_ok = false;            // the shape has a bucket plan (set at create)
+    bool rows = false;               // in use (only with variant == V_TILED)
+    bool rows_tight = false;         // list capacities at half the expected counts: lists fill up all the time (for tests)
+    int rows_shift[kMaxOrder] = {};  // rows per bucket of mode n = 1 << shift
+    int rows_bucket0[kMaxOrder] = {};
+    int rows_n_buckets = 0;          // for the current tables (K_n) and |Psi|
+    int rows_max_buckets = 0;        // with no table rows at all: what LDS and the device tables are sized for
+    unsigned int rows_list_words = 0;
+    size_t rows_apply_lds = 0;
+    std::vector<std::vector<unsigned long long>> count_prefix;   // per mode: prefix sums of sorted_counts
+    float* d_lists = nullptr;
+    size_t lists_bytes = 0;
+    unsigned int* d_list_fill = nullptr;
+    uint2* d_bucket_info = nullptr;
+    int4* d_bucket_rows = nullptr;
+    unsigned int* d_overflow = nullptr;
     float* use_hot_partial = nullptr; // the partial tables of the step being enqueued: the two above, or the
     float* use_gb_partial = nullptr;  // library's static scratch array (ftk_sgd_step_noalloc)
 
@@ -357,12 +375,12 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
     }
 }
 
-template <int N, int P, int WAVES, bool X4>
-int launch_tiled_npwx(ftk_ctx* c, const TiledArgs& g) {
-    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4>), c->max_lds)) return rc;
+template <int N, int P, int WAVES, bool X4, bool ROWS>
+int launch_tiled_npwxr(ftk_ctx* c, const TiledArgs& g) {
+    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4, ROWS>), c->max_lds)) return rc;
     if (c->prepare_only) return FTK_OK;
     Bracket t(c, FTK_K_GRAD);
-    hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES, X4>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
+    hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES, X4, ROWS>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
                        c->stream, g);
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;
@@ -370,7 +388,13 @@ int launch_tiled_npwx(ftk_ctx* c, const TiledArgs& g) {
 
 template <int N, int P, int WAVES>
 int launch_tiled_npw(ftk_ctx* c, const TiledArgs& g) {
-    return c->tiled_x4 ? launch_tiled_npwx<N, P, WAVES, true>(c, g) : launch_tiled_npwx<N, P, WAVES, false>(c, g);
+    // the rows form is built for rows fetched 16 bytes per lane (every J_n a multiple of four) only
+    if (c->rows) {
+        // the row owners' table (up to 64 KB, dynamic) sits next to 4 KB of static LDS
+        if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(rows_apply_kernel), 65536)) return rc;
+        return c->tiled_x4 ? launch_tiled_npwxr<N, P, WAVES, true, true>(c, g) : fail(c, FTK_EUNSUPPORTED, "rows needs every J_n to be a multiple of 4");
+    }
+    return c->tiled_x4 ? launch_tiled_npwxr<N, P, WAVES, true, false>(c, g) : launch_tiled_npwxr<N, P, WAVES, false, false>(c, g);
 }
 
 template <int N>
@@ -408,6 +432,20 @@ int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
     g.gb_partial = c->use_gb_partial;
     g.B_total = c->L.B_total;
     g.lambda_A = lambda_A;
+    g.lists = c->d_lists;
+    g.list_fill = c->d_list_fill;
+    g.bucket_info = c->d_bucket_info;
+    g.overflow = c->d_overflow;
+    g.list_words = c->rows_list_words;
+    g.n_buckets = c->rows ? c->rows_n_buckets : 0;
+    for (int n = 0; n < kMaxOrder; ++n) {
+        g.bucket0[n] = c->rows_bucket0[n];
+        g.bucket_shift[n] = c->rows_shift[n];
+    }
+    if (c->rows && !c->prepare_only &&
+        (in_place || !c->d_lists || !c->d_list_fill || !c->d_bucket_info || !c->d_overflow || c->rows_n_buckets < 1 ||
+         (size_t)c->mfma_grid * c->rows_list_words * sizeof(float) > c->lists_bytes))
+        return fail(c, FTK_EUNSUPPORTED, "the rows form of the tiled kernel is not set up for this step");
     // what the kernel assumes: padded ranks 16 P, records of 4 * ceil((N + 1) / 4) words, an LDS
     // table that fits, partial tables sized for grid x waves
     if (!c->tiled_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->use_hot_partial || !c->use_gb_partial ||
@@ -543,7 +581,8 @@ void release(ftk_ctx* c) {
     for (int n = 0; n < kMaxOrder; ++n)
         if (c->d_new_of_old[n]) hipFree(c->d_new_of_old[n]);
     void* ptrs[] = {c->d_rec, c->d_rec_tiles, c->d_stage, c->d_A, c->d_dA, c->d_B, c->d_GB, c->d_sums, c->d_flag,
-                    c->d_pos, c->d_bidx, c->d_bval, c->d_hot_partial, c->d_gb_partial};
+                    c->d_pos, c->d_bidx, c->d_bval, c->d_hot_partial, c->d_gb_partial, c->d_lists, c->d_list_fill,
+                    c->d_bucket_info, c->d_bucket_rows, c->d_overflow};
     for (void* p : ptrs)
         if (p) hipFree(p);
     delete c;
@@ -552,7 +591,9 @@ void release(ftk_ctx* c) {
 // Choose which rows are accumulated in LDS for a sample set of n_samples entries: most frequent
 // first, down to a fraction of an expected hit per workgroup and step, as many as the LDS budget
 // allows.  Rows are already sorted by count within a mode, so this is a merge of sorted lists.
-void pick_hot_rows(ftk_ctx* c, long long n_samples) {
+int plan_rows(ftk_ctx* c, long long n_samples);
+
+int pick_hot_rows(ftk_ctx* c, long long n_samples) {
     const int N = c->order;
     // One workgroup per CU, but no more than there are groups of 64 samples to give every wave
     // one: every workgroup writes (and the update pass reads) a whole partial table.
@@ -570,6 +611,7 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     long long budget_bytes, row_bytes;
     if (c->variant == V_TILED) {
         budget_bytes = (long long)c->max_lds - 4LL * (long long)tiled_lds_floats(N, c->tiled_P, c->tiled_waves, 0) - 1024;
+        if (c->rows) budget_bytes -= 4LL * (long long)tiled_rows_lds_words(N, c->tiled_waves, c->rows_max_buckets);
         row_bytes = 64LL * c->tiled_P;
     } else {
         budget_bytes = (long long)c->max_lds - 4LL * (kMfmaWaves * mfma16_wave_scratch(N) + N * 256 + kSinkRows * 16) - 1024;
@@ -612,6 +654,64 @@ void pick_hot_rows(ftk_ctx* c, long long n_samples) {
     c->mfma_lds_bytes = 4 * ((size_t)(c->hot_H + kSinkRows) * 16 + kMfmaWaves * mfma16_wave_scratch(N) + N * 256);
     c->tiled_lds_bytes = 4 * tiled_lds_floats(N, c->tiled_P, c->tiled_waves, c->hot_H);
     c->hot_for_M = n_samples;
+    if (c->variant == V_TILED && c->rows) return plan_rows(c, n_samples);
+    return FTK_OK;
+}
+
+// The rows form of the tiled kernel: buckets of the rows outside the tables, one list per (gradient
+// workgroup, bucket) with room for the expected number of entries plus slack, and the device tables
+// that describe them.  Called whenever the tables or |Psi| change (never while a step is being enqueued).
+int plan_rows(ftk_ctx* c, long long n_samples) {
+    const int N = c->order;
+    std::vector<uint2> info;
+    std::vector<int4> rows;
+    unsigned long long words = 0;
+    size_t lds_cells = 0;
+    try {
+        for (int n = 0; n < N; ++n) {
+            c->rows_bucket0[n] = (int)info.size();
+            const long long per_bucket = 1LL << c->rows_shift[n];
+            const std::vector<unsigned long long>& prefix = c->count_prefix[n];
+            for (long long lo = c->hot_K[n]; lo < c->dims[n]; lo += per_bucket) {
+                const long long hi = std::min<long long>(lo + per_bucket, c->dims[n]);
+                // expected entries of this bucket in one workgroup's list
+                const double expect = (double)(prefix[(size_t)hi] - prefix[(size_t)lo]) / (double)c->nnz * (double)n_samples /
+                                      (double)c->mfma_grid;
+                const double cap = c->rows_tight ? std::max(1.0, std::floor(0.5 * expect)) : std::ceil(expect + 6.0 * std::sqrt(expect) + 8.0);
+                if (cap * (double)c->mfma_grid_max > 2e9 || words > 0x0fffffffull) return fail(c, FTK_EUNSUPPORTED, "rows: the lists of one workgroup exceed 2^28 words");
+                info.push_back(make_uint2((unsigned int)words, (unsigned int)cap));
+                rows.push_back(make_int4(n, (int)lo, (int)(hi - lo), 0));
+                words += (unsigned long long)cap * (unsigned long long)rows_entry_words(c->L.J[n]);
+                lds_cells = std::max(lds_cells, (size_t)(hi - lo) * (size_t)c->L.J[n]);
+            }
+        }
+    } catch (...) {
+        return fail(c, FTK_ENOMEM, "host allocation failed");
+    }
+    if (words > 0x0fffffffull) return fail(c, FTK_EUNSUPPORTED, "rows: the lists of one workgroup exceed 2^28 words");
+    if (info.empty()) {   // every row is in a table: one empty bucket keeps the launches well formed
+        info.push_back(make_uint2(0u, 0u));
+        rows.push_back(make_int4(0, (int)c->dims[0], 0, 0));
+    }
+    if (c->mfma_grid_max > kRowsApplyMaxSources) return fail(c, FTK_EUNSUPPORTED, "rows: more than %d gradient workgroups", kRowsApplyMaxSources);
+    if ((int)info.size() > c->rows_max_buckets) return fail(c, FTK_EUNSUPPORTED, "rows: internal error, more buckets than planned for");
+    const size_t need = (size_t)c->mfma_grid_max * std::max<unsigned long long>(words, 1) * sizeof(float);
+    if (need > ((size_t)8 << 30)) return fail(c, FTK_EUNSUPPORTED, "rows: the lists would need %zu bytes (limit 8 GiB)", need);
+    FTK_HIP(c, hipStreamSynchronize(c->stream));
+    if (need > c->lists_bytes) {
+        if (c->d_lists) hipFree(c->d_lists);
+        c->d_lists = nullptr;
+        c->lists_bytes = 0;
+        FTK_HIP(c, hipMalloc(&c->d_lists, need));
+        c->lists_bytes = need;
+    }
+    FTK_HIP(c, hipMemcpy(c->d_bucket_info, info.data(), info.size() * sizeof(uint2), hipMemcpyHostToDevice));
+    FTK_HIP(c, hipMemcpy(c->d_bucket_rows, rows.data(), rows.size() * sizeof(int4), hipMemcpyHostToDevice));
+    c->rows_n_buckets = (int)info.size();
+    c->rows_list_words = (unsigned int)std::max<unsigned long long>(words, 1);
+    c->rows_apply_lds = std::max<size_t>(lds_cells, 1) * sizeof(float);
+    c->tiled_lds_bytes += 4 * tiled_rows_lds_words(N, c->tiled_waves, c->rows_n_buckets);
+    return FTK_OK;
 }
 
 int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, const float* vals, uint64_t init_seed,
@@ -761,7 +861,49 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
         // (tiled) or per-workgroup (mfma16) tables of the core gradient
         FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid_max * c->max_lds));
         FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid_max * 8 * c->L.B_total * sizeof(float)));
-        pick_hot_rows(c, 1LL << 20);
+        // the rows form of the tiled kernel: bucket sizes follow from the shape alone
+        if (c->tiled_ok && c->tiled_x4) {
+            c->count_prefix.assign(N, {});
+            for (int n = 0; n < N; ++n) {
+                std::vector<unsigned long long>& pre = c->count_prefix[n];
+                pre.resize((size_t)dims[n] + 1);
+                pre[0] = 0;
+                for (size_t r = 0; r < (size_t)dims[n]; ++r) pre[r + 1] = pre[r] + c->sorted_counts[n][r];
+                // a bucket's rows fit a 64 KB LDS table of the row-owner kernel ...
+                int shift = 8;
+                while (shift < 20 && (2LL << shift) * c->L.J[n] * 4 <= 65536) ++shift;
+                c->rows_shift[n] = shift;
+            }
+            auto count_buckets = [&]() {
+                long long total = 0;
+                for (int n = 0; n < N; ++n) total += (dims[n] + (1LL << c->rows_shift[n]) - 1) >> c->rows_shift[n];
+                return total;
+            };
+            // ... and there are at least four buckets per CU (the owners then spread evenly) where the shape allows it (down to 256 rows a bucket)
+            for (bool changed = true; changed && count_buckets() < 4LL * c->num_cu;) {
+                changed = false;
+                for (int n = 0; n < N; ++n)
+                    if (c->rows_shift[n] > 8 && (dims[n] >> c->rows_shift[n]) > 0) {
+                        c->rows_shift[n] -= 1;
+                        changed = true;
+                    }
+            }
+            const long long max_buckets = std::max<long long>(count_buckets(), 1);
+            bool fits = max_buckets <= 4096;
+            for (int n = 0; n < N; ++n) fits = fits && (1LL << c->rows_shift[n]) * c->L.J[n] * 4 <= 65536;
+            fits = fits && 4LL * ((long long)tiled_lds_floats(N, c->tiled_P, c->tiled_waves, 16) +
+                                  (long long)tiled_rows_lds_words(N, c->tiled_waves, (int)max_buckets)) + 1024 <= c->max_lds;
+            if (fits) {
+                c->rows_max_buckets = (int)max_buckets;
+                FTK_HIP(c, hipMalloc(&c->d_bucket_info, (size_t)max_buckets * sizeof(uint2)));
+                FTK_HIP(c, hipMalloc(&c->d_bucket_rows, (size_t)max_buckets * sizeof(int4)));
+                FTK_HIP(c, hipMalloc(&c->d_list_fill, (size_t)c->mfma_grid_max * max_buckets * sizeof(unsigned int)));
+                FTK_HIP(c, hipMalloc(&c->d_overflow, sizeof(unsigned int)));
+                FTK_HIP(c, hipMemset(c->d_overflow, 0, sizeof(unsigned int)));
+                c->rows_ok = true;
+            }
+        }
+        if (const int rc = pick_hot_rows(c, 1LL << 20)) return rc;
     }
     if (const int rc = scratch_setup(c)) return rc;
     if (const int rc = prepare_variant(c)) return rc;
@@ -846,7 +988,14 @@ int ftk_sample(ftk_ctx* c, uint64_t seed, int64_t n_samples) {
     c->sample_seed = seed;
     c->n_samples = n_samples;
     c->batch_valid = false;
-    if (c->variant != V_GENERIC && c->hot_for_M != n_samples) pick_hot_rows(c, n_samples);
+    if (c->variant != V_GENERIC && c->hot_for_M != n_samples) {
+        if (c->rows)   // the lists are re-planned (and possibly re-allocated) on the device
+            if (const int rc_dev = check_device(c)) return rc_dev;
+        if (const int rc = pick_hot_rows(c, n_samples)) {
+            c->n_samples = 0;   // no usable Psi
+            return rc;
+        }
+    }
     return FTK_OK;
 }
 
@@ -886,6 +1035,7 @@ int ftk_sgd_step_noalloc(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, flo
     if (c->variant == V_GENERIC || c->mode == FTK_HOGWILD_MODEWISE)
         return fail(c, FTK_EUNSUPPORTED, "ftk_sgd_step_noalloc runs on the matrix-core kernels only: the one-lane-per-sample "
                                          "kernels keep Psi in arrays that are allocated on demand");
+    if (c->rows) return fail(c, FTK_EUNSUPPORTED, "ftk_sgd_step_noalloc does not serve the \"rows\" kernel (its lists are allocated buffers)");
     float* base = scratch_address(c);
     if (!base) return fail(c, FTK_EUNSUPPORTED, "no static scratch array on device %d", c->device);
     // the partial tables of this step: [grid][H][row floats], then [grid x parts][B_total]
@@ -925,9 +1075,34 @@ int step_impl(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B
         p.A = c->d_A;
         p.dA = c->d_dA;
         p.n4 = c->A_total / 4;
+        const bool rows = tiled && c->rows;
+        if (rows) {
+            // the row-owning workgroups: every bucket's lists summed on chip, its rows of A updated with plain stores
+            RowsApplyArgs r = {};
+            r.lists = c->d_lists;
+            r.list_fill = c->d_list_fill;
+            r.bucket_info = c->d_bucket_info;
+            r.bucket_rows = c->d_bucket_rows;
+            r.list_words = c->rows_list_words;
+            r.n_buckets = c->rows_n_buckets;
+            r.n_sources = c->mfma_grid;
+            r.A = c->d_A;
+            r.dA = c->d_dA;
+            for (int n = 0; n < kMaxOrder; ++n) {
+                r.A_off[n] = c->L.A_off[n];
+                r.J[n] = c->L.J[n];
+            }
+            r.overflow = c->d_overflow;
+            r.lr_A = lr_A;
+            Bracket t(c, FTK_K_APPLY);
+            hipLaunchKernelGGL(rows_apply_kernel, dim3(c->rows_n_buckets), dim3(kRowsApplyThreads), c->rows_apply_lds, c->stream, r);
+            FTK_HIP(c, hipGetLastError());
+            p.clear_word = c->d_overflow;
+        }
         // in-place mode: the gradient pass already added -lr_A * gradient to A (and to the workgroup
-        // tables), so there is no accumulator to scan and the tables are added as they are
-        p.dense_blocks = in_place ? 0 : blocks_for(p.n4, 256, c->num_cu * 16);
+        // tables), so there is no accumulator to scan and the tables are added as they are; rows form:
+        // the row owners above have done the accumulator's part
+        p.dense_blocks = (in_place || rows) ? 0 : blocks_for(p.n4, 256, c->num_cu * 16);
         if (mfma) {
             p.hot_partial = c->use_hot_partial;
             p.hot_parts = c->mfma_grid;
@@ -1126,7 +1301,8 @@ int ftk_set_sampling(ftk_ctx* c, int rule) {
     }
     if (rule != c->sampling) c->batch_valid = false;
     c->sampling = rule;
-    if (c->variant != V_GENERIC) pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
+    if (c->variant != V_GENERIC)
+        if (const int rc = pick_hot_rows(c, std::max<long long>(c->n_samples, 1))) return rc;
     return prepare_variant(c);
 }
 
@@ -1135,6 +1311,8 @@ int ftk_set_mode(ftk_ctx* c, int mode) {
     if (const int rc_dev = check_device(c)) return rc_dev;
     if (mode != FTK_SYNC && mode != FTK_HOGWILD && mode != FTK_HOGWILD_MODEWISE)
         return fail(c, FTK_EINVAL, "unknown mode %d", mode);
+    if (mode != FTK_SYNC && c->rows)
+        return fail(c, FTK_EUNSUPPORTED, "the \"rows\" kernel serves the synchronous step only");
     if (mode == FTK_HOGWILD_MODEWISE && c->gen_threads == 0)
         return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the one-lane-per-sample kernels, which do not fit this shape");
     c->mode = mode;
@@ -1196,6 +1374,26 @@ int ftk_set_kernel(ftk_ctx* c, const char* name) {
     // the accumulators of both variants are clean between steps, so switching is always safe
     if (!strcmp(name, "auto"))
         name = (c->mfma16_ok && (c->order <= 5 || !c->tiled_ok)) ? "mfma16" : c->tiled_ok ? "tiled" : c->mfma16_ok ? "mfma16" : "generic";
+    if (!strcmp(name, "rows") || !strcmp(name, "rows:tight")) {
+        if (!c->rows_ok)
+            return fail(c, FTK_EUNSUPPORTED, "rows needs the tiled kernel's shapes with every J_n a multiple of 4 and at most 4096 buckets of rows");
+        if (c->mode != FTK_SYNC) return fail(c, FTK_EUNSUPPORTED, "the \"rows\" kernel serves the synchronous step only");
+        const int old_variant = c->variant;
+        const bool old_rows = c->rows, old_tight = c->rows_tight;
+        c->variant = V_TILED;
+        c->rows = true;
+        c->rows_tight = name[4] == ':';
+        int rc = pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
+        if (rc == FTK_OK) rc = prepare_variant(c);
+        if (rc != FTK_OK) {   // back to what was in use
+            c->variant = old_variant;
+            c->rows = old_rows;
+            c->rows_tight = old_tight;
+            if (c->variant != V_GENERIC) pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
+        }
+        return rc;
+    }
+    c->rows = false;
     if (!strcmp(name, "generic")) {
         if (c->gen_threads == 0) return fail(c, FTK_EUNSUPPORTED, "the generic kernel does not fit this shape");
         c->variant = V_GENERIC;
@@ -1204,19 +1402,22 @@ int ftk_set_kernel(ftk_ctx* c, const char* name) {
     if (!strcmp(name, "mfma16")) {
         if (!c->mfma16_ok) return fail(c, FTK_EUNSUPPORTED, "mfma16 needs J_n = R = 16 and order <= 6");
         c->variant = V_MFMA16;
-        pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
+        if (const int rc = pick_hot_rows(c, std::max<long long>(c->n_samples, 1))) return rc;
         return prepare_variant(c);
     }
     if (!strcmp(name, "tiled")) {
         if (!c->tiled_ok) return fail(c, FTK_EUNSUPPORTED, "tiled needs order <= 8 with J_n, R <= 64 (order 9, 10: <= 16) and padded core factors that fit LDS twice");
         c->variant = V_TILED;
-        pick_hot_rows(c, std::max<long long>(c->n_samples, 1));
+        if (const int rc = pick_hot_rows(c, std::max<long long>(c->n_samples, 1))) return rc;
         return prepare_variant(c);
     }
     return fail(c, FTK_EUNSUPPORTED, "no kernel variant named '%s'", name);
 }
 
-const char* ftk_kernel_name(const ftk_ctx* c) { return c ? kVariantNames[c->variant] : "none"; }
+const char* ftk_kernel_name(const ftk_ctx* c) {
+    if (!c) return "none";
+    return (c->variant == V_TILED && c->rows) ? "rows" : kVariantNames[c->variant];
+}
 
 int ftk_get_table_rows(ftk_ctx* c, int32_t* K_out, int32_t* top_out) {
     if (!c) return FTK_EINVAL;

@@ -748,6 +748,7 @@ struct ApplyArgs {
     int gb_parts;
     int gb_clear;               // zero GB[0] afterwards (single atomically accumulated table)
     float lr_A, lr_B, lambda_B, inv_M;
+    unsigned int* clear_word;   // a counter to reset for the next step (or NULL)
 };
 
 __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
@@ -823,6 +824,7 @@ __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
         const float b0 = p.B[q];
         p.B[q] = b0 - p.lr_B * fmaf(total, p.inv_M, p.lambda_B * b0);
         if (p.gb_clear) p.GB[q] = 0.0f;
+        if (q == 0 && p.clear_word) *p.clear_word = 0u;
     }
 }
 

@@ -23,6 +23,19 @@
 // route gets an out-of-range buffer offset resp. the address of an LDS row nobody reads.
 // The core gradient lives in matrix-core accumulators for the whole kernel and leaves each wave
 // as one table of plain stores.
+//
+// ROWS (thread-block strategy (1) of Section 4.2: the rows of a mode are owned by thread blocks, and
+// the row update sums over the samples of Psi that hit the row, Eq. Gradient_low_rank): rows outside
+// the tables are not added to memory with atomics.  The rows of every mode are cut into buckets of
+// 2^shift rows; a workgroup of this kernel keeps one list per bucket, and the gradient row of a
+// (sample, mode) is appended to the list of its row's bucket as J_n floats + the row number (padded to
+// a multiple of 16 bytes, so that the owner can read an entry with 16-byte loads), with plain stores
+// (list positions come from LDS counters).  rows_apply_kernel then gives every bucket to
+// one workgroup, which sums the bucket's lists of all gradient workgroups in an LDS table and updates
+// the bucket's rows of A^(n) with plain stores: no atomics on A or on an accumulator.  A list that is
+// full (their capacities follow the expected counts, with slack) sends the row through the float
+// atomic into the accumulator after all, and counts it; the bucket owners fold the accumulator in
+// when that counter is not zero.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -62,9 +75,30 @@ struct TiledArgs {
     unsigned int mode_bytes[kMaxOrder];   // I_n * J_n * 4
     float lambda_A;
     float scale;                 // 1, or -lr_A in in-place mode
+    // ROWS only: the per-workgroup lists of gradient rows (see the header comment)
+    float* lists;                // [gridDim.x][list_words]
+    unsigned int* list_fill;     // [n_buckets][gridDim.x]: entries in each list when the kernel ends
+    const uint2* bucket_info;    // [n_buckets]: x = first word of the bucket's list in a workgroup's area, y = capacity in entries
+    unsigned int* overflow;      // entries that found their list full
+    unsigned int list_words;     // words in one workgroup's area
+    int n_buckets;
+    int bucket0[kMaxOrder];      // first bucket of mode n
+    int bucket_shift[kMaxOrder]; // rows per bucket of mode n = 1 << shift
 };
 
+// words of one list entry of a mode with J floats per row: the row's gradient, the row number, padding to 16 bytes
+__host__ __device__ constexpr int rows_entry_words(int J) { return (J + 1 + 3) & ~3; }
+
+// list entry words of a (sample, mode) in the parked group: no entry (row in a table, or no sample), list was full
+constexpr unsigned int kNoEntry = 0xffffffffu, kListFull = 0xfffffffeu;
+
 __host__ __device__ constexpr int tiled_park_words(int order) { return (order + 1) * 64; }
+// ROWS: behind the ordinary layout, LDS holds three arrays of n_buckets words (rounded up to a multiple of
+// four, so that what follows stays 16-byte aligned): list counters | first words | capacities; then per wave
+// two parked groups of [order][64] entry words + 64 words (the first: "a list was full")
+__host__ __device__ constexpr size_t tiled_rows_lds_words(int order, int waves, int n_buckets) {
+    return (size_t)3 * ((n_buckets + 3) & ~3) + (size_t)waves * 2 * (order * 64 + 64);
+}
 // per wave: two parked groups, the transpose buffer, and 4 x 16 P words nobody reads (see `sink`)
 __host__ __device__ constexpr int tiled_wave_scratch(int order, int P) {
     return 2 * tiled_park_words(order) + kTransposeFloats + 64 * P;
@@ -73,7 +107,7 @@ __host__ __device__ constexpr size_t tiled_lds_floats(int order, int P, int wave
     return (size_t)2 * order * 256 * P * P + (size_t)H * 16 * P + (size_t)waves * tiled_wave_scratch(order, P);
 }
 
-template <int N, int P, int WAVES, bool X4>
+template <int N, int P, int WAVES, bool X4, bool ROWS>
 __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;
@@ -102,6 +136,20 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         Bt[operand_slot<P>(n, r, j)] = b;
     }
     for (int q = tid; q < g.H * D; q += THREADS) hot[q] = 0.0f;
+    // ROWS: list counters, bucket info and the parked entry words behind everything else
+    const int nb4 = (g.n_buckets + 3) & ~3;
+    unsigned int* list_count = reinterpret_cast<unsigned int*>(hot + (size_t)g.H * D + WAVES * tiled_wave_scratch(N, P));
+    unsigned int* list_first = list_count + nb4;
+    unsigned int* list_cap = list_first + nb4;
+    unsigned int* wave_entries = list_cap + nb4 + wave * 2 * (N * 64 + 64);
+    if constexpr (ROWS) {
+        for (int q = tid; q < g.n_buckets; q += THREADS) {
+            const uint2 info = g.bucket_info[q];
+            list_count[q] = 0u;
+            list_first[q] = info.x;
+            list_cap[q] = info.y;
+        }
+    }
 
     floatx4 GBacc[N][P][P];
     floatx4 Top[N][P];
@@ -121,6 +169,9 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.mode_bytes[n]);
         rsrc_dA[n] = make_rsrc(g.dA + g.A_off[n], g.mode_bytes[n]);
     }
+    // ROWS: this workgroup's list area (the host keeps list_words below 2^28, so byte offsets stay below 2^30)
+    const __amdgpu_buffer_rsrc_t rsrc_lists =
+        make_rsrc(ROWS ? (const void*)(g.lists + (size_t)blockIdx.x * g.list_words) : (const void*)g.A, ROWS ? g.list_words * 4u : 0u);
 
     const long long M = g.M;
     const long long n_groups = (M + 63) / 64;
@@ -134,7 +185,10 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     };
 
     // Park a group's records: row numbers and values of inactive lanes are zero.
-    auto park_record = [&](long long grp, const uint4 (&rec)[W4], float* park) {
+    // ROWS: every (sample, mode) whose row is outside the tables also takes its place in the list of
+    // its row's bucket here (one LDS counter increment per lane and mode); `entries` gets the first
+    // word of that place in the workgroup's list area, or one of the two markers.
+    auto park_record = [&](long long grp, const uint4 (&rec)[W4], float* park, unsigned int* entries) {
         const bool act = grp * 64 + lane < M;
         uint32_t flat[4 * W4];
 #pragma unroll
@@ -148,6 +202,28 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 #pragma unroll
         for (int n = 0; n < N; ++n) sidx[n * 64 + lane] = act ? (int)flat[n] : 0;
         park[N * 64 + lane] = act ? __uint_as_float(flat[N]) : 0.0f;
+        if constexpr (ROWS) {
+            bool full = false;
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const int row = (int)flat[n];
+                unsigned int e = kNoEntry;
+                if (act && row >= g.K[n]) {
+                    const int b = g.bucket0[n] + ((row - g.K[n]) >> g.bucket_shift[n]);
+                    const unsigned int place = atomicAdd(&list_count[b], 1u);
+                    if (place < list_cap[b]) {
+                        e = list_first[b] + place * (unsigned int)rows_entry_words(g.J[n]);
+                    } else {
+                        e = kListFull;
+                        full = true;
+                        atomicAdd(g.overflow, 1u);
+                    }
+                }
+                entries[n * 64 + lane] = e;
+            }
+            const unsigned long long any_full = __builtin_amdgcn_ballot_w64(full);
+            if (lane == 0) entries[N * 64] = any_full != 0ull ? 1u : 0u;
+        }
     };
     // Request the factor rows of tile `sub` of a parked group whose first sample is number `first`.
     //   X4: rows[n][jb] = components 16 jb + 4g .. +3 of the row of sample c           (layout X)
@@ -192,7 +268,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     int buf = 0;
     if (group < n_groups) {
         load_record(group, rec);
-        park_record(group, rec, wave_lds);
+        park_record(group, rec, wave_lds, wave_entries);
         lds_wave_sync();
         if (group + group_stride < n_groups) load_record(group + group_stride, rec);
         gather_rows(wave_lds, 0, group * 64, cur);
@@ -204,6 +280,8 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         float* park_next = wave_lds + (buf ^ 1) * tiled_park_words(N);
         const int* sidx = reinterpret_cast<const int*>(park);
         const float* sval = park + N * 64;
+        const unsigned int* entries = wave_entries + buf * (N * 64 + 64);
+        unsigned int* entries_next = wave_entries + (buf ^ 1) * (N * 64 + 64);
 
 #pragma unroll 1
         for (int sub = 0; sub < 4; ++sub) {
@@ -216,7 +294,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     gather_rows(park, sub + 1, group * 64, rows);
                 } else {
                     if (group + group_stride < n_groups) {
-                        park_record(group + group_stride, rec, park_next);
+                        park_record(group + group_stride, rec, park_next, entries_next);
                         lds_wave_sync();
                         if (group + 2 * group_stride < n_groups) load_record(group + 2 * group_stride, rec);
                     }
@@ -378,10 +456,24 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 // row numbers of samples 4g .. 4g+3 in this mode (read here, not kept for all modes at once)
                 const int4 rows4 = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
                 const int rowv[4] = {rows4.x, rows4.y, rows4.z, rows4.w};
+                // ROWS: first word of each sample's list entry (or a marker), and whether any list of the group was full
+                unsigned int entv[4] = {kNoEntry, kNoEntry, kNoEntry, kNoEntry};
+                bool group_had_full_list = false;
+                if constexpr (ROWS) {
+                    const uint4 e4 = *reinterpret_cast<const uint4*>(entries + n * 64 + sub * 16 + 4 * g4);
+                    entv[0] = e4.x;
+                    entv[1] = e4.y;
+                    entv[2] = e4.z;
+                    entv[3] = e4.w;
+                    group_had_full_list = __builtin_amdgcn_readfirstlane((int)entries[N * 64]) != 0;
+                }
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int row = rowv[v];
-                    abase[v] = (actY[v] && row >= g.K[n]) ? (unsigned int)(row * g.J[n] * 4) : kDropped;
+                    if constexpr (ROWS)
+                        abase[v] = entv[v] == kListFull ? (unsigned int)(row * g.J[n] * 4) : kDropped;
+                    else
+                        abase[v] = (actY[v] && row >= g.K[n]) ? (unsigned int)(row * g.J[n] * 4) : kDropped;
                     tab[v] = actY[v] && row < g.K[n] && row >= g.top[n];
                     tbase[v] = tab[v] ? hot_addr + (unsigned int)((g.hot_off[n] + row) * D * 4) : sink_addr;
                     onehot[v] = row == c ? 1.0f : 0.0f;
@@ -426,7 +518,18 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         grad[v] = g.scale * fmaf(g.lambda_A, aY[n][jb][v], gs[jb][v]);
-                        __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[v], rsrc_dA[n], (int)(abase[v] + col4), 0, 0);
+                        if constexpr (ROWS) {
+                            // the list entry: components 0 .. J_n - 1, then the row number (its lane may be in
+                            // a block of columns of its own when J_n is a multiple of 16: see below)
+                            const int col = 16 * jb + c;
+                            const unsigned int word = col < g.J[n] ? __float_as_uint(grad[v]) : (unsigned int)rowv[v];
+                            const unsigned int off = (col <= g.J[n] && entv[v] < kListFull) ? (entv[v] + (unsigned int)col) * 4u : kDropped;
+                            __builtin_amdgcn_raw_buffer_store_b32(word, rsrc_lists, (int)off, 0, 0);
+                            if (group_had_full_list)
+                                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[v], rsrc_dA[n], (int)(abase[v] + col4), 0, 0);
+                        } else {
+                            __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[v], rsrc_dA[n], (int)(abase[v] + col4), 0, 0);
+                        }
                         const int e = BATCH == 4 ? v : 4 * jb + v;
                         cell[e] = tbase[v] + (unsigned int)((16 * jb + c) * 4);
                         tval[e] = grad[v];
@@ -446,6 +549,15 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     if (BATCH == 4 && any_table) table_batch();
                 }
                 if (BATCH != 4 && any_table) table_batch();
+                if constexpr (ROWS) {
+                    if (g.J[n] == D) {   // no lane of the blocks above holds column J_n: the row numbers go out on their own
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const unsigned int off = (c == 0 && entv[v] < kListFull) ? (entv[v] + (unsigned int)D) * 4u : kDropped;
+                            __builtin_amdgcn_raw_buffer_store_b32((unsigned int)rowv[v], rsrc_lists, (int)off, 0, 0);
+                        }
+                    }
+                }
             }
             if constexpr (!X4) {
 #pragma unroll
@@ -482,6 +594,127 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     __syncthreads();
     float* hot_out = g.hot_partial + (size_t)blockIdx.x * g.H * D;
     for (int q = tid; q < g.H * D; q += THREADS) hot_out[q] = hot[q];
+    if constexpr (ROWS) {
+        for (int q = tid; q < g.n_buckets; q += THREADS)
+            g.list_fill[(size_t)q * gridDim.x + blockIdx.x] = min(list_count[q], list_cap[q]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// ROWS, second half: one workgroup per bucket of rows.  It sums, in an LDS table, the gradient rows
+// that the gradient workgroups appended to their lists of this bucket, and then updates the bucket's
+// rows A^(n)[i,:] <- A^(n)[i,:] - lr_A (sum) with plain stores.  If any list was full during the
+// gradient pass (the counter is not zero), the rows that went into the accumulator instead are
+// folded in (and the accumulator cleared) first.
+// ---------------------------------------------------------------------------------------------
+struct RowsApplyArgs {
+    const float* lists;              // [n_sources][list_words]
+    const unsigned int* list_fill;   // [n_buckets][n_sources]
+    const uint2* bucket_info;        // [n_buckets]: first word, capacity
+    const int4* bucket_rows;         // [n_buckets]: x = mode, y = first row of the bucket within its mode, z = rows in the bucket
+    unsigned int list_words;
+    int n_buckets;
+    int n_sources;                   // workgroups of the gradient launch
+    float* A;
+    float* dA;
+    long long A_off[kMaxOrder];
+    int J[kMaxOrder];
+    const unsigned int* overflow;
+    float lr_A;
+};
+
+constexpr int kRowsApplyThreads = 512;
+constexpr int kRowsApplyMaxSources = 1024;   // gradient workgroups (one per CU)
+__global__ void __launch_bounds__(kRowsApplyThreads) rows_apply_kernel(RowsApplyArgs p) {
+    extern __shared__ float table[];   // [rows][J_n]
+    __shared__ unsigned int fill[kRowsApplyMaxSources];
+    const int tid = threadIdx.x;
+    const int b = (int)blockIdx.x;
+    const int4 d = p.bucket_rows[b];
+    const int n = d.x, row0 = d.y, rows = d.z, J = p.J[n], stride = rows_entry_words(J);
+    const int cells = rows * J;
+    const uint2 info = p.bucket_info[b];
+    const int cap = (int)info.y;
+    for (int q = tid; q < cells; q += kRowsApplyThreads) table[q] = 0.0f;
+    for (int w = tid; w < p.n_sources; w += kRowsApplyThreads) fill[w] = p.list_fill[(size_t)b * p.n_sources + w];
+    __syncthreads();
+    // Every place of every source's list of this bucket is one work item (places past a list's fill
+    // are skipped), so that the loads of many lists are in flight at once: a thread takes `kAhead`
+    // entries at a time and asks for 16 floats of each, as 16-byte loads, before it adds the first.
+    constexpr int kAhead = 4;
+    typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+    const unsigned int places = (unsigned int)p.n_sources * (unsigned int)cap;   // below 2^31: checked by the host
+    for (unsigned int base = 0; base < places; base += kRowsApplyThreads * kAhead) {
+        const float* src[kAhead];
+        int row[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const unsigned int i = base + (unsigned int)(u * kRowsApplyThreads + tid);
+            const unsigned int w = i / (unsigned int)cap, place = i - w * (unsigned int)cap;
+            const bool valid = i < places && place < fill[w < (unsigned int)p.n_sources ? w : 0u];
+            src[u] = valid ? p.lists + (size_t)w * p.list_words + info.x + (size_t)place * stride : nullptr;
+            row[u] = valid ? (int)__float_as_uint(src[u][J]) - row0 : -1;
+        }
+        for (int j0 = 0; j0 < J; j0 += 16) {
+            uintx4 v[kAhead][4];
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u)
+#pragma unroll
+                for (int k4 = 0; k4 < 4; ++k4)   // words past J inside the entry are the row number and padding: read, not used
+                    v[u][k4] = (src[u] && j0 + 4 * k4 < J) ? *reinterpret_cast<const uintx4*>(src[u] + j0 + 4 * k4) : uintx4{0u, 0u, 0u, 0u};
+            // compare-and-swap adds, one entry's 16 floats at a time: all reads, then all swaps, and only
+            // the swaps that lost (another thread changed the cell in between) go round again
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u)
+                if (row[u] >= 0 && row[u] < rows) {
+                    unsigned int* cell = reinterpret_cast<unsigned int*>(table + row[u] * J + j0);
+                    unsigned int seen[16], got[16];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) seen[k] = j0 + k < J ? cell[k] : 0u;
+#pragma unroll
+                    for (int k = 0; k < 16; ++k)
+                        got[k] = j0 + k < J ? atomicCAS(cell + k, seen[k], __float_as_uint(__uint_as_float(seen[k]) + __uint_as_float(v[u][k >> 2][k & 3])))
+                                            : 0u;
+                    // lanes of one instruction that hit the same row lose together, on every cell of the row:
+                    // the lost swaps of a round all go out again before any is waited for
+                    bool lost = false;
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) lost = lost || got[k] != seen[k];
+                    while (lost) {
+                        unsigned int again[16];
+#pragma unroll
+                        for (int k = 0; k < 16; ++k)
+                            again[k] = got[k] != seen[k]
+                                           ? atomicCAS(cell + k, got[k], __float_as_uint(__uint_as_float(got[k]) + __uint_as_float(v[u][k >> 2][k & 3])))
+                                           : got[k];
+                        lost = false;
+#pragma unroll
+                        for (int k = 0; k < 16; ++k) {
+                            const bool was_lost = got[k] != seen[k];
+                            seen[k] = was_lost ? got[k] : seen[k];      // what the retry expected
+                            got[k] = was_lost ? again[k] : seen[k];     // settled cells compare equal from now on
+                            lost = lost || got[k] != seen[k];
+                        }
+                    }
+                }
+        }
+    }
+    __syncthreads();
+    float* A_rows = p.A + p.A_off[n] + (long long)row0 * J;
+    if (*p.overflow != 0u) {
+        float* dA_rows = p.dA + p.A_off[n] + (long long)row0 * J;
+        for (int q = tid; q < cells; q += kRowsApplyThreads) {
+            const float extra = dA_rows[q];
+            if (extra != 0.0f) {
+                table[q] += extra;
+                dA_rows[q] = 0.0f;
+            }
+        }
+    }
+    for (int q = tid; q < cells; q += kRowsApplyThreads) {
+        const float t = table[q];
+        if (t != 0.0f) A_rows[q] = fmaf(-p.lr_A, t, A_rows[q]);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -51,7 +51,7 @@ def one_step_case(w, idx, vals, A0=None, B0=None, seed=None, kernel=None, tiles=
         if kernel:
             ft.ftk_set_kernel(kernel)
             if kernel != "auto":
-                assert ft.ftk_kernel_name() == kernel
+                assert ft.ftk_kernel_name() == kernel.split(":")[0]
         if A0 is not None:
             ft.ftk_set_factors(A0, B0)
             A, B = [a.copy() for a in A0], [b.copy() for b in B0]
@@ -223,7 +223,7 @@ TINY = [
 
 
 @pytest.mark.parametrize("layout", ["padded", "exact"])
-@pytest.mark.parametrize("kernel", ["auto", "generic", "tiled", "mfma16"])
+@pytest.mark.parametrize("kernel", ["auto", "generic", "tiled", "mfma16", "rows"])
 @pytest.mark.parametrize("order,dims,nnz,J,R,M", TINY)
 def test_one_step_small_shapes(order, dims, nnz, J, R, M, kernel, layout):
     """Every gradient-kernel variant on every small shape: "auto" is the specialised J = R = 16 kernel
@@ -239,6 +239,15 @@ def test_one_step_small_shapes(order, dims, nnz, J, R, M, kernel, layout):
             one_step_case(w, idx, vals, kernel=kernel, flags=flags)
         assert e.value.code == binding.FTK_EUNSUPPORTED
         return
+    if kernel == "rows":
+        # the tiled kernel's shapes with every (possibly padded) J_n a multiple of four; refused elsewhere
+        padded = layout == "padded" and 2 <= order <= 5 and max(J) <= 16 and R <= 16
+        fits = padded or (all(j % 4 == 0 for j in J) and max(J) <= 64 and R <= 64 and (order <= 8 or (max(J) <= 16 and R <= 16)))
+        if not fits:
+            with pytest.raises(binding.FtkError) as e:
+                one_step_case(w, idx, vals, kernel=kernel, flags=flags)
+            assert e.value.code == binding.FTK_EUNSUPPORTED
+            return
     if kernel == "mfma16":
         # by name: where the (possibly padded) ranks are all 16 and the order is at most 6, also at order 6,
         # which "auto" gives to the tiled kernel; refused elsewhere
@@ -363,17 +372,18 @@ def test_matrix_core_kernel_with_ranks_off_the_block_size(order, dims, J, R, zip
         one_step_case(w, idx, vals, kernel="tiled", tiles=tiles, flags=binding.FTK_LAYOUT_EXACT)
 
 
+@pytest.mark.parametrize("kernel", [None, "rows"])
 @pytest.mark.parametrize("name,nnz,M,dims", [
     ("C2", 200_000, 20_000, (4_800, 1_777, 220)),
     ("C3", 100_000, 5_000, (10_000, 6_250, 300)),
     ("C4", 200_000, 20_000, (1_000,) * 6),
     ("C5", 50_000, 2_000, (4_800, 1_777, 220)),
 ])
-def test_one_step_scaled_workloads(name, nnz, M, dims):
-    announce("scaled %s" % name)
+def test_one_step_scaled_workloads(name, nnz, M, dims, kernel):
+    announce("scaled %s%s" % (name, ", kernel rows" if kernel else ""))
     w = synth.replace(synth.WORKLOADS[name].scaled(nnz=nnz, n_samples=M, dims=dims), **TEST_STEP_SIZES[name])
     idx, vals = synth.make_tensor(w)
-    one_step_case(w, idx, vals)
+    one_step_case(w, idx, vals, kernel=kernel)
 
 
 def test_signed_parameters_and_hot_rows():
@@ -409,6 +419,14 @@ COLD_ROW_CASES = [
     ("mfma16", (20_000, 50_000, 300, 40, 1_200), (1.1, None, None, None, None), (16,) * 5, 16, 300_000, 40_007, 0.3),
     ("tiled", (30_000, 50_000, 900), (1.1, None, None), (32, 32, 32), 32, 300_000, 40_011, 1e-2),   # 32-wide blocks
     ("tiled", (40_000, 60_000, 1_500), (1.1, None, None), (16, 16, 16), 16, 400_000, 60_013, 1e-2),
+    # the same rows through the lists of the row-owning workgroups instead of atomics: row number in a spare lane
+    # (J_n = 8, 20), in a store of its own (J_n = 16, 32), and with lists so short that many rows fall back to atomics
+    ("rows", (30_000, 50_000, 900), (1.1, None, None), (32, 32, 32), 32, 300_000, 40_011, 1e-2),
+    ("rows", (40_000, 60_000, 1_500), (1.1, None, None), (16, 16, 16), 16, 400_000, 60_013, 1e-2),
+    ("rows", (40_000, 60_000, 1_500), (1.1, None, None), (8, 20, 8), 16, 400_000, 60_013, 1e-2),
+    ("rows:tight", (40_000, 60_000, 1_500), (1.1, None, None), (8, 20, 8), 16, 400_000, 60_013, 1e-2),
+    ("rows:tight", (30_000, 50_000, 900), (1.1, None, None), (32, 32, 32), 32, 300_000, 40_011, 1e-2),
+    ("rows", (20_000, 50_000, 300, 40, 1_200, 700), (1.1, None, None, None, None, None), (8,) * 6, 16, 300_000, 40_007, 1.0),
 ]
 
 
@@ -449,7 +467,7 @@ def test_rows_outside_the_tables_hit_once_or_twice(kernel, dims, zipf, J, R, nnz
     draw = oracle.sample_positions_tiles if tiles else oracle.sample_positions
     with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed, flags=binding.FTK_LAYOUT_EXACT) as ft:
         ft.ftk_set_kernel(kernel)
-        assert ft.ftk_kernel_name() == kernel
+        assert ft.ftk_kernel_name() == kernel.split(":")[0]
         if tiles:
             ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
         ft.ftk_set_factors(A0, B0)
