@@ -27,11 +27,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
-# what the same counters read for kernels of known size (profiles/grad_mfma16_C2.txt, section 2)
-MEASURED_TRAFFIC_BYTES = {("C2", "grad:mfma16"): 171.7e6 + 108.8e6}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X fp32 dense matrix (and vector) peak, published
 KERNEL_SLOTS = ["sample_gather", "grad", "apply"]
+
+
+def measured_traffic_bytes(workload: str, kernel: str):
+    """HBM bytes of one launch of `kernel` on `workload` as rocprofv3's FETCH_SIZE / WRITE_SIZE counters measured
+    them (profiles/hbm_traffic.txt, which also says how); None where that kernel on that workload was not measured."""
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                cols = line.split()
+                if len(cols) >= 7 and not line.startswith("#") and cols[0] == workload and cols[1] == kernel:
+                    return float(cols[6]) * 1e6
+    except OSError:
+        pass
+    return None
 
 
 def algorithmic_bytes_per_sample(w) -> int:
@@ -95,8 +107,10 @@ def main() -> int:
         ft.ftk_set_mode(binding.FTK_HOGWILD)
     elif args.mode == "modewise":
         ft.ftk_set_mode(binding.FTK_HOGWILD_MODEWISE)
-    # the mode-by-mode in-place order runs on the one-lane-per-sample kernels whatever the shape
-    kernel_label = "generic, factor phase + core phase" if args.mode == "modewise" else ft.ftk_kernel_name()
+    # the mode-by-mode in-place order runs on the J = R = 16 kernel, or else on the one-lane-per-sample kernels
+    kernel_label = ft.ftk_kernel_name()
+    if args.mode == "modewise":
+        kernel_label = "%s, factor phase + core phase" % (kernel_label if kernel_label == "mfma16" else "generic")
     print("[bench] context ready, gradient kernel = %s" % kernel_label, file=sys.stderr, flush=True)
 
     def run_steps(first: int, count: int) -> None:
@@ -139,13 +153,21 @@ def main() -> int:
     else:
         head = {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved_gbs / HBM_PEAK_GBS}
+    # `traffic` only where this very kernel was measured on this workload under the default sampling rule and mode
+    traffic = None
+    if args.sampling == "entries" and args.mode == "sync" and args.layout == "padded":
+        traffic = measured_traffic_bytes(w.name, dominant + ":" + kernel_label)
     roofline = {
         **head, "kernel": dominant + ":" + kernel_label,
-        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant + ":" + kernel_label)),
-        "hbm_gbs_in_kernel": achieved_gbs, "hbm_frac_in_kernel": achieved_gbs / HBM_PEAK_GBS,
+        "traffic": traffic,
+        # two different things, named apart: algorithmic bytes over time ("effective"), and the bytes the
+        # HBM counters saw over the same time ("measured"; below the effective figure where rows hit in cache)
+        "effective_gbs": achieved_gbs, "effective_frac": achieved_gbs / HBM_PEAK_GBS,
+        "measured_hbm_gbs": None if traffic is None else traffic / (dom_ms * 1e-3) / 1e9,
+        "measured_hbm_frac": None if traffic is None else traffic / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "bytes_per_sample": algorithmic_bytes_per_sample(w), "avg_kernel_ms": dom_ms,
-        "whole_step_gbs": bytes_per_launch / (ms_per_step * 1e-3) / 1e9,
-        "whole_step_frac": bytes_per_launch / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "whole_step_effective_gbs": bytes_per_launch / (ms_per_step * 1e-3) / 1e9,
+        "whole_step_effective_frac": bytes_per_launch / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "flops_per_sample": algorithmic_flops_per_sample(w), "fp32_tflops_in_kernel": achieved_tflops,
         "per_kernel_ms": {k: v["avg_ms"] for k, v in per_kernel.items()},
     }

@@ -128,15 +128,18 @@ int ftk_get_samples(ftk_ctx* ctx, int64_t* pos_out);
  * accumulated per workgroup and added at the end of the step.  The core factors are updated once
  * per step from the accumulated gradient, M = |Psi| (Section 4.2).  Results depend on scheduling;
  * this mode is meant to be judged by its RMSE curve.
- * FTK_HOGWILD_MODEWISE removes the first two deviations at the price of a second pass: a factor
+ * FTK_HOGWILD_MODEWISE follows Algorithm 1 as printed, at the price of a second pass: a factor
  * phase in which every sample takes its modes one after the other, mode n using what modes < n of
- * the same sample have just written (Algorithm 1 lines 1-16), every row update a float atomic add
- * into A^(n), no per-workgroup accumulation; then a core phase over the same Psi that takes the
- * core gradient at the updated rows (lines 17-39) and updates every B^(n) once.  Samples still
- * run concurrently, so samples that share a row see each other's updates in no fixed order; on a
- * Psi whose samples share no row the result is that of the printed order up to fp32 rounding.
- * It runs on the one-lane-per-sample kernels only (FTK_EUNSUPPORTED where they do not fit the
- * shape) and is not tuned.
+ * the same sample have just written (Algorithm 1 lines 1-16: after mode n's row has moved by delta,
+ * the sample's projections c^(n) are advanced by delta B^(n), which is the projection of the row it
+ * has just written); then a core phase over the same Psi that takes the core gradient at the
+ * updated rows (lines 17-39) and updates every B^(n) once.  Samples still run concurrently, so
+ * samples that share a row see each other's updates in no fixed order; on a Psi whose samples share
+ * no row the result is that of the printed order up to fp32 rounding.
+ * It runs on the matrix cores where the "mfma16" kernel is in use (16 samples at a time; rows outside
+ * the workgroup tables are changed by float atomics as they are met, the most frequently hit rows
+ * are accumulated per workgroup and added when the factor phase ends), and on the one-lane-per-sample
+ * kernels otherwise (every row update a float atomic; FTK_EUNSUPPORTED where they do not fit the shape).
  */
 int ftk_sgd_step(ftk_ctx* ctx, float lr_A, float lr_B, float lambda_A, float lambda_B);
 

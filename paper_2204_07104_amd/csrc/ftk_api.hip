@@ -317,26 +317,36 @@ int launch_grad_generic(ftk_ctx* c, float lambda_A, float lr_A, bool modewise = 
     return FTK_OK;
 }
 
-template <int N, bool TILES, bool INPLACE>
-int launch_mfma16_nti(ftk_ctx* c, const Mfma16Args& g) {
-    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_mfma16_kernel<N, TILES, INPLACE>), c->max_lds)) return rc;
+template <int N, bool TILES, int MODE>
+int launch_mfma16_ntm(ftk_ctx* c, const Mfma16Args& g) {
+    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_mfma16_kernel<N, TILES, MODE>), c->max_lds)) return rc;
     if (c->prepare_only) return FTK_OK;
     Bracket t(c, FTK_K_GRAD);
-    hipLaunchKernelGGL((grad_mfma16_kernel<N, TILES, INPLACE>), dim3(c->mfma_grid), dim3(kMfmaThreads), c->mfma_lds_bytes,
+    hipLaunchKernelGGL((grad_mfma16_kernel<N, TILES, MODE>), dim3(c->mfma_grid), dim3(kMfmaThreads), c->mfma_lds_bytes,
                        c->stream, g);
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;
 }
 
-template <int N>
-int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g) {
-    const bool tiles = c->sampling == FTK_SAMPLE_TILES, in_place = c->mode == FTK_HOGWILD;
-    if (tiles) return in_place ? launch_mfma16_nti<N, true, true>(c, g) : launch_mfma16_nti<N, true, false>(c, g);
-    return in_place ? launch_mfma16_nti<N, false, true>(c, g) : launch_mfma16_nti<N, false, false>(c, g);
+template <int N, bool TILES>
+int launch_mfma16_nt(ftk_ctx* c, const Mfma16Args& g, int pass) {
+    switch (pass) {
+        case kSyncPass: return launch_mfma16_ntm<N, TILES, kSyncPass>(c, g);
+        case kInPlacePass: return launch_mfma16_ntm<N, TILES, kInPlacePass>(c, g);
+        case kFactorPhase: return launch_mfma16_ntm<N, TILES, kFactorPhase>(c, g);
+        default: return launch_mfma16_ntm<N, TILES, kCorePhase>(c, g);
+    }
 }
 
-int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
-    const bool in_place = c->mode == FTK_HOGWILD;
+template <int N>
+int launch_mfma16_n(ftk_ctx* c, const Mfma16Args& g, int pass) {
+    return c->sampling == FTK_SAMPLE_TILES ? launch_mfma16_nt<N, true>(c, g, pass) : launch_mfma16_nt<N, false>(c, g, pass);
+}
+
+// pass: kSyncPass / kInPlacePass by the context's mode (pass < 0), or one of the two phases of the mode-by-mode order
+int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A, int pass = -1) {
+    if (pass < 0) pass = c->mode == FTK_HOGWILD ? kInPlacePass : kSyncPass;
+    const bool in_place = pass == kInPlacePass || pass == kFactorPhase;
     Mfma16Args g;
     g.coo = sampled_records(c);
     g.rule = sample_rule(c);
@@ -365,12 +375,12 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A) {
     if (!c->mfma16_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->use_hot_partial || !c->use_gb_partial)
         return fail(c, FTK_EUNSUPPORTED, "mfma16 kernel is not available for this shape");
     switch (c->order) {
-        case 1: return launch_mfma16_n<1>(c, g);
-        case 2: return launch_mfma16_n<2>(c, g);
-        case 3: return launch_mfma16_n<3>(c, g);
-        case 4: return launch_mfma16_n<4>(c, g);
-        case 5: return launch_mfma16_n<5>(c, g);
-        case 6: return launch_mfma16_n<6>(c, g);
+        case 1: return launch_mfma16_n<1>(c, g, pass);
+        case 2: return launch_mfma16_n<2>(c, g, pass);
+        case 3: return launch_mfma16_n<3>(c, g, pass);
+        case 4: return launch_mfma16_n<4>(c, g, pass);
+        case 5: return launch_mfma16_n<5>(c, g, pass);
+        case 6: return launch_mfma16_n<6>(c, g, pass);
         default: return fail(c, FTK_EUNSUPPORTED, "mfma16 kernel is built for order <= 6");
     }
 }
@@ -1058,10 +1068,61 @@ int ftk_sgd_step_noalloc(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, flo
 
 namespace {
 
+// The update pass after a matrix-core gradient pass, in parts: `hot` adds the workgroups' tables of the frequent
+// rows to A (scaled by -lr_A; -1 where the tables already hold -lr_A x gradient), `core` updates B from the
+// workgroups' core-gradient tables.
+int launch_apply_parts(ftk_ctx* c, bool hot, bool core, float lr_A, float lr_B, float lambda_B) {
+    ApplyArgs p = {};
+    p.A = c->d_A;
+    p.dA = c->d_dA;
+    p.n4 = c->A_total / 4;
+    p.dense_blocks = 0;
+    if (hot) {
+        p.hot_partial = c->use_hot_partial;
+        p.hot_parts = c->mfma_grid;
+        p.H = c->hot_H;
+        p.J = 16;
+        p.hot_blocks = (c->hot_H * p.J + 63) / 64;
+        p.order = c->order;
+        for (int n = 0; n < kMaxOrder; ++n) {
+            p.Jn[n] = c->L.J[n];
+            p.K[n] = c->hot_K[n];
+            p.hot_off[n] = c->hot_off[n];
+            p.A_off[n] = c->L.A_off[n];
+        }
+    }
+    p.B = c->d_B;
+    p.GB = c->use_gb_partial;
+    p.B_total = c->L.B_total;
+    p.gb_parts = c->mfma_grid;
+    p.gb_clear = 0;
+    p.lr_A = lr_A;
+    p.lr_B = lr_B;
+    p.lambda_B = lambda_B;
+    p.inv_M = 1.0f / (float)c->n_samples;
+    const int b_blocks = core ? (c->L.B_total + 63) / 64 : 0;
+    if (p.hot_blocks + b_blocks < 1) return FTK_OK;
+    Bracket t(c, FTK_K_APPLY);
+    hipLaunchKernelGGL(apply_kernel, dim3(p.hot_blocks + b_blocks), dim3(256), 0, c->stream, p);
+    FTK_HIP(c, hipGetLastError());
+    return FTK_OK;
+}
+
+// Algorithm 1 in the order it is printed, on the matrix cores (J_n = R = 16 kernel): the factor phase (lines
+// 1-16: the modes of a sample in turn, rows changed in place), the tables of the frequent rows added to A, then
+// the core phase (lines 17-39) over the same Psi at the rows the factor phase left, and one update of B.
+int step_modewise_mfma16(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
+    if (int rc = launch_grad_mfma16(c, lambda_A, lr_A, kFactorPhase)) return rc;
+    if (int rc = launch_apply_parts(c, true, false, -1.0f, lr_B, lambda_B)) return rc;
+    if (int rc = launch_grad_mfma16(c, lambda_A, lr_A, kCorePhase)) return rc;
+    return launch_apply_parts(c, false, true, -1.0f, lr_B, lambda_B);
+}
+
 // One step over the current Psi with the partial tables c->use_hot_partial / c->use_gb_partial.
 int step_impl(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
-    // the mode-by-mode in-place order exists for the one-lane-per-sample kernels only
+    // the mode-by-mode in-place order: on the J_n = R = 16 kernel, else on the one-lane-per-sample kernels
     const bool modewise = c->mode == FTK_HOGWILD_MODEWISE;
+    if (modewise && c->variant == V_MFMA16) return step_modewise_mfma16(c, lr_A, lr_B, lambda_A, lambda_B);
     const bool mfma = c->variant != V_GENERIC && !modewise;   // a matrix-core variant: per-workgroup tables
     const bool tiled = c->variant == V_TILED && !modewise;
     const bool in_place = c->mode != FTK_SYNC;
@@ -1141,9 +1202,15 @@ int prepare_variant(ftk_ctx* c) {
     c->use_hot_partial = c->d_hot_partial;
     c->use_gb_partial = c->d_gb_partial;
     const bool modewise = c->mode == FTK_HOGWILD_MODEWISE;
-    const int rc = (c->variant == V_TILED && !modewise) ? launch_grad_tiled(c, 0.0f, 0.0f)
-                   : (c->variant == V_MFMA16 && !modewise) ? launch_grad_mfma16(c, 0.0f, 0.0f)
-                                                           : launch_grad_generic(c, 0.0f, 0.0f, modewise);
+    int rc;
+    if (modewise && c->variant == V_MFMA16) {
+        rc = launch_grad_mfma16(c, 0.0f, 0.0f, kFactorPhase);
+        if (rc == FTK_OK) rc = launch_grad_mfma16(c, 0.0f, 0.0f, kCorePhase);
+    } else {
+        rc = (c->variant == V_TILED && !modewise) ? launch_grad_tiled(c, 0.0f, 0.0f)
+             : (c->variant == V_MFMA16 && !modewise) ? launch_grad_mfma16(c, 0.0f, 0.0f)
+                                                     : launch_grad_generic(c, 0.0f, 0.0f, modewise);
+    }
     c->prepare_only = false;
     return rc;
 }
@@ -1313,8 +1380,8 @@ int ftk_set_mode(ftk_ctx* c, int mode) {
         return fail(c, FTK_EINVAL, "unknown mode %d", mode);
     if (mode != FTK_SYNC && c->rows)
         return fail(c, FTK_EUNSUPPORTED, "the \"rows\" kernel serves the synchronous step only");
-    if (mode == FTK_HOGWILD_MODEWISE && c->gen_threads == 0)
-        return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the one-lane-per-sample kernels, which do not fit this shape");
+    if (mode == FTK_HOGWILD_MODEWISE && c->variant != V_MFMA16 && c->gen_threads == 0)
+        return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the J_n = R = 16 kernel or on the one-lane-per-sample kernels, which do not fit this shape");
     c->mode = mode;
     return prepare_variant(c);
 }

@@ -171,7 +171,18 @@ __device__ __forceinline__ void gather_rows(const __amdgpu_buffer_rsrc_t (&rsrc_
 // parked as value 0 and, in every mode, as the row just past the mode's last one: the buffer
 // range check makes that row read as zeros, so the slot's projections, prediction, error and
 // gradients are all exact zeros, and it is on neither scatter list.  No masks in the arithmetic.
-template <int N, bool INPLACE>
+// MODE: what one pass over Psi does.
+//   kSyncPass     all gradients at the rows as gathered; rows outside the tables are added to the accumulator g.dA
+//   kInPlacePass  the same gradients scaled by g.scale = -lr_A and added straight into A (g.dA is A)
+//   kFactorPhase  Algorithm 1, lines 1-16, for the 16 samples of a tile at once: the modes of a sample are taken in
+//                 turn, and after mode n's row has moved by delta = -lr_A (-e GS^(n) + lambda_A a^(n)) the sample's
+//                 projections of that mode are advanced, c^(n) += delta B^(n) (one more 16x16 product), so that the
+//                 next mode's prediction, error and GS see the row mode n has just written; rows are updated as in
+//                 kInPlacePass; no core gradient
+//   kCorePhase    Algorithm 1, lines 17-39: only the core gradient, at the rows the factor phase left
+constexpr int kSyncPass = 0, kInPlacePass = 1, kFactorPhase = 2, kCorePhase = 3;
+
+template <int N, int MODE>
 __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, unsigned int hot_addr,
                                               unsigned int top_key, const unsigned int* scur, const unsigned int* snxt,
                                               float* tbuf, int c, int g4) {
@@ -225,6 +236,46 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 #pragma unroll
         for (int n = 0; n < N; ++n) s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][3], aX[n][3], s[n], 0, 0, 0);
 
+        float aY[N][4], wY[N][4], grad[N][4];
+        if constexpr (MODE == kFactorPhase) {
+            // rows in layout Y (for the regulariser term), out of the buffer before the gradients go into it
+            lds_wave_sync();
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) aY[n][v] = tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c];
+            lds_wave_sync();
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                // w^(n) from the projections as they stand: those of modes < n already advanced
+                floatx4 wn = {1.0f, 1.0f, 1.0f, 1.0f};
+#pragma unroll
+                for (int k = 0; k < N; ++k)
+                    if (k != n) wn *= s[k];
+                const floatx4 full = wn * s[n];
+                const float part_n = (full[0] + full[1]) + (full[2] + full[3]);
+                const floatx4 xsum_n = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, part_n, floatx4{0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0);
+                wn *= xsum_n[0] - x;   // -e w^(n)
+                floatx4 gsn = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) gsn = __builtin_amdgcn_mfma_f32_16x16x4f32(wn[k], st.Br[n][k], gsn, 0, 0, 0);
+                // delta of the row (layout Y), staged for the scatter below ...
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    grad[n][v] = g.scale * fmaf(g.lambda_A, aY[n][v], gsn[v]);
+                    tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c] = grad[n][v];
+                }
+                // ... and read back in layout X to advance the sample's projections of this mode
+                if (n + 1 < N) {
+                    lds_wave_sync();
+                    const float4 dx = *reinterpret_cast<const float4*>(tbuf + n * kTransposeFloats + c * 20 + 4 * g4);
+                    s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][0], dx.x, s[n], 0, 0, 0);
+                    s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][1], dx.y, s[n], 0, 0, 0);
+                    s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][2], dx.z, s[n], 0, 0, 0);
+                    s[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.Bq[n][3], dx.w, s[n], 0, 0, 0);
+                }
+            }
+        } else {
         // leave-one-out products (prefix sweep, then suffix sweep), prediction, error
         floatx4 w[N];
         floatx4 run = {1.0f, 1.0f, 1.0f, 1.0f};
@@ -248,7 +299,6 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 
         // rows in layout Y, out of the buffer before -e w goes into it
         lds_wave_sync();
-        float aY[N][4];
 #pragma unroll
         for (int n = 0; n < N; ++n)
 #pragma unroll
@@ -266,30 +316,31 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
         floatx4 gs[N];
 #pragma unroll
         for (int n = 0; n < N; ++n) gs[n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (MODE != kCorePhase) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+            for (int k = 0; k < 4; ++k)
 #pragma unroll
-            for (int n = 0; n < N; ++n)
-                gs[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[n][k], st.Br[n][k], gs[n], 0, 0, 0);
+                for (int n = 0; n < N; ++n)
+                    gs[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[n][k], st.Br[n][k], gs[n], 0, 0, 0);
+        }
         lds_wave_sync();
-        float wY[N][4];
 #pragma unroll
         for (int n = 0; n < N; ++n)
 #pragma unroll
             for (int v = 0; v < 4; ++v) wY[n][v] = tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c];
 
         // Factor-row gradients -e GS + lambda_A a (layout Y: one 64-byte row per 16 lanes).
-        float grad[N][4];
 #pragma unroll
         for (int n = 0; n < N; ++n)
 #pragma unroll
             for (int v = 0; v < 4; ++v) grad[n][v] = fmaf(g.lambda_A, aY[n][v], gs[n][v]);
-        if constexpr (INPLACE) {   // in-place mode adds -lr_A * gradient
+        if constexpr (MODE == kInPlacePass) {   // in-place mode adds -lr_A * gradient
 #pragma unroll
             for (int n = 0; n < N; ++n)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) grad[n][v] *= g.scale;
         }
+        }   // MODE != kFactorPhase
         // Where each row goes was decided when the group was parked:
         //   the 16 most frequent rows of a mode: summed over the tile by the matrix core against a
         //     one-hot operand, straight from the registers
@@ -300,10 +351,22 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
         // A global float atomic instruction costs this chip the same ~110 clocks of a per-CU unit
         // whether one or all four of its 16-lane rows are in range, so the lists matter: without
         // them nearly every instruction of every (mode, quarter) would carry at least one such row.
+        if constexpr (MODE == kCorePhase) {
+            // core gradient only: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
 #pragma unroll
-        for (int n = 0; n < N; ++n)
+            for (int v = 0; v < 4; ++v)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c] = grad[n][v];
+                for (int n = 0; n < N; ++n)
+                    st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
+            lds_wave_sync();   // the next tile overwrites the buffer
+            continue;
+        }
+        if constexpr (MODE != kFactorPhase) {   // (the factor phase has staged its rows mode by mode)
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) tbuf[n * kTransposeFloats + (4 * g4 + v) * 20 + c] = grad[n][v];
+        }
         lds_wave_sync();
 
         // Everything the scatter reads from the staged rows is asked for in one go: the values of the
@@ -364,11 +427,13 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
                     st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot[n][k], grad[n][k], st.Top[n], 0, 0, 0);
             }
         // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
+        if constexpr (MODE != kFactorPhase) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
+            for (int v = 0; v < 4; ++v)
 #pragma unroll
-            for (int n = 0; n < N; ++n)
-                st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
+                for (int n = 0; n < N; ++n)
+                    st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
+        }
 
         // LDS table, four list positions (16 rows) per batch.  Entries past the end of the list aim
         // at a row of +inf, which absorbs any finite addend: their swaps succeed and change nothing.
@@ -416,9 +481,8 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 }
 
 // TILES: Psi is drawn by the tile-sampling rule (runs of 64 neighbouring records) instead of entry
-// by entry.  INPLACE: the gradients are scaled by g.scale = -lr_A and rows outside the tables are
-// added straight into A (g.dA is A); otherwise g.scale is 1 and not looked at.
-template <int N, bool TILES, bool INPLACE>
+// by entry.  MODE: see process_group (in the synchronous pass g.scale is 1 and not looked at).
+template <int N, bool TILES, int MODE>
 __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g) {
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;   // 16-byte words per record
@@ -584,7 +648,7 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
             park_record(t + 1, rec, snxt);
             load_record(t + 2, rec);
             lds_wave_sync();
-            process_group<N, INPLACE>(g, st, hot_addr, top_key, scur, snxt, tbuf, c, g4);
+            process_group<N, MODE>(g, st, hot_addr, top_key, scur, snxt, tbuf, c, g4);
         };
         // The first turn is peeled off the loop: the loop proper is then entered with the same
         // sequence of outstanding memory operations as its own back edge, and the compiler's

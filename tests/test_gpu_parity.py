@@ -700,6 +700,8 @@ def test_other_workloads_full_size_one_step(name):
     ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "generic", binding.FTK_HOGWILD),
     ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "auto", binding.FTK_HOGWILD_MODEWISE),
     ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "auto", binding.FTK_HOGWILD_MODEWISE),
+    ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "generic", binding.FTK_HOGWILD_MODEWISE),
+    ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "generic", binding.FTK_HOGWILD_MODEWISE),
 ])
 def test_hogwild_mode_rmse_curve(name, nnz, M, dims, lr_A, lr_B, kernel, mode):
     """10 steps with factor rows updated in place.  The result depends on scheduling, so it is held
@@ -736,16 +738,19 @@ def test_hogwild_mode_rmse_curve(name, nnz, M, dims, lr_A, lr_B, kernel, mode):
     assert_params_close(gB, B0, "B")
 
 
-def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared():
+@pytest.mark.parametrize("kernel,N,J,R,lr_A", [("mfma16", 3, (16, 8, 12), 8, 5e-2), ("generic", 3, (16, 8, 12), 8, 5e-2),
+                                               ("mfma16", 5, (16, 16, 16, 16, 16), 16, 1e-3), ("mfma16", 2, (4, 16), 11, 5e-2)])
+def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared(kernel, N, J, R, lr_A):
     """Every stored entry has rows of its own in every mode, and Psi holds no position twice: then
     no two samples touch the same row, running them at once changes nothing, and one step in
     FTK_HOGWILD_MODEWISE has to give what Algorithm 1 gives when its lines are followed one sample
     after the other -- parameter by parameter.  The step is large enough that following the modes in
-    turn matters: the same step with all gradients taken at the starting rows lands elsewhere."""
-    announce("modewise in-place, conflict-free")
-    nnz, N, J, R = 6000, 3, (16, 8, 12), 8
+    turn matters: the same step with all gradients taken at the starting rows lands elsewhere.
+    On the matrix cores (J_n = R = 16 kernel, ranks padded to 16) and on the one-lane-per-sample kernels."""
+    announce("modewise in-place, conflict-free, kernel=%s order=%d" % (kernel, N))
+    nnz = 6000
     rng = np.random.default_rng(11)
-    dims = (nnz, nnz, nnz)
+    dims = (nnz,) * N
     idx = [rng.permutation(nnz).astype(np.int32) for _ in range(N)]
     vals = rng.uniform(1.0, 5.0, nnz).astype(np.float32)
     M, seed = 60, 0
@@ -754,10 +759,12 @@ def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared()
         if len(set(pos.tolist())) == M:
             break
         seed += 1
-    lr_A, lr_B, lam_A, lam_B = 5e-2, 1e-2, 1e-2, 1e-2
+    lr_B, lam_A, lam_B = 1e-2, 1e-2, 1e-2
     A, B = oracle.init_factors(3, dims, J, R)
     A_sync, B_sync = [a.copy() for a in A], [b.copy() for b in B]
     with binding.FastTucker(dims, idx, vals, J, R, 3) as ft:
+        ft.ftk_set_kernel(kernel)
+        assert ft.ftk_kernel_name() == kernel
         ft.ftk_set_mode(binding.FTK_HOGWILD_MODEWISE)
         ft.ftk_sample(seed, M)
         assert np.array_equal(ft.ftk_get_samples(), pos)
