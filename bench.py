@@ -3,7 +3,9 @@
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2]
 
-A "step" is one pass of the whole hot path over one sample set Psi:
+W warm-up steps, then exactly K timed steps between two events on the library's stream (before the warm-up,
+untimed steps are run for --spin-up-seconds of wall time so that the clocks are up; they are reported as
+`spin_up_steps`).  A "step" is one pass of the whole hot path over one sample set Psi:
 ftk_sample (Philox positions + COO fetch) followed by ftk_sgd_step (row gather, projections,
 leave-one-out products, both gradients, both updates).  Inputs are resident in HBM before the
 timed region.  Prints ONE JSON line; `value` is sampled nonzeros per second.
@@ -74,6 +76,9 @@ def main() -> int:
     ap.add_argument("--mode", default="sync", choices=["sync", "hogwild", "modewise"],
                     help="'hogwild' / 'modewise' time the in-place modes (not the headline metric)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target wall time of the CPU-oracle leg (0: skip)")
+    ap.add_argument("--spin-up-seconds", type=float, default=0.3,
+                    help="untimed steps run before the W warm-up steps until this much wall time has passed, so that a "
+                         "short run (K = 20) is not timed on a GPU that is still clocking up; 0: none")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -119,7 +124,15 @@ def main() -> int:
             ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
 
     K, W = args.steps, args.warmup
-    run_steps(0, W)
+    # spin-up (untimed, before the warm-up steps): the first milliseconds after an idle period run at reduced clocks
+    spun = 0
+    t_spin = time.perf_counter()
+    while time.perf_counter() - t_spin < args.spin_up_seconds:
+        run_steps(spun, 50)
+        torch.cuda.synchronize()
+        spun += 50
+    run_steps(spun, W)
+    W += spun          # step numbers (sampling seeds) of the timed steps follow on
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -211,8 +224,9 @@ def main() -> int:
                   % (w.order, ("%dM" % (w.nnz // 1_000_000)) if w.nnz >= 1_000_000 else str(w.nnz),
                      ("J=R=%d" % w.R) if set(w.J) == {w.R} else
                      ("J=%s R=%d" % (w.J[0] if len(set(w.J)) == 1 else list(w.J), w.R))),
-        "value": value, "unit": "nonzeros/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "value": value, "unit": "nonzeros/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "spin_up_steps": spun,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: order-%d COO %s, nnz=%d, J=%s, R=%d, |Psi|=%d per step, %s step%s"
                                % (w.name, w.order, "x".join(str(d) for d in w.dims), w.nnz, list(w.J), w.R, w.n_samples,
