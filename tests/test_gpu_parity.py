@@ -310,11 +310,12 @@ def test_one_step_random_shapes(case_seed):
     assert ran or order * R > 256
 
 
-@pytest.mark.parametrize("order,dims,J,R", [
-    (3, (900, 300, 40), (16, 16, 16), 16),
-    (3, (500, 200, 30), (20, 7, 33), 12),
+@pytest.mark.parametrize("order,dims,J,R,kernel", [
+    (3, (900, 300, 40), (16, 16, 16), 16, None),
+    (3, (500, 200, 30), (20, 7, 33), 12, None),
+    (3, (9_000, 3_000, 40), (20, 8, 32), 12, "rows"),     # the lists are re-planned (and grow) with |Psi|
 ])
-def test_sample_count_changing_from_step_to_step(order, dims, J, R):
+def test_sample_count_changing_from_step_to_step(order, dims, J, R, kernel):
     """|Psi| changes every step (1 sample, one group, many groups, back): the number of workgroups, the rows
     kept in the workgroup tables and the partial tables the update pass reads all follow it.  Parameters
     against the oracle after every step, both sampling rules."""
@@ -326,6 +327,9 @@ def test_sample_count_changing_from_step_to_step(order, dims, J, R):
         draw = oracle.sample_positions_tiles if tiles else oracle.sample_positions
         A, B = oracle_state(w)
         with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed) as ft:
+            if kernel:
+                ft.ftk_set_kernel(kernel)
+                assert ft.ftk_kernel_name() == kernel
             if tiles:
                 ft.ftk_set_sampling(binding.FTK_SAMPLE_TILES)
             for t, M in enumerate([700, 64, 9_000, 1, 3_329, 130, 20_000, 65]):
@@ -667,21 +671,25 @@ def test_c2_full_size_one_step():
     assert moved_B > 1e-2, moved_B
 
 
-@pytest.mark.parametrize("name", ["C3", "C4", "C5", "C2 at J = R = 8"])
+@pytest.mark.parametrize("name", ["C3", "C4", "C5", "C2 at J = R = 8", "C4 with row owners"])
 def test_other_workloads_full_size_one_step(name):
     """The other named workloads at full size, on the kernel the library picks for them: the sample
     set bit-exact and every parameter after one synchronous step against the oracle (up to half a
     minute of one host core for the 4e6 samples of C3 and the 64 x 64 contractions of C5).  The C2
     tensor at J = R = 8, the paper's most used ranks, runs on the J = R = 16 kernel through the padded
     layout: the same comparison at full size for that route."""
+    kernel = None
     if name == "C2 at J = R = 8":
         w = synth.replace(synth.WORKLOADS["C2"], J=(8, 8, 8), R=8, lr_A=1e-7, lr_B=1e-2)
+    elif name == "C4 with row owners":     # the "rows" kernel at full size: 12e6 list entries per step
+        w = synth.replace(synth.WORKLOADS["C4"], **TEST_STEP_SIZES["C4"])
+        kernel = "rows"
     else:
         w = synth.replace(synth.WORKLOADS[name], **TEST_STEP_SIZES[name])
     announce("%s full size: generating" % name)
     idx, vals = synth.make_tensor(w)
     announce("%s full size: step" % name)
-    gA, gB, A, B = one_step_case(w, idx, vals)
+    gA, gB, A, B = one_step_case(w, idx, vals, kernel=kernel)
     A0, B0 = oracle_state(w)
     assert all(np.isfinite(a).all() for a in A + B)
     moved_A = max(float(np.abs(a.astype(np.float64) - a0).max()) for a, a0 in zip(A, A0))
