@@ -106,6 +106,7 @@ struct ftk_ctx {
     float* d_gb_partial = nullptr;    // [mfma_grid][B_total]
     // "rows" form of the tiled variant: rows outside the tables are appended to per-workgroup lists and summed by
     // row-owning workgroups (ftk_kernels_tiled.hpp, ROWS)
+    bool pair_turns = false;         // J = R = 16 kernel: turns in pairs that share their Philox blocks (large |Psi|, entry rule)
     bool rows_ok = false;            // the shape has a bucket plan (set at create)
     bool rows = false;               // in use (only with variant == V_TILED)
     bool rows_tight = false;         // list capacities at half the expected counts: lists fill up all the time (for tests)
@@ -356,6 +357,7 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A, int pass = -1) {
     g.B = c->d_B;
     g.dA = in_place ? c->d_A : c->d_dA;
     g.scale = in_place ? -lr_A : 1.0f;
+    g.pair_turns = c->pair_turns ? 1 : 0;
     for (int n = 0; n < kMfma16MaxOrder; ++n) {
         g.A_off[n] = c->L.A_off[n];
         g.B_off[n] = c->L.B_off[n];
@@ -611,7 +613,10 @@ int pick_hot_rows(ftk_ctx* c, long long n_samples) {
         // a wave's unit of work: 64 samples, or 128 (two turns that share their Philox blocks) in the
         // J = R = 16 kernel under the entry-sampling rule
         const long long waves = c->variant == V_TILED ? c->tiled_waves : kMfmaWaves;
-        const long long unit = (c->variant == V_MFMA16 && c->sampling == FTK_SAMPLE_ENTRIES) ? 128 : 64;
+        // pairs only where every wave of a full launch has at least two groups of 64 anyway
+        c->pair_turns = c->variant == V_MFMA16 && c->sampling == FTK_SAMPLE_ENTRIES &&
+                        (n_samples + 63) / 64 >= 2LL * c->mfma_grid_max * kMfmaWaves;
+        const long long unit = c->pair_turns ? 128 : 64;
         const long long units = (n_samples + unit - 1) / unit;
         c->mfma_grid = (int)std::max<long long>(1, std::min<long long>(c->mfma_grid_max, (units + waves - 1) / waves));
     }
@@ -1382,8 +1387,11 @@ int ftk_set_mode(ftk_ctx* c, int mode) {
         return fail(c, FTK_EUNSUPPORTED, "the \"rows\" kernel serves the synchronous step only");
     if (mode == FTK_HOGWILD_MODEWISE && c->variant != V_MFMA16 && c->gen_threads == 0)
         return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the J_n = R = 16 kernel or on the one-lane-per-sample kernels, which do not fit this shape");
+    const int old_mode = c->mode;
     c->mode = mode;
-    return prepare_variant(c);
+    const int rc = prepare_variant(c);
+    if (rc != FTK_OK) c->mode = old_mode;
+    return rc;
 }
 
 int ftk_set_stream(ftk_ctx* c, void* hip_stream) {

@@ -98,6 +98,7 @@ struct Mfma16Args {
     unsigned int first_row[kMfma16MaxOrder];   // A_off[n] / 16: number of mode n's row 0 counted over the packed array
     float lambda_A;
     float scale;              // 1 (synchronous: the update pass applies -lr_A) or -lr_A (in-place mode)
+    int pair_turns;           // entry-sampling rule: a wave's turns come in pairs that share their Philox blocks (see the kernel)
 };
 
 __device__ __forceinline__ void lds_wave_sync() {
@@ -200,12 +201,19 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
     for (int sub = 0; sub < 4; ++sub) {
         // The tile's scatter lists were written when the group was parked: their first batches and
         // lengths are asked for now, long before they are used.
+        // (Up to order 3, where the registers allow it; above, everything is read where it is used.)
+        constexpr bool AHEAD = N <= 3;
         const unsigned int* alist = atomic_list + sub * (16 * N) + g4 * (4 * N);
         const unsigned int* tlist = table_list + sub * (16 * N) + g4 * (4 * N);
-        const uint4 a_first = *reinterpret_cast<const uint4*>(alist);
-        const uint4 a_second = N > 1 ? *reinterpret_cast<const uint4*>(alist + 4) : a_first;
-        const uint4 t_first = *reinterpret_cast<const uint4*>(tlist);
-        const unsigned int len_atomic = list_len[sub], len_table = list_len[4 + sub];
+        uint4 a_first = {0u, 0u, 0u, 0u}, a_second = {0u, 0u, 0u, 0u}, t_first = {0u, 0u, 0u, 0u};
+        unsigned int len_atomic = 0u, len_table = 0u;
+        if constexpr (AHEAD) {
+            a_first = *reinterpret_cast<const uint4*>(alist);
+            a_second = N > 1 ? *reinterpret_cast<const uint4*>(alist + 4) : a_first;
+            t_first = *reinterpret_cast<const uint4*>(tlist);
+            len_atomic = list_len[sub];
+            len_table = list_len[4 + sub];
+        }
 
         if (sub == 0)
             gather_rows<N>(rsrc_A, scur, 3, c, g4, st.ring[3]);
@@ -369,42 +377,6 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
         }
         lds_wave_sync();
 
-        // Everything the scatter reads from the staged rows is asked for in one go: the values of the
-        // first eight atomic-list positions and of the first four table-list positions.
-        const unsigned int ea[8] = {a_first.x, a_first.y, a_first.z, a_first.w, a_second.x, a_second.y, a_second.z, a_second.w};
-        const unsigned int et[4] = {t_first.x, t_first.y, t_first.z, t_first.w};
-        float aval[8], tval[4];
-        unsigned int cell[4], seen[4];
-#pragma unroll
-        for (int i = 0; i < (N > 1 ? 8 : 4); ++i) aval[i] = tbuf[(ea[i] & 127u) * 20u + (unsigned int)c];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) tval[i] = tbuf[(et[i] >> 20) * 20u + (unsigned int)c];
-        // one-hot operands of the 16 most frequent rows: all compares first, then the products
-        float onehot[N][4];
-#pragma unroll
-        for (int n = 0; n < N; ++n)
-            if (g.top[n] > 0) {
-                const uint4 r = *reinterpret_cast<const uint4*>(scur + n * 64 + sub * 16 + 4 * g4);
-                onehot[n][0] = r.x == top_key ? 1.0f : 0.0f;
-                onehot[n][1] = r.y == top_key ? 1.0f : 0.0f;
-                onehot[n][2] = r.z == top_key ? 1.0f : 0.0f;
-                onehot[n][3] = r.w == top_key ? 1.0f : 0.0f;
-            }
-        const int n_atomic = __builtin_amdgcn_readfirstlane((int)len_atomic);
-        const int n_table = __builtin_amdgcn_readfirstlane((int)len_table);
-
-        // Global atomics.  Eight instructions go out whatever the list holds (entries past its end
-        // aim beyond the array and are dropped by the hardware, cheaply): a fixed count lets the
-        // compiler wait for prefetched rows without waiting for atomics issued after them.
-#pragma unroll
-        for (int i = 0; i < (N > 1 ? 8 : 4); ++i)
-            __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(aval[i], rsrc_dA, (int)(((ea[i] >> 1) & ~63u) | c4), 0, 0);
-        // the table cells of the first batch are read while the matrix core is busy below
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            cell[i] = hot_addr + (et[i] & 0xfffffu) + c4;
-            seen[i] = *(lds_u32*)(uintptr_t)cell[i];
-        }
         auto atomics4 = [&](int first) {
             const uint4 e4 = *reinterpret_cast<const uint4*>(alist + first);
             const unsigned int e[4] = {e4.x, e4.y, e4.z, e4.w};
@@ -415,28 +387,9 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
             for (int i = 0; i < 4; ++i)
                 __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val[i], rsrc_dA, (int)(((e[i] >> 1) & ~63u) | c4), 0, 0);
         };
-#pragma unroll
-        for (int b = 2; b < N; ++b)
-            if (n_atomic > 16 * b) atomics4(4 * b);
-
-#pragma unroll
-        for (int n = 0; n < N; ++n)
-            if (g.top[n] > 0) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot[n][k], grad[n][k], st.Top[n], 0, 0, 0);
-            }
-        // core gradient: GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
-        if constexpr (MODE != kFactorPhase) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-#pragma unroll
-                for (int n = 0; n < N; ++n)
-                    st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
-        }
-
         // LDS table, four list positions (16 rows) per batch.  Entries past the end of the list aim
         // at a row of +inf, which absorbs any finite addend: their swaps succeed and change nothing.
+        int n_table = 0;
         auto swap4 = [&](int first, const float (&val)[4], const unsigned int (&cl)[4], const unsigned int (&sn)[4]) {
             unsigned int got[4];
 #pragma unroll
@@ -460,22 +413,106 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
                 }
             }
         };
-        if (n_table > 0) swap4(0, tval, cell, seen);
+        auto table4 = [&](int first) {   // one batch, read where it is used
+            const uint4 e4 = *reinterpret_cast<const uint4*>(tlist + first);
+            const unsigned int e[4] = {e4.x, e4.y, e4.z, e4.w};
+            float val[4];
+            unsigned int cl[4], sn[4];
 #pragma unroll
-        for (int b = 1; b < N; ++b)
-            if (n_table > 16 * b) {
-                const uint4 e4 = *reinterpret_cast<const uint4*>(tlist + 4 * b);
-                const unsigned int e[4] = {e4.x, e4.y, e4.z, e4.w};
-                float val[4];
-                unsigned int cl[4], sn[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    val[i] = tbuf[(e[i] >> 20) * 20u + (unsigned int)c];
-                    cl[i] = hot_addr + (e[i] & 0xfffffu) + c4;
-                    sn[i] = *(lds_u32*)(uintptr_t)cl[i];
-                }
-                swap4(4 * b, val, cl, sn);
+            for (int i = 0; i < 4; ++i) {
+                val[i] = tbuf[(e[i] >> 20) * 20u + (unsigned int)c];
+                cl[i] = hot_addr + (e[i] & 0xfffffu) + c4;
+                sn[i] = *(lds_u32*)(uintptr_t)cl[i];
             }
+            swap4(first, val, cl, sn);
+        };
+        auto core_gradient = [&]() {   // GB[j = 4g+v'][r = c] += sum_samples a_j (-e w_r)
+            if constexpr (MODE != kFactorPhase) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int n = 0; n < N; ++n)
+                        st.GBacc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][v], wY[n][v], st.GBacc[n], 0, 0, 0);
+            }
+        };
+
+        if constexpr (AHEAD) {
+            // Everything the scatter reads from the staged rows is asked for in one go: the values of the
+            // first eight atomic-list positions and of the first four table-list positions.
+            const unsigned int ea[8] = {a_first.x, a_first.y, a_first.z, a_first.w, a_second.x, a_second.y, a_second.z, a_second.w};
+            const unsigned int et[4] = {t_first.x, t_first.y, t_first.z, t_first.w};
+            float aval[8], tval[4];
+            unsigned int cell[4], seen[4];
+#pragma unroll
+            for (int i = 0; i < (N > 1 ? 8 : 4); ++i) aval[i] = tbuf[(ea[i] & 127u) * 20u + (unsigned int)c];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) tval[i] = tbuf[(et[i] >> 20) * 20u + (unsigned int)c];
+            // one-hot operands of the 16 most frequent rows: all compares first, then the products
+            float onehot[N][4];
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+                if (g.top[n] > 0) {
+                    const uint4 r = *reinterpret_cast<const uint4*>(scur + n * 64 + sub * 16 + 4 * g4);
+                    onehot[n][0] = r.x == top_key ? 1.0f : 0.0f;
+                    onehot[n][1] = r.y == top_key ? 1.0f : 0.0f;
+                    onehot[n][2] = r.z == top_key ? 1.0f : 0.0f;
+                    onehot[n][3] = r.w == top_key ? 1.0f : 0.0f;
+                }
+            const int n_atomic = __builtin_amdgcn_readfirstlane((int)len_atomic);
+            n_table = __builtin_amdgcn_readfirstlane((int)len_table);
+
+            // Global atomics.  Eight instructions go out whatever the list holds (entries past its end
+            // aim beyond the array and are dropped by the hardware, cheaply): a fixed count lets the
+            // compiler wait for prefetched rows without waiting for atomics issued after them.
+#pragma unroll
+            for (int i = 0; i < (N > 1 ? 8 : 4); ++i)
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(aval[i], rsrc_dA, (int)(((ea[i] >> 1) & ~63u) | c4), 0, 0);
+            // the table cells of the first batch are read while the matrix core is busy below
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                cell[i] = hot_addr + (et[i] & 0xfffffu) + c4;
+                seen[i] = *(lds_u32*)(uintptr_t)cell[i];
+            }
+#pragma unroll
+            for (int b = 2; b < N; ++b)
+                if (n_atomic > 16 * b) atomics4(4 * b);
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+                if (g.top[n] > 0) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot[n][k], grad[n][k], st.Top[n], 0, 0, 0);
+                }
+            core_gradient();
+            if (n_table > 0) swap4(0, tval, cell, seen);
+#pragma unroll
+            for (int b = 1; b < N; ++b)
+                if (n_table > 16 * b) table4(4 * b);
+        } else {
+            // the same steps with everything read where it is used (fewer values alive at once)
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+                if (g.top[n] > 0) {
+                    const uint4 r = *reinterpret_cast<const uint4*>(scur + n * 64 + sub * 16 + 4 * g4);
+                    const unsigned int rw[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float onehot = rw[k] == top_key ? 1.0f : 0.0f;
+                        st.Top[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot, grad[n][k], st.Top[n], 0, 0, 0);
+                    }
+                }
+            const int n_atomic = __builtin_amdgcn_readfirstlane((int)list_len[sub]);
+            n_table = __builtin_amdgcn_readfirstlane((int)list_len[4 + sub]);
+            atomics4(0);
+            if (N > 1) atomics4(4);
+#pragma unroll
+            for (int b = 2; b < N; ++b)
+                if (n_atomic > 16 * b) atomics4(4 * b);
+            core_gradient();
+#pragma unroll
+            for (int b = 0; b < N; ++b)
+                if (n_table > 16 * b) table4(4 * b);
+        }
         lds_wave_sync();   // the next tile overwrites the staged rows
     }
 }
@@ -525,21 +562,23 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
 
     // Which samples a wave takes.  Its turns are numbered t = 0, 1, 2, ...; the wave is number
     // `wave_id` of `n_waves` in the launch.
-    //   entry rule: turns 2u and 2u + 1 share the 128 samples [128 q, 128 q + 128), q = wave_id +
-    //     u * n_waves: lane l takes sample 128 q + 2 l in the even turn and 128 q + 2 l + 1 in the odd
-    //     one.  Both come out of ONE Philox block (counter 64 q + l, low and high pair of words), which is
-    //     evaluated in the even turn only.
-    //   tile rule: turn t is run t * n_waves + wave_id, lane l its l-th record.
+    //   paired turns (entry rule, when every wave has several turns: g.pair_turns): turns 2u and
+    //     2u + 1 share the 128 samples [128 q, 128 q + 128), q = wave_id + u * n_waves: lane l takes
+    //     sample 128 q + 2 l in the even turn and 128 q + 2 l + 1 in the odd one.  Both come out of ONE
+    //     Philox block (counter 64 q + l, low and high pair of words), evaluated in the even turn only.
+    //   otherwise: turn t is the group of 64 samples (tile rule: the run) number t * n_waves + wave_id,
+    //     lane l its l-th sample.
     // Which lane and turn a sample lands in changes the order of the sums only.
     const long long wave_id = (long long)blockIdx.x * kMfmaWaves + wave;
     const long long n_waves = (long long)gridDim.x * kMfmaWaves;
-    const long long n_turns_all = TILES ? (M + 63) / 64 : 2 * ((M + 127) / 128);   // over all waves
+    const bool paired = !TILES && g.pair_turns != 0;
+    const long long n_turns_all = paired ? 2 * ((M + 127) / 128) : (M + 63) / 64;   // over all waves
     auto sample_of = [&](long long t) -> long long {   // this lane's sample number in turn t
-        if constexpr (TILES) return (t * n_waves + wave_id) * 64 + lane;
+        if (!paired) return (t * n_waves + wave_id) * 64 + lane;
         return ((t >> 1) * n_waves + wave_id) * 128 + 2 * lane + (t & 1);
     };
     auto turn_exists = [&](long long t) -> bool {      // wave-uniform: the turn holds at least one sample slot below M's last group
-        if constexpr (TILES) return t * n_waves + wave_id < n_turns_all;
+        if (!paired) return t * n_waves + wave_id < n_turns_all;
         return 2 * ((t >> 1) * n_waves + wave_id) < n_turns_all;
     };
     uint32_t odd_place = 0u;   // entry rule: where the odd turn's sample is read, kept from the even turn
@@ -551,6 +590,8 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
         uint32_t p;
         if constexpr (TILES) {
             p = tile_place(g.seed, (uint64_t)k, g.rule);
+        } else if (!paired) {
+            p = sample_position(g.seed, (uint64_t)k, g.rule.nnz);
         } else {
             if ((t & 1) == 0) {
                 const uint64_t ctr = (uint64_t)k >> 1;
