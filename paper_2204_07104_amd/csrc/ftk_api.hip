@@ -18,6 +18,8 @@
 #include "ftk_kernels_generic.hpp"
 #include "ftk_kernels_mfma16.hpp"
 #include "ftk_kernels_tiled.hpp"
+#define FTK_INSTANCES_EXTERN
+#include "ftk_instances.hpp"   // the matrix-core kernel instances are compiled in translation units of their own
 
 using namespace ftk;
 

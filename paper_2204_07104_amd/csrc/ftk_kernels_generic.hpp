@@ -55,6 +55,9 @@ struct Coo {
 
 __host__ __device__ inline int record_words(int order) { return ((order + 1 + 3) / 4) * 4; }
 
+// Kernels that are no templates are defined once, in the host file's translation unit: the units that hold the
+// instances of the matrix-core kernel templates define FTK_TEMPLATE_KERNELS_ONLY and skip them.
+#ifndef FTK_TEMPLATE_KERNELS_ONLY
 // ---------------------------------------------------------------------------------------------
 // Psi: positions from Philox, and the sampled entries gathered into a dense batch
 // (step a1 + a2: the only place the tensor is read with random access).
@@ -416,5 +419,7 @@ __global__ void __launch_bounds__(256) widen_positions_kernel(const uint32_t* __
     const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (k < count) out[k] = (long long)pos[k];
 }
+
+#endif  // FTK_TEMPLATE_KERNELS_ONLY
 
 }  // namespace ftk

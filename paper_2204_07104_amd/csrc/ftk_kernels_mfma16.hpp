@@ -856,6 +856,7 @@ struct ApplyArgs {
     unsigned int* clear_word;   // a counter to reset for the next step (or NULL)
 };
 
+#ifndef FTK_TEMPLATE_KERNELS_ONLY   // no template: defined in the host file's translation unit only
 __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
     __shared__ float red[4][64];
     const int tid = threadIdx.x;
@@ -932,5 +933,6 @@ __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
         if (q == 0 && p.clear_word) *p.clear_word = 0u;
     }
 }
+#endif
 
 }  // namespace ftk

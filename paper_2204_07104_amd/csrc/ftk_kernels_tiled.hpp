@@ -625,6 +625,7 @@ struct RowsApplyArgs {
 
 constexpr int kRowsApplyThreads = 512;
 constexpr int kRowsApplyMaxSources = 1024;   // gradient workgroups (one per CU)
+#ifndef FTK_TEMPLATE_KERNELS_ONLY   // no template: defined in the host file's translation unit only
 __global__ void __launch_bounds__(kRowsApplyThreads) rows_apply_kernel(RowsApplyArgs p) {
     extern __shared__ float table[];   // [rows][J_n]
     __shared__ unsigned int fill[kRowsApplyMaxSources];
@@ -716,6 +717,7 @@ __global__ void __launch_bounds__(kRowsApplyThreads) rows_apply_kernel(RowsApply
         if (t != 0.0f) A_rows[q] = fmaf(-p.lr_A, t, A_rows[q]);
     }
 }
+#endif
 
 // ---------------------------------------------------------------------------------------------
 // Evaluation pass over all stored entries (RMSE / MAE) for the same shapes: records streamed,
