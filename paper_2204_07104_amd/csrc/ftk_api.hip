@@ -12,6 +12,7 @@
 #include <new>
 #include <string>
 #include <utility>
+#include <limits>
 #include <vector>
 
 #include "../../include/ftk.h"
@@ -105,6 +106,11 @@ struct ftk_ctx {
     int mfma_grid_max = 0;            // what the partial tables are sized for (one workgroup per CU)
     size_t mfma_lds_bytes = 0;
     float* d_hot_partial = nullptr;   // [mfma_grid][hot_H][16]
+    // Ranks above 32 (tiled kernel, P = 4): A, dA and the workgroups' tables of the frequent rows are ONE allocation
+    // (d_A its start), because there the table rows are added by the same buffer atomics as the rows of dA (or of A,
+    // in-place mode) and must be within reach of the same 32-bit offsets.  The tables are zero between steps.
+    float* d_arena = nullptr;
+    float* d_wide_tables = nullptr;   // [mfma_grid][hot_H][16 P], behind dA; NULL: no such tables (K[n] = top[n])
     float* d_gb_partial = nullptr;    // [mfma_grid][B_total]
     // "rows" form of the tiled variant: rows outside the tables are appended to per-workgroup lists and summed by
     // row-owning workgroups (ftk_kernels_tiled.hpp, ROWS)
@@ -420,6 +426,9 @@ int launch_tiled_n(ftk_ctx* c, const TiledArgs& g) {
     }
 }
 
+// Ranks above 32 on the tiled kernel: the workgroups' tables of the frequent rows are the ones behind dA, filled by atomics.
+inline bool wide_tables(const ftk_ctx* c) { return c->variant == V_TILED && c->tiled_P == 4 && c->d_wide_tables != nullptr; }
+
 int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
     const bool in_place = c->mode == FTK_HOGWILD;
     TiledArgs g;
@@ -442,7 +451,20 @@ int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
         g.mode_bytes[n] = (unsigned int)(c->dims[n] * c->L.J[n] * 4);
     }
     g.H = c->hot_H;
-    g.hot_partial = c->use_hot_partial;
+    g.hot_partial = wide_tables(c) ? c->d_wide_tables : c->use_hot_partial;
+    g.table_stride = (unsigned int)((size_t)c->hot_H * 16 * c->tiled_P * sizeof(float));
+    for (int n = 0; n < kMaxOrder; ++n) {
+        g.table_off[n] = 0;
+        g.dA_bytes[n] = g.mode_bytes[n];
+        if (wide_tables(c) && n < c->order) {
+            // from row 0 of mode n in the array the atomics go to, to the tables and to their end
+            const size_t to_tables = (size_t)(c->d_wide_tables - (g.dA + c->L.A_off[n])) * sizeof(float);
+            const size_t to_end = to_tables + (size_t)c->mfma_grid * g.table_stride;
+            if (to_end >= (1ull << 30)) return fail(c, FTK_EUNSUPPORTED, "tiled kernel: the workgroups' tables are out of the atomics' reach");
+            g.table_off[n] = (unsigned int)to_tables;
+            g.dA_bytes[n] = (unsigned int)to_end;
+        }
+    }
     g.gb_partial = c->use_gb_partial;
     g.B_total = c->L.B_total;
     g.lambda_A = lambda_A;
@@ -462,7 +484,8 @@ int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
         return fail(c, FTK_EUNSUPPORTED, "the rows form of the tiled kernel is not set up for this step");
     // what the kernel assumes: padded ranks 16 P, records of 4 * ceil((N + 1) / 4) words, an LDS
     // table that fits, partial tables sized for grid x waves
-    if (!c->tiled_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !c->use_hot_partial || !c->use_gb_partial ||
+    if (!c->tiled_ok || c->rec_words != 4 * ((c->order + 1 + 3) / 4) || !g.hot_partial || !c->use_gb_partial ||
+        (size_t)c->mfma_grid * g.table_stride > (size_t)c->num_cu * (size_t)c->max_lds ||
         c->tiled_lds_bytes > (size_t)c->max_lds || (size_t)c->hot_H * 64 * c->tiled_P > (size_t)c->max_lds)
         return fail(c, FTK_EUNSUPPORTED, "tiled kernel is not available for this shape");
     switch (c->order) {
@@ -594,7 +617,8 @@ void release(ftk_ctx* c) {
     drop_pending(c);
     for (int n = 0; n < kMaxOrder; ++n)
         if (c->d_new_of_old[n]) hipFree(c->d_new_of_old[n]);
-    void* ptrs[] = {c->d_rec, c->d_rec_tiles, c->d_stage, c->d_A, c->d_dA, c->d_B, c->d_GB, c->d_sums, c->d_flag,
+    if (c->d_arena) c->d_A = c->d_dA = nullptr;   // parts of the arena
+    void* ptrs[] = {c->d_arena, c->d_rec, c->d_rec_tiles, c->d_stage, c->d_A, c->d_dA, c->d_B, c->d_GB, c->d_sums, c->d_flag,
                     c->d_pos, c->d_bidx, c->d_bval, c->d_hot_partial, c->d_gb_partial, c->d_lists, c->d_list_fill,
                     c->d_bucket_info, c->d_bucket_rows, c->d_overflow};
     for (void* p : ptrs)
@@ -639,13 +663,35 @@ int pick_hot_rows(ftk_ctx* c, long long n_samples) {
     // A table row saves its workgroup one global atomic per hit (~12 ns of a per-CU unit that is the
     // kernel's bottleneck) and costs one 64-byte store and one read at the end of the step: worth
     // it from a fraction of an expected hit per workgroup and step.
-    const double min_count = 0.25 * (double)c->mfma_grid * (double)c->nnz / (double)std::max<long long>(n_samples, 1);
+    double min_count = 0.25 * (double)c->mfma_grid * (double)c->nnz / (double)std::max<long long>(n_samples, 1);
+    // Ranks above 32: the pass is bound by matrix-instruction issue and the atomic unit has room, so the
+    // table rows are added by atomics as well (to per-workgroup tables in global memory, see the kernel)
+    // and save no atomic.  What they are for is to keep a frequent row from queueing on ONE address across
+    // all workgroups: float atomics on one address retire at ~41 ns each, so a row is worth a table row
+    // (which the update pass has to sum over all workgroups) when its hits would keep that queue busy for
+    // a good part of the pass, which takes about twice its matrix time.
+    if (c->variant == V_TILED && c->tiled_P == 4) {
+        const double width = 16.0 * c->tiled_P;
+        const double pass_seconds = (double)n_samples * 6.0 * N * width * width / (0.5 * 157.3e12);
+        const double min_hits = 0.35 * pass_seconds / 41e-9;
+        min_count = std::max(min_count, min_hits * (double)c->nnz / (double)std::max<long long>(n_samples, 1));
+        // (no tables behind dA: only the rows of the one-hot product are summed per workgroup)
+        if (!c->d_wide_tables) min_count = std::numeric_limits<double>::infinity();
+    }
+    // the 16 most frequent rows of a mode, where they go through the one-hot product (decided below), are
+    // summed without a swap: they are taken whatever their count
+    bool top_ok[kMaxOrder] = {};
+    for (int n = 0; n < N; ++n) {
+        double top_hits = 0.0;
+        for (int r = 0; r < 16 && r < (int)c->dims[n]; ++r) top_hits += (double)c->sorted_counts[n][r];
+        top_ok[n] = c->dims[n] >= 16 && top_hits * 8.0 >= (double)c->nnz;
+    }
     int taken[kMaxOrder] = {};
     for (int t = 0; t < H; ++t) {
         int best = -1;
         unsigned int best_count = 0;
         for (int n = 0; n < N; ++n)
-            if (taken[n] < c->dims[n] && (double)c->sorted_counts[n][taken[n]] >= min_count) {
+            if (taken[n] < c->dims[n] && ((double)c->sorted_counts[n][taken[n]] >= min_count || (top_ok[n] && taken[n] < 16))) {
                 const unsigned int cnt = c->sorted_counts[n][taken[n]];
                 if (best < 0 || cnt > best_count) {
                     best = n;
@@ -663,9 +709,7 @@ int pick_hot_rows(ftk_ctx* c, long long n_samples) {
         // The 16 most frequent rows go through a one-hot matrix product (four more matrix
         // instructions per tile and mode) only where they collect a fair share of the samples:
         // at least two of a tile's 16 on average.  Elsewhere they are ordinary table rows.
-        double top_hits = 0.0;
-        for (int r = 0; r < 16 && r < (int)c->dims[n]; ++r) top_hits += (double)c->sorted_counts[n][r];
-        c->hot_top[n] = (taken[n] >= 16 && top_hits * 8.0 >= (double)c->nnz) ? 16 : 0;
+        c->hot_top[n] = (taken[n] >= 16 && top_ok[n]) ? 16 : 0;
     }
     c->hot_H = std::max(off, 1);
     c->mfma_lds_bytes = 4 * ((size_t)(c->hot_H + kSinkRows) * 16 + kMfmaWaves * mfma16_wave_scratch(N) + N * 256);
@@ -846,8 +890,22 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     d_col = nullptr;
 
     // ---- parameters ----
-    FTK_HIP(c, hipMalloc(&c->d_A, (size_t)c->A_total * sizeof(float)));
-    FTK_HIP(c, hipMalloc(&c->d_dA, (size_t)c->A_total * sizeof(float)));
+    {
+        // the tables never outgrow what the LDS of a CU holds per workgroup (the kernels' table rows are sized for that)
+        const size_t table_floats = (size_t)c->num_cu * (size_t)c->max_lds / sizeof(float);
+        const size_t arena_floats = 2 * (size_t)c->A_total + table_floats;
+        // every offset the atomics use stays below the out-of-range marker of the kernel (2^30) with room to spare
+        if (c->tiled_ok && c->tiled_P == 4 && arena_floats * sizeof(float) < (1ull << 30) - (1ull << 20)) {
+            FTK_HIP(c, hipMalloc(&c->d_arena, arena_floats * sizeof(float)));
+            c->d_A = c->d_arena;
+            c->d_dA = c->d_A + c->A_total;
+            c->d_wide_tables = c->d_dA + c->A_total;
+            FTK_HIP(c, hipMemset(c->d_wide_tables, 0, table_floats * sizeof(float)));
+        } else {
+            FTK_HIP(c, hipMalloc(&c->d_A, (size_t)c->A_total * sizeof(float)));
+            FTK_HIP(c, hipMalloc(&c->d_dA, (size_t)c->A_total * sizeof(float)));
+        }
+    }
     FTK_HIP(c, hipMalloc(&c->d_B, (size_t)c->L.B_total * sizeof(float)));
     FTK_HIP(c, hipMalloc(&c->d_GB, (size_t)c->L.B_total * sizeof(float)));
     FTK_HIP(c, hipMalloc(&c->d_stage, (size_t)stage * sizeof(float)));
@@ -874,10 +932,10 @@ int create_impl(ftk_ctx* c, const int64_t* dims, const int32_t* const* idx, cons
     if (c->mfma16_ok || c->tiled_ok) {
         c->mfma_grid_max = c->num_cu;
         c->mfma_grid = c->mfma_grid_max;
-        // per-workgroup tables of the frequently hit rows: never more than the LDS can hold; per-wave
-        // (tiled) or per-workgroup (mfma16) tables of the core gradient
+        // per-workgroup tables of the frequently hit rows: never more than the LDS can hold; per-workgroup
+        // tables of the core gradient
         FTK_HIP(c, hipMalloc(&c->d_hot_partial, (size_t)c->mfma_grid_max * c->max_lds));
-        FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid_max * 8 * c->L.B_total * sizeof(float)));
+        FTK_HIP(c, hipMalloc(&c->d_gb_partial, (size_t)c->mfma_grid_max * c->L.B_total * sizeof(float)));
         // the rows form of the tiled kernel: bucket sizes follow from the shape alone
         if (c->tiled_ok && c->tiled_x4) {
             c->count_prefix.assign(N, {});
@@ -1057,8 +1115,9 @@ int ftk_sgd_step_noalloc(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, flo
     if (!base) return fail(c, FTK_EUNSUPPORTED, "no static scratch array on device %d", c->device);
     // the partial tables of this step: [grid][H][row floats], then [grid x parts][B_total]
     const bool tiled = c->variant == V_TILED;
-    const size_t hot_floats = (((size_t)c->mfma_grid * c->hot_H * (tiled ? 16 * c->tiled_P : 16)) + 63) / 64 * 64;
-    const size_t gb_floats = (size_t)c->mfma_grid * (tiled ? c->tiled_waves : 1) * c->L.B_total;
+    // (ranks above 32: the tables of the frequent rows sit behind dA, allocated with it)
+    const size_t hot_floats = wide_tables(c) ? 0 : (((size_t)c->mfma_grid * c->hot_H * (tiled ? 16 * c->tiled_P : 16)) + 63) / 64 * 64;
+    const size_t gb_floats = (size_t)c->mfma_grid * c->L.B_total;
     const size_t need = (hot_floats + gb_floats) * sizeof(float);
     if (need > kScratchBytes)
         return fail(c, FTK_EUNSUPPORTED, "this shape and |Psi| need %zu bytes of partial tables, the static scratch array holds %zu",
@@ -1172,7 +1231,9 @@ int step_impl(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B
         // the row owners above have done the accumulator's part
         p.dense_blocks = (in_place || rows) ? 0 : blocks_for(p.n4, 256, c->num_cu * 16);
         if (mfma) {
-            p.hot_partial = c->use_hot_partial;
+            // tables behind dA were filled by atomics: cleared as they are read, for the next step
+            p.hot_clear = tiled && wide_tables(c);
+            p.hot_partial = p.hot_clear ? c->d_wide_tables : c->use_hot_partial;
             p.hot_parts = c->mfma_grid;
             p.H = c->hot_H;
             p.J = tiled ? 16 * c->tiled_P : 16;
@@ -1188,7 +1249,7 @@ int step_impl(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B
         p.B = c->d_B;
         p.GB = mfma ? c->use_gb_partial : c->d_GB;
         p.B_total = c->L.B_total;
-        p.gb_parts = tiled ? c->mfma_grid * c->tiled_waves : mfma ? c->mfma_grid : 1;
+        p.gb_parts = mfma ? c->mfma_grid : 1;
         p.gb_clear = mfma ? 0 : 1;
         p.lr_A = in_place ? -1.0f : lr_A;
         p.lr_B = lr_B;

@@ -836,7 +836,8 @@ struct ApplyArgs {
     long long n4;               // float4 elements of the packed A / dA allocation
     int dense_blocks;
     // frequently hit rows
-    const float* hot_partial;   // [hot_parts][H][J]
+    float* hot_partial;         // [hot_parts][H][J]
+    int hot_clear;              // zero the tables as they are read (tables that the next gradient pass adds to with atomics)
     int hot_parts;
     int hot_blocks;             // ceil(H * J / 64)
     int H;
@@ -898,7 +899,8 @@ __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
     if (!is_hot) blk -= p.hot_blocks;
     const int count = is_hot ? p.H * p.J : p.B_total;
     const int parts = is_hot ? p.hot_parts : p.gb_parts;
-    const float* src = is_hot ? p.hot_partial : p.GB;
+    float* src = is_hot ? p.hot_partial : p.GB;
+    const bool clear = is_hot && p.hot_clear;
     const int q = blk * 64 + ql;
     float acc0 = 0.0f, acc1 = 0.0f;
     if (q < count) {
@@ -908,10 +910,19 @@ __global__ void __launch_bounds__(256) apply_kernel(ApplyArgs p) {
             float t[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) t[u] = src[(size_t)(b + 4 * u) * count + q];
+            if (clear) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (t[u] != 0.0f) src[(size_t)(b + 4 * u) * count + q] = 0.0f;
+            }
             acc0 += (t[0] + t[2]) + (t[4] + t[6]);
             acc1 += (t[1] + t[3]) + (t[5] + t[7]);
         }
-        for (; b < parts; b += 4) acc0 += src[(size_t)b * count + q];
+        for (; b < parts; b += 4) {
+            const float t = src[(size_t)b * count + q];
+            if (clear && t != 0.0f) src[(size_t)b * count + q] = 0.0f;
+            acc0 += t;
+        }
     }
     red[sub][ql] = acc0 + acc1;
     __syncthreads();

@@ -17,12 +17,19 @@
 // projections, and the other layout comes from an LDS transpose; otherwise lanes fetch single
 // floats in the layout of the gradient and the transpose runs the other way.
 // Factor-row gradients take the same three routes as in the J = R = 16 kernel: rows 0..15 of a
-// mode through the one-hot product, rows [16, K_n) into an LDS table per workgroup
-// (compare-and-swap adds), all other rows through float atomics.  Both the atomic and the table
-// swap are issued by every lane for every element, without a test: an element that takes another
-// route gets an out-of-range buffer offset resp. the address of an LDS row nobody reads.
-// The core gradient lives in matrix-core accumulators for the whole kernel and leaves each wave
-// as one table of plain stores.
+// mode through the one-hot product, rows [16, K_n) into a table per workgroup, all other rows
+// through float atomics.  The atomic is issued by every lane for every element, without a test: an
+// element that takes another route gets an out-of-range buffer offset.  The workgroup's table is
+//   P <= 2  in LDS (compare-and-swap adds, issued for every element of a tile that has a table row,
+//           those of other routes at an LDS row nobody reads): these shapes are bound by the float
+//           atomic instructions, and every row summed on chip is an atomic request less;
+//   P = 4   in global memory, in the same allocation as the accumulator, and its rows are added by
+//           the very atomics that are issued anyway (another offset, nothing else): this shape is
+//           bound by instruction issue with one wave per SIMD, the atomic unit has room, and what a
+//           table row is for is to keep the most frequent rows from queueing on one address across
+//           all workgroups.
+// The core gradient lives in matrix-core accumulators for the whole kernel, is summed over the
+// workgroup's waves in LDS at the end and leaves the workgroup as one table of plain stores.
 //
 // ROWS (thread-block strategy (1) of Section 4.2: the rows of a mode are owned by thread blocks, and
 // the row update sums over the samples of Psi that hit the row, Eq. Gradient_low_rank): rows outside
@@ -65,14 +72,19 @@ struct TiledArgs {
     int B_off[kMaxOrder];
     int J[kMaxOrder];
     int R;
-    int K[kMaxOrder];            // rows [0, K[n]) of mode n live in the LDS table
+    int K[kMaxOrder];            // rows [0, K[n]) of mode n are summed per workgroup (one-hot product or table)
     int top[kMaxOrder];          // 16 if rows 0..15 go through the one-hot product, else 0
-    int hot_off[kMaxOrder];      // first LDS table row of mode n
-    int H;                       // rows in the LDS table
-    float* hot_partial;          // [gridDim.x][H][16 P]
-    float* gb_partial;           // [gridDim.x * waves][B_total]
+    int hot_off[kMaxOrder];      // first table row of mode n
+    int H;                       // rows in a workgroup's table
+    float* hot_partial;          // [gridDim.x][H][16 P]: the workgroups' tables as the update pass reads them
+    float* gb_partial;           // [gridDim.x][B_total]
     int B_total;
     unsigned int mode_bytes[kMaxOrder];   // I_n * J_n * 4
+    // P = 4: rows [top[n], K[n]) are added, by the same float atomics as all other rows, to this workgroup's rows
+    // of hot_partial, which then sits in the same allocation as dA, behind it:
+    unsigned int table_off[kMaxOrder];    // bytes from row 0 of mode n in dA to hot_partial
+    unsigned int table_stride;            // bytes of one workgroup's table, H * 16 P * 4
+    unsigned int dA_bytes[kMaxOrder];     // bytes from row 0 of mode n in dA to the end of the launch's tables (or mode_bytes[n])
     float lambda_A;
     float scale;                 // 1, or -lr_A in in-place mode
     // ROWS only: the per-workgroup lists of gradient rows (see the header comment)
@@ -113,6 +125,10 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     constexpr int W4 = (N + 1 + 3) / 4;
     constexpr int D = 16 * P;            // padded rank
     constexpr int THREADS = WAVES * 64;
+    // Rows [top, K) of a mode: summed in the workgroup's LDS table (P <= 2, where the float atomics are what bounds
+    // the pass), or in the workgroup's table in global memory through the atomics every element issues anyway
+    // (P = 4, where instruction issue bounds the pass and a swap with its round trip costs more than it saves).
+    constexpr bool LDS_TABLE = P < 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g4 = lane >> 4;
     float* Bl = lds;                                 // B^(n) (zero padded) as operands of the projections, see operand_slot
@@ -167,7 +183,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 #pragma unroll
     for (int n = 0; n < N; ++n) {
         rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.mode_bytes[n]);
-        rsrc_dA[n] = make_rsrc(g.dA + g.A_off[n], g.mode_bytes[n]);
+        rsrc_dA[n] = make_rsrc(g.dA + g.A_off[n], LDS_TABLE ? g.mode_bytes[n] : g.dA_bytes[n]);
     }
     // ROWS: this workgroup's list area (the host keeps list_words below 2^28, so byte offsets stay below 2^30)
     const __amdgpu_buffer_rsrc_t rsrc_lists =
@@ -467,23 +483,33 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     entv[3] = e4.w;
                     group_had_full_list = __builtin_amdgcn_readfirstlane((int)entries[N * 64]) != 0;
                 }
+                // P = 4: first byte of this workgroup's table rows of mode n, seen from row 0 of the mode in dA
+                const unsigned int table_base = LDS_TABLE ? 0u : g.table_off[n] + (unsigned int)blockIdx.x * g.table_stride +
+                                                                     (unsigned int)(g.hot_off[n] * D * 4);
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int row = rowv[v];
+                    tab[v] = actY[v] && row < g.K[n] && row >= g.top[n];
                     if constexpr (ROWS)
                         abase[v] = entv[v] == kListFull ? (unsigned int)(row * g.J[n] * 4) : kDropped;
                     else
                         abase[v] = (actY[v] && row >= g.K[n]) ? (unsigned int)(row * g.J[n] * 4) : kDropped;
-                    tab[v] = actY[v] && row < g.K[n] && row >= g.top[n];
-                    tbase[v] = tab[v] ? hot_addr + (unsigned int)((g.hot_off[n] + row) * D * 4) : sink_addr;
+                    if constexpr (LDS_TABLE)
+                        tbase[v] = tab[v] ? hot_addr + (unsigned int)((g.hot_off[n] + row) * D * 4) : sink_addr;
+                    else if (tab[v])
+                        abase[v] = table_base + (unsigned int)(row * D * 4);
                     onehot[v] = row == c ? 1.0f : 0.0f;
                 }
-                // Table rows: compare-and-swap adds, all reads of a batch of the lane's elements first, then all
-                // swaps, so their round trips overlap.  A swap loses when another wave, another lane of the same
-                // instruction or an earlier element of this lane changed the word in between: those go round
-                // again (swaps that aimed at the unread rows are not looked at).  A batch is the whole mode, or
-                // one block of 16 columns where registers are short (P = 4).
-                constexpr int BATCH = P == 4 ? 4 : 4 * P;
+                // ROWS, P = 4: the atomics otherwise only go out after a full list; table rows need them too
+                bool rows_need_atomics = group_had_full_list;
+                if constexpr (ROWS && !LDS_TABLE) {
+                    if (g.K[n] > g.top[n]) rows_need_atomics = rows_need_atomics || __builtin_amdgcn_ballot_w64(tab[0] || tab[1] || tab[2] || tab[3]) != 0;
+                }
+                // Table rows (P <= 2): compare-and-swap adds, the reads of all the lane's elements of the mode first,
+                // then the swaps, so their round trips overlap.  A swap loses when another wave, another lane of the
+                // same instruction or an earlier element of this lane changed the word in between: those go round
+                // again (swaps that aimed at the unread rows are not looked at).
+                constexpr int BATCH = LDS_TABLE ? 4 * P : 1;
                 unsigned int cell[BATCH];
                 float tval[BATCH];
                 auto table_batch = [&]() {
@@ -509,7 +535,11 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                         }
                     }
                 };
-                const bool any_table = g.K[n] > g.top[n];
+                // the swaps are skipped for a tile in which no sample has a table row in this mode (wave-uniform test)
+                bool any_table = false;
+                if constexpr (LDS_TABLE) {
+                    if (g.K[n] > g.top[n]) any_table = __builtin_amdgcn_ballot_w64(tab[0] || tab[1] || tab[2] || tab[3]) != 0;
+                }
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
                     // byte offset of the lane's column inside a row, or the marker for columns past J_n
@@ -525,14 +555,15 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                             const unsigned int word = col < g.J[n] ? __float_as_uint(grad[v]) : (unsigned int)rowv[v];
                             const unsigned int off = (col <= g.J[n] && entv[v] < kListFull) ? (entv[v] + (unsigned int)col) * 4u : kDropped;
                             __builtin_amdgcn_raw_buffer_store_b32(word, rsrc_lists, (int)off, 0, 0);
-                            if (group_had_full_list)
+                            if (rows_need_atomics)
                                 __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[v], rsrc_dA[n], (int)(abase[v] + col4), 0, 0);
                         } else {
                             __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[v], rsrc_dA[n], (int)(abase[v] + col4), 0, 0);
                         }
-                        const int e = BATCH == 4 ? v : 4 * jb + v;
-                        cell[e] = tbase[v] + (unsigned int)((16 * jb + c) * 4);
-                        tval[e] = grad[v];
+                        if constexpr (LDS_TABLE) {
+                            cell[4 * jb + v] = tbase[v] + (unsigned int)((16 * jb + c) * 4);
+                            tval[4 * jb + v] = grad[v];
+                        }
                     }
                     if (g.top[n] > 0) {
 #pragma unroll
@@ -546,9 +577,10 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                         for (int v = 0; v < 4; ++v)
                             GBacc[n][jb][rb] =
                                 __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][jb][v], wY[rb][v], GBacc[n][jb][rb], 0, 0, 0);
-                    if (BATCH == 4 && any_table) table_batch();
                 }
-                if (BATCH != 4 && any_table) table_batch();
+                if constexpr (LDS_TABLE) {
+                    if (any_table) table_batch();
+                }
                 if constexpr (ROWS) {
                     if (g.J[n] == D) {   // no lane of the blocks above holds column J_n: the row numbers go out on their own
 #pragma unroll
@@ -578,22 +610,43 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 for (int v = 0; v < 4; ++v)
                     lds_float_add(hot + (size_t)(g.hot_off[n] + 4 * g4 + v) * D + 16 * jb + c, Top[n][jb][v]);
         }
-    // core gradient: one table per wave, plain stores (entries outside J_n x R are padding, not stored)
-    float* gb_out = g.gb_partial + ((size_t)blockIdx.x * WAVES + wave) * g.B_total;
+    // core gradient: summed over the workgroup's waves in LDS, where the operand tables are no longer needed (the
+    // waves take turns, so plain adds do), and stored as one table per workgroup (entries outside J_n x R are padding)
+    __syncthreads();
+    float* gb_sum = lds;   // [N][D][D]
+#pragma unroll 1
+    for (int turn = 0; turn < WAVES; ++turn) {
+        if (wave == turn) {
 #pragma unroll
-    for (int n = 0; n < N; ++n)
+            for (int n = 0; n < N; ++n)
 #pragma unroll
-        for (int jb = 0; jb < P; ++jb)
+                for (int jb = 0; jb < P; ++jb)
 #pragma unroll
-            for (int rb = 0; rb < P; ++rb)
+                    for (int rb = 0; rb < P; ++rb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int j = 16 * jb + 4 * g4 + v, r = 16 * rb + c;
-                    if (j < g.J[n] && r < g.R) gb_out[g.B_off[n] + j * g.R + r] = GBacc[n][jb][rb][v];
-                }
+                        for (int v = 0; v < 4; ++v) {
+                            float* cell = gb_sum + ((size_t)n * D + 16 * jb + 4 * g4 + v) * D + 16 * rb + c;
+                            *cell = turn == 0 ? GBacc[n][jb][rb][v] : *cell + GBacc[n][jb][rb][v];
+                        }
+        }
+        __syncthreads();
+    }
+    float* gb_out = g.gb_partial + (size_t)blockIdx.x * g.B_total;
+    for (int q = tid; q < N * D * D; q += THREADS) {
+        const int n = q / (D * D), rem = q - n * D * D, j = rem / D, r = rem - j * D;
+        if (j < g.J[n] && r < g.R) gb_out[g.B_off[n] + j * g.R + r] = gb_sum[q];
+    }
     __syncthreads();
     float* hot_out = g.hot_partial + (size_t)blockIdx.x * g.H * D;
-    for (int q = tid; q < g.H * D; q += THREADS) hot_out[q] = hot[q];
+    if constexpr (LDS_TABLE) {
+        for (int q = tid; q < g.H * D; q += THREADS) hot_out[q] = hot[q];
+    } else {
+        // only rows 0..15 of a mode were summed on chip; the other table rows of hot_out hold what the atomics added
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+            if (g.top[n] > 0)
+                for (int q = tid; q < 16 * D; q += THREADS) hot_out[g.hot_off[n] * D + q] = hot[g.hot_off[n] * D + q];
+    }
     if constexpr (ROWS) {
         for (int q = tid; q < g.n_buckets; q += THREADS)
             g.list_fill[(size_t)q * gridDim.x + blockIdx.x] = min(list_count[q], list_cap[q]);

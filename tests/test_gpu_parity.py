@@ -423,6 +423,10 @@ COLD_ROW_CASES = [
     ("mfma16", (20_000, 50_000, 300, 40, 1_200), (1.1, None, None, None, None), (16,) * 5, 16, 300_000, 40_007, 0.3),
     ("tiled", (30_000, 50_000, 900), (1.1, None, None), (32, 32, 32), 32, 300_000, 40_011, 1e-2),   # 32-wide blocks
     ("tiled", (40_000, 60_000, 1_500), (1.1, None, None), (16, 16, 16), 16, 400_000, 60_013, 1e-2),
+    # 64-wide blocks: the table rows (here the 100 evenly hit rows of the last mode beyond its first 16) are summed in
+    # per-workgroup tables in global memory by the same atomics as the rows outside the tables
+    ("tiled", (30_000, 50_000, 100), (1.1, None, None), (64, 64, 64), 64, 300_000, 40_011, 3e-3),
+    ("rows", (30_000, 50_000, 100), (1.1, None, None), (64, 64, 64), 64, 300_000, 40_011, 3e-3),
     # the same rows through the lists of the row-owning workgroups instead of atomics: row number in a spare lane
     # (J_n = 8, 20), in a store of its own (J_n = 16, 32), and with lists so short that many rows fall back to atomics
     ("rows", (30_000, 50_000, 900), (1.1, None, None), (32, 32, 32), 32, 300_000, 40_011, 1e-2),

@@ -79,8 +79,9 @@ def test_refusals_of_the_step_without_allocation():
         assert e.value.code == binding.FTK_EUNSUPPORTED
         ft.ftk_set_kernel("auto")
         ft.ftk_sgd_step_noalloc(1e-3, 1e-3, 0.0, 0.0)
-    # a shape whose partial tables exceed the static array: 64-wide ranks, one core-gradient table per wave
-    w = synth.tiny_workload(3, (300, 200, 100), 200_000, (64, 64, 64), 64, 150_000)
+    # a shape whose partial tables exceed the static array: one mode, so that nearly all of a CU's LDS is table
+    # (about 2 100 rows of 64 bytes per workgroup, 34 MB over 256 workgroups), and every row hit often enough to be in it
+    w = synth.tiny_workload(1, (6_000,), 100_000, (16,), 16, 600_000)
     idx, vals = synth.make_tensor(w)
     with binding.FastTucker(w.dims, idx, vals, w.J, w.R) as ft:
         ft.ftk_sample(1, w.n_samples)
