@@ -270,8 +270,9 @@ int ftk_set_kernel(ftk_ctx* ctx, const char* name);
 const char* ftk_kernel_name(const ftk_ctx* ctx);
 
 /*
- * Which factor rows the current gradient kernel sums on chip instead of adding them to memory one
- * sample at a time (the sum over the samples that hit a row in Eq. Gradient_low_rank is the same
+ * Which factor rows the current gradient kernel sums per workgroup (on chip; at ranks above 32 in a
+ * table of the workgroup's own in device memory) instead of adding them to the shared accumulator
+ * one sample at a time (the sum over the samples that hit a row in Eq. Gradient_low_rank is the same
  * either way; this only reports where it is formed).  Rows of a mode are ranked by how often they
  * occur in Omega, most frequent first, ties by ascending row number; for the sample count of the
  * last ftk_sample (or a default before the first) the kernel keeps ranks [0, K_out[n]) of mode n
