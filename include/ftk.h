@@ -140,6 +140,10 @@ int ftk_get_samples(ftk_ctx* ctx, int64_t* pos_out);
  * the workgroup tables are changed by float atomics as they are met, the most frequently hit rows
  * are accumulated per workgroup and added when the factor phase ends), and on the one-lane-per-sample
  * kernels otherwise (every row update a float atomic; FTK_EUNSUPPORTED where they do not fit the shape).
+ * Non-finite parameters: the kernels keep the sample slots behind the end of Psi and the padding of
+ * short ranks out of the sums by arithmetic (their operands are zero), which holds while A and B
+ * are finite.  Once a step has produced inf or NaN (a step size far too large), every later call
+ * still returns normally, but which further elements turn NaN is unspecified.
  */
 int ftk_sgd_step(ftk_ctx* ctx, float lr_A, float lr_B, float lambda_A, float lambda_B);
 

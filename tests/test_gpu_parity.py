@@ -514,6 +514,24 @@ def test_zero_learning_rate_leaves_parameters_bit_identical():
         assert np.array_equal(x, y)
 
 
+@pytest.mark.parametrize("kernel,J,R", [("auto", (16, 16, 16), 16), ("tiled", (16, 16, 16), 16), ("tiled", (32, 32, 32), 32),
+                                        ("tiled", (64, 64, 64), 64), ("rows", (8, 8, 8), 8), ("generic", (5, 6, 7), 3)])
+def test_a_diverged_run_still_returns(kernel, J, R):
+    """A step size far too large turns the parameters into inf and NaN.  The header promises only that every
+    call still returns: the compare-and-swap loops compare bit patterns, so NaN does not keep them turning."""
+    announce("diverged run, kernel=%s J=%r" % (kernel, J))
+    w = synth.tiny_workload(3, (300, 200, 100), 20_000, J, R, 9_001)
+    idx, vals = synth.make_tensor(w)
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, 3, flags=binding.FTK_LAYOUT_EXACT) as ft:
+        ft.ftk_set_kernel(kernel)
+        for t in range(4):
+            ft.ftk_sample(t, w.n_samples)
+            ft.ftk_sgd_step(1e30, 1e30, 0.1, 0.1)
+        A, B = ft.ftk_get_factors()
+        assert not np.isfinite(ft.ftk_rmse())
+    assert not all(np.isfinite(a).all() for a in A)
+
+
 def test_repeating_a_step_reuses_psi_and_accumulators_are_clean():
     """Two steps on the same Psi equal two oracle steps on it: nothing is left over in the
     gradient accumulators between steps."""
