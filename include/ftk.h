@@ -160,7 +160,9 @@ int ftk_sgd_step(ftk_ctx* ctx, float lr_A, float lr_B, float lambda_A, float lam
  *    one-lane-per-sample kernels keep Psi in arrays allocated on demand: FTK_EUNSUPPORTED.
  *  - FTK_EUNSUPPORTED, with the sizes in ftk_last_error, if this shape and |Psi| need more than
  *    the 32 MiB (workgroups x (table rows x padded rank + core-gradient floats) x 4 bytes; the
- *    benchmark shape, order 3 with J = R = 16 and |Psi| = 1e6, needs 23 MB).
+ *    benchmark shape, order 3 with J = R = 16 and |Psi| = 1e6, needs 23 MB).  At ranks above 32
+ *    the factor-row tables are part of the context's own parameter allocation (made by
+ *    ftk_create) and only the core-gradient tables use the static array.
  *  - Every context on a GPU shares that GPU's array, and nothing in it has to survive from one
  *    call to the next (each workgroup overwrites its part before the update pass reads it), but
  *    two such calls that overlap on one GPU -- different streams, different host threads -- race.
