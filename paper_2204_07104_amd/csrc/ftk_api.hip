@@ -739,7 +739,7 @@ int plan_rows(ftk_ctx* c, long long n_samples) {
                 const double expect = (double)(prefix[(size_t)hi] - prefix[(size_t)lo]) / (double)c->nnz * (double)n_samples /
                                       (double)c->mfma_grid;
                 const double cap = c->rows_tight ? std::max(1.0, std::floor(0.5 * expect)) : std::ceil(expect + 6.0 * std::sqrt(expect) + 8.0);
-                if (cap * (double)c->mfma_grid_max > 2e9 || words > 0x0fffffffull) return fail(c, FTK_EUNSUPPORTED, "rows: the lists of one workgroup exceed 2^28 words");
+                if (cap * (double)c->mfma_grid_max > 2e9 || words > 0x07ffffffull) return fail(c, FTK_EUNSUPPORTED, "rows: the lists of one workgroup exceed 2^27 words");
                 info.push_back(make_uint2((unsigned int)words, (unsigned int)cap));
                 rows.push_back(make_int4(n, (int)lo, (int)(hi - lo), 0));
                 words += (unsigned long long)cap * (unsigned long long)rows_entry_words(c->L.J[n]);
@@ -749,7 +749,7 @@ int plan_rows(ftk_ctx* c, long long n_samples) {
     } catch (...) {
         return fail(c, FTK_ENOMEM, "host allocation failed");
     }
-    if (words > 0x0fffffffull) return fail(c, FTK_EUNSUPPORTED, "rows: the lists of one workgroup exceed 2^28 words");
+    if (words > 0x07ffffffull) return fail(c, FTK_EUNSUPPORTED, "rows: the lists of one workgroup exceed 2^27 words");
     if (info.empty()) {   // every row is in a table: one empty bucket keeps the launches well formed
         info.push_back(make_uint2(0u, 0u));
         rows.push_back(make_int4(0, (int)c->dims[0], 0, 0));

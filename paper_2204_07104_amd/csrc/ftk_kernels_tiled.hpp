@@ -35,7 +35,7 @@
 // the row update sums over the samples of Psi that hit the row, Eq. Gradient_low_rank): rows outside
 // the tables are not added to memory with atomics.  The rows of every mode are cut into buckets of
 // 2^shift rows; a workgroup of this kernel keeps one list per bucket, and the gradient row of a
-// (sample, mode) is appended to the list of its row's bucket as J_n floats + the row number (padded to
+// (sample, mode) is appended to the list of its row's bucket as J_n floats + a word that names the row (padded to
 // a multiple of 16 bytes, so that the owner can read an entry with 16-byte loads), with plain stores
 // (list positions come from LDS counters).  rows_apply_kernel then gives every bucket to
 // one workgroup, which sums the bucket's lists of all gradient workgroups in an LDS table and updates
@@ -98,22 +98,32 @@ struct TiledArgs {
     int bucket_shift[kMaxOrder]; // rows per bucket of mode n = 1 << shift
 };
 
-// words of one list entry of a mode with J floats per row: the row's gradient, the row number, padding to 16 bytes
+// words of one list entry of a mode with J floats per row: the row's gradient, the word that names the row (its
+// byte offset inside the mode, row * J * 4), padding to 16 bytes
 __host__ __device__ constexpr int rows_entry_words(int J) { return (J + 1 + 3) & ~3; }
 
-// list entry words of a (sample, mode) in the parked group: no entry (row in a table, or no sample), list was full
-constexpr unsigned int kNoEntry = 0xffffffffu, kListFull = 0xfffffffeu;
-
+// one parked group of 64 samples, in words.  Evaluation pass: [order][64] row numbers | [64] values.
 __host__ __device__ constexpr int tiled_park_words(int order) { return (order + 1) * 64; }
+// Gradient pass: [order][64] byte offsets of the rows inside their modes (for the gathers) | [order][64] route words
+// (where the row's gradient goes, decided once per sample when the group is parked) | [64] values
+__host__ __device__ constexpr int tiled_grad_park_words(int order) { return (2 * order + 1) * 64; }
+// A route word is what the tile adds its column offset to for the float atomic: a byte offset below 2^30 lands (the
+// row in the accumulator; P = 4: also the row of the workgroup's table behind it), anything else is out of range:
+//   kRouteTable | byte offset of the row in the workgroup's LDS table   (P <= 2)
+//   kRouteOneHot | 4 row (row 0..15): summed by the one-hot product;  kRouteNone: nothing to add (no sample)
+//   kRouteList | byte offset, in the workgroup's list area, of the entry the row's gradient is written to   (ROWS)
+// Every word is a multiple of four (the atomic's address has to be aligned even where it is out of range) and below
+// 0xc0000000 (the marker 2^30 of a padded column is added to it and must not wrap).
+constexpr unsigned int kRouteTable = 0x40000000u, kRouteOneHot = 0x80000000u, kRouteNone = kRouteOneHot | (0xffu << 2);
+constexpr unsigned int kRouteList = 0xa0000000u, kRouteListMask = 0xe0000000u;   // list areas stay below 2^29 bytes
 // ROWS: behind the ordinary layout, LDS holds three arrays of n_buckets words (rounded up to a multiple of
-// four, so that what follows stays 16-byte aligned): list counters | first words | capacities; then per wave
-// two parked groups of [order][64] entry words + 64 words (the first: "a list was full")
+// four): list counters | first words | capacities; then per wave and parked group one word, "a list was full"
 __host__ __device__ constexpr size_t tiled_rows_lds_words(int order, int waves, int n_buckets) {
-    return (size_t)3 * ((n_buckets + 3) & ~3) + (size_t)waves * 2 * (order * 64 + 64);
+    return (size_t)3 * ((n_buckets + 3) & ~3) + (size_t)waves * 2;
 }
 // per wave: two parked groups, the transpose buffer, and 4 x 16 P words nobody reads (see `sink`)
 __host__ __device__ constexpr int tiled_wave_scratch(int order, int P) {
-    return 2 * tiled_park_words(order) + kTransposeFloats + 64 * P;
+    return 2 * tiled_grad_park_words(order) + kTransposeFloats + 64 * P;
 }
 __host__ __device__ constexpr size_t tiled_lds_floats(int order, int P, int waves, int H) {
     return (size_t)2 * order * 256 * P * P + (size_t)H * 16 * P + (size_t)waves * tiled_wave_scratch(order, P);
@@ -135,12 +145,14 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     float* Bt = Bl + N * D * D;                      // its transpose as operands of the A gradient
     float* hot = Bt + N * D * D;                     // [H][D]
     float* wave_lds = hot + (size_t)g.H * D + wave * tiled_wave_scratch(N, P);
-    // two parked groups, each [N][64] row numbers then [64] values; tbuf [16][20]
-    float* tbuf = wave_lds + 2 * tiled_park_words(N);
+    // two parked groups (see tiled_grad_park_words); tbuf [16][20]
+    float* tbuf = wave_lds + 2 * tiled_grad_park_words(N);
     // Table updates are issued for every element; those of samples that take another route aim at a
     // row of their own that nobody reads (one per 16-lane group, so they never collide).
     float* sink = tbuf + kTransposeFloats;
     const unsigned int sink_addr = lds_address(sink + g4 * D), hot_addr = lds_address(hot);
+    const unsigned int sink_rel = sink_addr - hot_addr;          // beyond every row of the table
+    const unsigned int top_key = kRouteOneHot | ((unsigned int)c << 2);   // the route word of row c of the one-hot product
     // Out-of-range marker for buffer offsets: added to anything below 2^30 (every mode is smaller,
     // checked by the host) or to itself it stays beyond the end of the buffer as an unsigned offset.
     constexpr unsigned int kDropped = 0x40000000u;
@@ -152,12 +164,13 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         Bt[operand_slot<P>(n, r, j)] = b;
     }
     for (int q = tid; q < g.H * D; q += THREADS) hot[q] = 0.0f;
+    for (int q = lane; q < 4 * D; q += 64) sink[q] = __builtin_inff();
     // ROWS: list counters, bucket info and the parked entry words behind everything else
     const int nb4 = (g.n_buckets + 3) & ~3;
     unsigned int* list_count = reinterpret_cast<unsigned int*>(hot + (size_t)g.H * D + WAVES * tiled_wave_scratch(N, P));
     unsigned int* list_first = list_count + nb4;
     unsigned int* list_cap = list_first + nb4;
-    unsigned int* wave_entries = list_cap + nb4 + wave * 2 * (N * 64 + 64);
+    unsigned int* wave_full = list_cap + nb4 + wave * 2;   // per parked group: a list was full
     if constexpr (ROWS) {
         for (int q = tid; q < g.n_buckets; q += THREADS) {
             const uint2 info = g.bucket_info[q];
@@ -185,7 +198,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.mode_bytes[n]);
         rsrc_dA[n] = make_rsrc(g.dA + g.A_off[n], LDS_TABLE ? g.mode_bytes[n] : g.dA_bytes[n]);
     }
-    // ROWS: this workgroup's list area (the host keeps list_words below 2^28, so byte offsets stay below 2^30)
+    // ROWS: this workgroup's list area (the host keeps list_words below 2^27, so byte offsets stay below 2^29)
     const __amdgpu_buffer_rsrc_t rsrc_lists =
         make_rsrc(ROWS ? (const void*)(g.lists + (size_t)blockIdx.x * g.list_words) : (const void*)g.A, ROWS ? g.list_words * 4u : 0u);
 
@@ -200,11 +213,11 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
 
-    // Park a group's records: row numbers and values of inactive lanes are zero.
+    // Park a group's records: per (sample, mode) the byte offset of the row inside its mode (lanes past the end of Psi:
+    // the end of the mode, which reads as zeros) and the route word; per sample the value (lanes past the end: 0).
     // ROWS: every (sample, mode) whose row is outside the tables also takes its place in the list of
-    // its row's bucket here (one LDS counter increment per lane and mode); `entries` gets the first
-    // word of that place in the workgroup's list area, or one of the two markers.
-    auto park_record = [&](long long grp, const uint4 (&rec)[W4], float* park, unsigned int* entries) {
+    // its row's bucket here (one LDS counter increment per lane and mode); its route word names that place.
+    auto park_record = [&](long long grp, const uint4 (&rec)[W4], float* park, unsigned int* was_full) {
         const bool act = grp * 64 + lane < M;
         uint32_t flat[4 * W4];
 #pragma unroll
@@ -214,63 +227,78 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             flat[4 * q + 2] = rec[q].z;
             flat[4 * q + 3] = rec[q].w;
         }
-        int* sidx = reinterpret_cast<int*>(park);
+        unsigned int* words = reinterpret_cast<unsigned int*>(park);
+        unsigned int list_word[N];   // ROWS: the route word of a row whose gradient goes to a list, else 0
 #pragma unroll
-        for (int n = 0; n < N; ++n) sidx[n * 64 + lane] = act ? (int)flat[n] : 0;
-        park[N * 64 + lane] = act ? __uint_as_float(flat[N]) : 0.0f;
+        for (int n = 0; n < N; ++n) list_word[n] = 0u;
         if constexpr (ROWS) {
             bool full = false;
 #pragma unroll
             for (int n = 0; n < N; ++n) {
                 const int row = (int)flat[n];
-                unsigned int e = kNoEntry;
                 if (act && row >= g.K[n]) {
                     const int b = g.bucket0[n] + ((row - g.K[n]) >> g.bucket_shift[n]);
                     const unsigned int place = atomicAdd(&list_count[b], 1u);
                     if (place < list_cap[b]) {
-                        e = list_first[b] + place * (unsigned int)rows_entry_words(g.J[n]);
-                    } else {
-                        e = kListFull;
+                        list_word[n] = kRouteList | ((list_first[b] + place * (unsigned int)rows_entry_words(g.J[n])) * 4u);
+                    } else {   // the row goes through the float atomic after all
                         full = true;
                         atomicAdd(g.overflow, 1u);
                     }
                 }
-                entries[n * 64 + lane] = e;
             }
             const unsigned long long any_full = __builtin_amdgcn_ballot_w64(full);
-            if (lane == 0) entries[N * 64] = any_full != 0ull ? 1u : 0u;
+            if (lane == 0) *was_full = any_full != 0ull ? 1u : 0u;
         }
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int row = (int)flat[n];
+            const unsigned int in_mode = (unsigned int)(row * g.J[n] * 4);
+            unsigned int route;
+            if (!act)
+                route = kRouteNone;
+            else if (list_word[n] != 0u)
+                route = list_word[n];
+            else if (row < g.top[n])
+                route = kRouteOneHot | ((unsigned int)row << 2);
+            else if (row < g.K[n])
+                route = LDS_TABLE ? kRouteTable | (unsigned int)((g.hot_off[n] + row) * D * 4)
+                                  : g.table_off[n] + (unsigned int)blockIdx.x * g.table_stride + (unsigned int)((g.hot_off[n] + row) * D * 4);
+            else
+                route = in_mode;
+            words[n * 64 + lane] = act ? in_mode : g.mode_bytes[n];
+            words[(N + n) * 64 + lane] = route;
+        }
+        park[2 * N * 64 + lane] = act ? __uint_as_float(flat[N]) : 0.0f;
     };
     // Request the factor rows of tile `sub` of a parked group whose first sample is number `first`.
     //   X4: rows[n][jb] = components 16 jb + 4g .. +3 of the row of sample c           (layout X)
     //  !X4: rows[n][jb][v] = component 16 jb + c of the row of sample 4g + v            (layout Y)
     // Components past J_n and samples past the end of Psi read as zero (out-of-range offset).
-    auto gather_rows = [&](const float* park, int sub, long long first, floatx4 (&rows)[N][P]) {
-        const int* sidx = reinterpret_cast<const int*>(park);
+    auto gather_rows = [&](const float* park, int sub, floatx4 (&rows)[N][P]) {
+        const int* in_mode = reinterpret_cast<const int*>(park);   // byte offsets of the rows; the end of the mode for no sample
         if constexpr (X4) {
-            const bool act = first + sub * 16 + c < M;
 #pragma unroll
             for (int n = 0; n < N; ++n) {
-                const int row = sidx[n * 64 + sub * 16 + c];
+                const int row_off = in_mode[n * 64 + sub * 16 + c];
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
                     const int col = 16 * jb + 4 * g4;
-                    const int off = (col < g.J[n] && act) ? (row * g.J[n] + col) * 4 : (int)g.mode_bytes[n];
+                    const int off = col < g.J[n] ? row_off + col * 4 : (int)g.mode_bytes[n];
                     rows[n][jb] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_A[n], off, 0, 0));
                 }
             }
         } else {
 #pragma unroll
             for (int n = 0; n < N; ++n) {
-                const int4 r = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
+                const int4 r = *reinterpret_cast<const int4*>(in_mode + n * 64 + sub * 16 + 4 * g4);
                 const int rr[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
                     const int col = 16 * jb + c;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const bool ok = col < g.J[n] && first + sub * 16 + 4 * g4 + v < M;
-                        const int off = ok ? (rr[v] * g.J[n] + col) * 4 : (int)g.mode_bytes[n];
+                        const int off = col < g.J[n] ? rr[v] + col * 4 : (int)g.mode_bytes[n];
                         rows[n][jb][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_A[n], off, 0, 0));
                     }
                 }
@@ -284,20 +312,20 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     int buf = 0;
     if (group < n_groups) {
         load_record(group, rec);
-        park_record(group, rec, wave_lds, wave_entries);
+        park_record(group, rec, wave_lds, wave_full);
         lds_wave_sync();
         if (group + group_stride < n_groups) load_record(group + group_stride, rec);
-        gather_rows(wave_lds, 0, group * 64, cur);
+        gather_rows(wave_lds, 0, cur);
     }
 
 #pragma unroll 1
     for (; group < n_groups; group += group_stride, buf ^= 1) {
-        const float* park = wave_lds + buf * tiled_park_words(N);
-        float* park_next = wave_lds + (buf ^ 1) * tiled_park_words(N);
-        const int* sidx = reinterpret_cast<const int*>(park);
-        const float* sval = park + N * 64;
-        const unsigned int* entries = wave_entries + buf * (N * 64 + 64);
-        unsigned int* entries_next = wave_entries + (buf ^ 1) * (N * 64 + 64);
+        const float* park = wave_lds + buf * tiled_grad_park_words(N);
+        float* park_next = wave_lds + (buf ^ 1) * tiled_grad_park_words(N);
+        const unsigned int* routes = reinterpret_cast<const unsigned int*>(park) + N * 64;
+        const float* sval = park + 2 * N * 64;
+        const unsigned int* was_full = wave_full + buf;
+        unsigned int* was_full_next = wave_full + (buf ^ 1);
 
 #pragma unroll 1
         for (int sub = 0; sub < 4; ++sub) {
@@ -307,23 +335,19 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             // the request goes out at the top of the tile into registers of its own.
             auto request_next = [&](floatx4 (&rows)[N][P]) {
                 if (sub < 3) {
-                    gather_rows(park, sub + 1, group * 64, rows);
+                    gather_rows(park, sub + 1, rows);
                 } else {
                     if (group + group_stride < n_groups) {
-                        park_record(group + group_stride, rec, park_next, entries_next);
+                        park_record(group + group_stride, rec, park_next, was_full_next);
                         lds_wave_sync();
                         if (group + 2 * group_stride < n_groups) load_record(group + 2 * group_stride, rec);
                     }
-                    gather_rows(park_next, 0, (group + group_stride) * 64, rows);
+                    gather_rows(park_next, 0, rows);
                 }
             };
             floatx4 nxt[X4 ? 1 : N][X4 ? 1 : P];
             if constexpr (!X4) request_next(nxt);
 
-            const long long base = group * 64 + sub * 16;
-            bool actY[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) actY[v] = base + 4 * g4 + v < M;
             const float x = sval[sub * 16 + c];
             // both layouts of the tile's rows: aX[k] = component 16 jb + 4g + k of sample c (only used
             // by the projections), aY[n][jb][v] = component 16 jb + c of sample 4g + v
@@ -462,53 +486,47 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     lds_wave_sync();
                 }
 
-                // factor-row gradients: three routes by row number (see the header comment).  Padding
-                // columns and samples past the end of Psi have a = 0 and -e GS = 0, so their gradient is
-                // zero without a test; what keeps them out of dA is the offset.
-                unsigned int abase[4];      // byte offset of the sample's row in dA, or the marker
-                unsigned int tbase[4];      // LDS address of its table row, or of the row nobody reads
-                bool tab[4];
+                // factor-row gradients: where each row's goes was decided when the group was parked (route words, see
+                // tiled_grad_park_words).  Padding columns and samples past the end of Psi have a = 0 and -e GS = 0, so
+                // their gradient is zero without a test; what keeps them out of dA is the offset.
+                const uint4 routes4 = *reinterpret_cast<const uint4*>(routes + n * 64 + sub * 16 + 4 * g4);
+                const unsigned int abase[4] = {routes4.x, routes4.y, routes4.z, routes4.w};   // samples 4g .. 4g+3
+                unsigned int tbase[4];      // P <= 2: LDS address of the sample's table row, or of the row nobody reads
                 float onehot[4];
-                // row numbers of samples 4g .. 4g+3 in this mode (read here, not kept for all modes at once)
-                const int4 rows4 = *reinterpret_cast<const int4*>(sidx + n * 64 + sub * 16 + 4 * g4);
-                const int rowv[4] = {rows4.x, rows4.y, rows4.z, rows4.w};
-                // ROWS: first word of each sample's list entry (or a marker), and whether any list of the group was full
-                unsigned int entv[4] = {kNoEntry, kNoEntry, kNoEntry, kNoEntry};
+                bool is_top[4];
+                // ROWS: the byte offset of each sample's list entry in the workgroup's list area (or the marker), the word that
+                // names its row in the entry (the row's byte offset inside its mode), and whether any list of the group was full
+                unsigned int entv[4] = {kDropped, kDropped, kDropped, kDropped};
+                unsigned int rowv[4] = {0u, 0u, 0u, 0u};
                 bool group_had_full_list = false;
                 if constexpr (ROWS) {
-                    const uint4 e4 = *reinterpret_cast<const uint4*>(entries + n * 64 + sub * 16 + 4 * g4);
-                    entv[0] = e4.x;
-                    entv[1] = e4.y;
-                    entv[2] = e4.z;
-                    entv[3] = e4.w;
-                    group_had_full_list = __builtin_amdgcn_readfirstlane((int)entries[N * 64]) != 0;
+                    const uint4 r4 = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned int*>(park) + n * 64 + sub * 16 + 4 * g4);
+                    rowv[0] = r4.x;
+                    rowv[1] = r4.y;
+                    rowv[2] = r4.z;
+                    rowv[3] = r4.w;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) entv[v] = (abase[v] & kRouteListMask) == kRouteList ? abase[v] & ~kRouteListMask : kDropped;
+                    group_had_full_list = __builtin_amdgcn_readfirstlane((int)*was_full) != 0;
                 }
-                // P = 4: first byte of this workgroup's table rows of mode n, seen from row 0 of the mode in dA
-                const unsigned int table_base = LDS_TABLE ? 0u : g.table_off[n] + (unsigned int)blockIdx.x * g.table_stride +
-                                                                     (unsigned int)(g.hot_off[n] * D * 4);
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int row = rowv[v];
-                    tab[v] = actY[v] && row < g.K[n] && row >= g.top[n];
-                    if constexpr (ROWS)
-                        abase[v] = entv[v] == kListFull ? (unsigned int)(row * g.J[n] * 4) : kDropped;
-                    else
-                        abase[v] = (actY[v] && row >= g.K[n]) ? (unsigned int)(row * g.J[n] * 4) : kDropped;
-                    if constexpr (LDS_TABLE)
-                        tbase[v] = tab[v] ? hot_addr + (unsigned int)((g.hot_off[n] + row) * D * 4) : sink_addr;
-                    else if (tab[v])
-                        abase[v] = table_base + (unsigned int)(row * D * 4);
-                    onehot[v] = row == c ? 1.0f : 0.0f;
+                    // a table word minus its tag is the row's offset in the table, every other word lands far above it
+                    if constexpr (LDS_TABLE) tbase[v] = hot_addr + min(abase[v] - kRouteTable, sink_rel);
+                    is_top[v] = abase[v] == top_key;
+                    onehot[v] = is_top[v] ? 1.0f : 0.0f;
                 }
-                // ROWS, P = 4: the atomics otherwise only go out after a full list; table rows need them too
+                // ROWS: the atomics only go out where a row needs them (its list was full; P = 4: a table row)
                 bool rows_need_atomics = group_had_full_list;
                 if constexpr (ROWS && !LDS_TABLE) {
-                    if (g.K[n] > g.top[n]) rows_need_atomics = rows_need_atomics || __builtin_amdgcn_ballot_w64(tab[0] || tab[1] || tab[2] || tab[3]) != 0;
+                    if (g.K[n] > g.top[n])
+                        rows_need_atomics = rows_need_atomics || __builtin_amdgcn_ballot_w64(min(min(abase[0], abase[1]), min(abase[2], abase[3])) < kRouteTable) != 0;
                 }
                 // Table rows (P <= 2): compare-and-swap adds, the reads of all the lane's elements of the mode first,
                 // then the swaps, so their round trips overlap.  A swap loses when another wave, another lane of the
                 // same instruction or an earlier element of this lane changed the word in between: those go round
-                // again (swaps that aimed at the unread rows are not looked at).
+                // again.  The rows nobody reads hold +inf, which absorbs any finite addend: swaps aimed there succeed
+                // and change nothing, so no lane has to be told apart.
                 constexpr int BATCH = LDS_TABLE ? 4 * P : 1;
                 unsigned int cell[BATCH];
                 float tval[BATCH];
@@ -522,11 +540,11 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     __builtin_amdgcn_sched_barrier(0);
                     bool lost = false;
 #pragma unroll
-                    for (int i = 0; i < BATCH; ++i) lost = lost || (got[i] != seen[i] && tab[i & 3]);
+                    for (int i = 0; i < BATCH; ++i) lost = lost || got[i] != seen[i];
                     if (__builtin_amdgcn_ballot_w64(lost) != 0) {
 #pragma unroll
                         for (int i = 0; i < BATCH; ++i) {
-                            bool again = got[i] != seen[i] && tab[i & 3];
+                            bool again = got[i] != seen[i];
                             while (again) {
                                 const unsigned int expect = got[i];
                                 got[i] = lds_cas(cell[i], expect, __float_as_uint(__uint_as_float(expect) + tval[i]));
@@ -535,10 +553,13 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                         }
                     }
                 };
-                // the swaps are skipped for a tile in which no sample has a table row in this mode (wave-uniform test)
+                // the one-hot products are skipped for a tile in which no sample hits rows 0..15 of this mode, the swaps
+                // for a tile in which no sample has a table row (wave-uniform tests)
+                const bool any_top = g.top[n] > 0 && __builtin_amdgcn_ballot_w64(is_top[0] || is_top[1] || is_top[2] || is_top[3]) != 0;
                 bool any_table = false;
                 if constexpr (LDS_TABLE) {
-                    if (g.K[n] > g.top[n]) any_table = __builtin_amdgcn_ballot_w64(tab[0] || tab[1] || tab[2] || tab[3]) != 0;
+                    if (g.K[n] > g.top[n])
+                        any_table = __builtin_amdgcn_ballot_w64(min(min(tbase[0], tbase[1]), min(tbase[2], tbase[3])) < sink_addr) != 0;
                 }
 #pragma unroll
                 for (int jb = 0; jb < P; ++jb) {
@@ -549,11 +570,11 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     for (int v = 0; v < 4; ++v) {
                         grad[v] = g.scale * fmaf(g.lambda_A, aY[n][jb][v], gs[jb][v]);
                         if constexpr (ROWS) {
-                            // the list entry: components 0 .. J_n - 1, then the row number (its lane may be in
+                            // the list entry: components 0 .. J_n - 1, then the word that names the row (its lane may be in
                             // a block of columns of its own when J_n is a multiple of 16: see below)
                             const int col = 16 * jb + c;
-                            const unsigned int word = col < g.J[n] ? __float_as_uint(grad[v]) : (unsigned int)rowv[v];
-                            const unsigned int off = (col <= g.J[n] && entv[v] < kListFull) ? (entv[v] + (unsigned int)col) * 4u : kDropped;
+                            const unsigned int word = col < g.J[n] ? __float_as_uint(grad[v]) : rowv[v];
+                            const unsigned int off = col <= g.J[n] ? entv[v] + (unsigned int)col * 4u : kDropped;
                             __builtin_amdgcn_raw_buffer_store_b32(word, rsrc_lists, (int)off, 0, 0);
                             if (rows_need_atomics)
                                 __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(grad[v], rsrc_dA[n], (int)(abase[v] + col4), 0, 0);
@@ -565,7 +586,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                             tval[4 * jb + v] = grad[v];
                         }
                     }
-                    if (g.top[n] > 0) {
+                    if (any_top) {
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
                             Top[n][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot[k], grad[k], Top[n][jb], 0, 0, 0);
@@ -582,11 +603,11 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     if (any_table) table_batch();
                 }
                 if constexpr (ROWS) {
-                    if (g.J[n] == D) {   // no lane of the blocks above holds column J_n: the row numbers go out on their own
+                    if (g.J[n] == D) {   // no lane of the blocks above holds column J_n: the rows' words go out on their own
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
-                            const unsigned int off = (c == 0 && entv[v] < kListFull) ? (entv[v] + (unsigned int)D) * 4u : kDropped;
-                            __builtin_amdgcn_raw_buffer_store_b32((unsigned int)rowv[v], rsrc_lists, (int)off, 0, 0);
+                            const unsigned int off = c == 0 ? entv[v] + (unsigned int)D * 4u : kDropped;
+                            __builtin_amdgcn_raw_buffer_store_b32(rowv[v], rsrc_lists, (int)off, 0, 0);
                         }
                     }
                 }
@@ -700,28 +721,29 @@ __global__ void __launch_bounds__(kRowsApplyThreads) rows_apply_kernel(RowsApply
     const unsigned int places = (unsigned int)p.n_sources * (unsigned int)cap;   // below 2^31: checked by the host
     for (unsigned int base = 0; base < places; base += kRowsApplyThreads * kAhead) {
         const float* src[kAhead];
-        int row[kAhead];
+        int row[kAhead];   // first cell of the entry's row in the table, or -1
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             const unsigned int i = base + (unsigned int)(u * kRowsApplyThreads + tid);
             const unsigned int w = i / (unsigned int)cap, place = i - w * (unsigned int)cap;
             const bool valid = i < places && place < fill[w < (unsigned int)p.n_sources ? w : 0u];
             src[u] = valid ? p.lists + (size_t)w * p.list_words + info.x + (size_t)place * stride : nullptr;
-            row[u] = valid ? (int)__float_as_uint(src[u][J]) - row0 : -1;
+            // the entry names its row by the row's byte offset inside the mode: the row's first cell in the table
+            row[u] = valid ? (int)(__float_as_uint(src[u][J]) >> 2) - row0 * J : -1;
         }
         for (int j0 = 0; j0 < J; j0 += 16) {
             uintx4 v[kAhead][4];
 #pragma unroll
             for (int u = 0; u < kAhead; ++u)
 #pragma unroll
-                for (int k4 = 0; k4 < 4; ++k4)   // words past J inside the entry are the row number and padding: read, not used
+                for (int k4 = 0; k4 < 4; ++k4)   // words past J inside the entry are the row's word and padding: read, not used
                     v[u][k4] = (src[u] && j0 + 4 * k4 < J) ? *reinterpret_cast<const uintx4*>(src[u] + j0 + 4 * k4) : uintx4{0u, 0u, 0u, 0u};
             // compare-and-swap adds, one entry's 16 floats at a time: all reads, then all swaps, and only
             // the swaps that lost (another thread changed the cell in between) go round again
 #pragma unroll
             for (int u = 0; u < kAhead; ++u)
-                if (row[u] >= 0 && row[u] < rows) {
-                    unsigned int* cell = reinterpret_cast<unsigned int*>(table + row[u] * J + j0);
+                if (row[u] >= 0 && row[u] < cells) {
+                    unsigned int* cell = reinterpret_cast<unsigned int*>(table + row[u] + j0);
                     unsigned int seen[16], got[16];
 #pragma unroll
                     for (int k = 0; k < 16; ++k) seen[k] = j0 + k < J ? cell[k] : 0u;
