@@ -161,7 +161,9 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         const int n = q / (D * D), rem = q - n * D * D, j = rem / D, r = rem - j * D;
         const float b = (j < g.J[n] && r < g.R) ? g.B[g.B_off[n] + j * g.R + r] : 0.0f;
         Bl[operand_slot<P>(n, j, r)] = b;
-        Bt[operand_slot<P>(n, r, j)] = b;
+        // the factor every row gradient carries (1, or -lr_A in in-place mode) rides in the operand of the A-gradient
+        // products, the only place Bt is used: -e GS comes out of the matrix cores already scaled
+        Bt[operand_slot<P>(n, r, j)] = g.scale * b;
     }
     for (int q = tid; q < g.H * D; q += THREADS) hot[q] = 0.0f;
     for (int q = lane; q < 4 * D; q += 64) sink[q] = __builtin_inff();
@@ -203,6 +205,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         make_rsrc(ROWS ? (const void*)(g.lists + (size_t)blockIdx.x * g.list_words) : (const void*)g.A, ROWS ? g.list_words * 4u : 0u);
 
     const long long M = g.M;
+    const float lambda_scaled = g.lambda_A * g.scale;
     const long long n_groups = (M + 63) / 64;
     const long long group_stride = (long long)gridDim.x * WAVES;
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
@@ -568,7 +571,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     float grad[4];
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        grad[v] = g.scale * fmaf(g.lambda_A, aY[n][jb][v], gs[jb][v]);
+                        grad[v] = fmaf(lambda_scaled, aY[n][jb][v], gs[jb][v]);
                         if constexpr (ROWS) {
                             // the list entry: components 0 .. J_n - 1, then the word that names the row (its lane may be in
                             // a block of columns of its own when J_n is a multiple of 16: see below)
