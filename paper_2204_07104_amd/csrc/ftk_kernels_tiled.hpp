@@ -87,6 +87,7 @@ struct TiledArgs {
     unsigned int dA_bytes[kMaxOrder];     // bytes from row 0 of mode n in dA to the end of the launch's tables (or mode_bytes[n])
     float lambda_A;
     float scale;                 // 1, or -lr_A in in-place mode
+    int sort_mode;               // P <= 2: the samples of a group are parked sorted by their route in this mode (-1: as drawn)
     // ROWS only: the per-workgroup lists of gradient rows (see the header comment)
     float* lists;                // [gridDim.x][list_words]
     unsigned int* list_fill;     // [n_buckets][gridDim.x]: entries in each list when the kernel ends
@@ -253,26 +254,50 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             const unsigned long long any_full = __builtin_amdgcn_ballot_w64(full);
             if (lane == 0) *was_full = any_full != 0ull ? 1u : 0u;
         }
+        unsigned int in_mode[N], route[N];
 #pragma unroll
         for (int n = 0; n < N; ++n) {
             const int row = (int)flat[n];
-            const unsigned int in_mode = (unsigned int)(row * g.J[n] * 4);
-            unsigned int route;
+            in_mode[n] = act ? (unsigned int)(row * g.J[n] * 4) : g.mode_bytes[n];
             if (!act)
-                route = kRouteNone;
+                route[n] = kRouteNone;
             else if (list_word[n] != 0u)
-                route = list_word[n];
+                route[n] = list_word[n];
             else if (row < g.top[n])
-                route = kRouteOneHot | ((unsigned int)row << 2);
+                route[n] = kRouteOneHot | ((unsigned int)row << 2);
             else if (row < g.K[n])
-                route = LDS_TABLE ? kRouteTable | (unsigned int)((g.hot_off[n] + row) * D * 4)
-                                  : g.table_off[n] + (unsigned int)blockIdx.x * g.table_stride + (unsigned int)((g.hot_off[n] + row) * D * 4);
+                route[n] = LDS_TABLE ? kRouteTable | (unsigned int)((g.hot_off[n] + row) * D * 4)
+                                     : g.table_off[n] + (unsigned int)blockIdx.x * g.table_stride + (unsigned int)((g.hot_off[n] + row) * D * 4);
             else
-                route = in_mode;
-            words[n * 64 + lane] = act ? in_mode : g.mode_bytes[n];
-            words[(N + n) * 64 + lane] = route;
+                route[n] = in_mode[n];
         }
-        park[2 * N * 64 + lane] = act ? __uint_as_float(flat[N]) : 0.0f;
+        // Where the sample is parked.  The order of the samples inside a group of 64 is free (it changes the order of
+        // the sums only).  P <= 2: the group is sorted by the kind of route its row takes in the mode the host names
+        // (the one whose routes are most mixed), so that a tile tends to hold one kind: the table swaps and the one-hot
+        // products of that mode are skipped in the tiles without such a row, and the atomic instructions of the other
+        // tiles carry no request.  Equal keys keep their order, so the lanes past the end of Psi (largest key) stay last.
+        int slot = lane;
+        if constexpr (LDS_TABLE) {
+            if (g.sort_mode >= 0) {
+                unsigned int key = 0u;
+#pragma unroll
+                for (int n = 0; n < N; ++n) key = n == g.sort_mode ? route[n] >> 30 : key;
+                if (!act) key = 3u;
+                slot = 0;
+#pragma unroll
+                for (unsigned int k = 0; k < 4; ++k) {
+                    const unsigned long long same = __builtin_amdgcn_ballot_w64(key == k);
+                    const int before = (int)__builtin_amdgcn_mbcnt_hi((unsigned int)(same >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)same, 0u));
+                    slot += key > k ? __builtin_popcountll(same) : key == k ? before : 0;
+                }
+            }
+        }
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            words[n * 64 + slot] = in_mode[n];
+            words[(N + n) * 64 + slot] = route[n];
+        }
+        park[2 * N * 64 + slot] = act ? __uint_as_float(flat[N]) : 0.0f;
     };
     // Request the factor rows of tile `sub` of a parked group whose first sample is number `first`.
     //   X4: rows[n][jb] = components 16 jb + 4g .. +3 of the row of sample c           (layout X)
