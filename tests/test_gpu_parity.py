@@ -728,6 +728,9 @@ def test_other_workloads_full_size_one_step(name):
     ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "auto", binding.FTK_HOGWILD),
     ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "auto", binding.FTK_HOGWILD),
     ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "generic", binding.FTK_HOGWILD),
+    # the general matrix-core kernel at all three block widths (its row gradients' factor -lr_A rides in an operand table)
+    ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "tiled", binding.FTK_HOGWILD),
+    ("C3", 100_000, 10_000, (10_000, 6_250, 300), 3e-9, 3e-7, "auto", binding.FTK_HOGWILD),
     # 64-wide ranks: the in-place pass adds to A and to the workgroups' tables behind it through one buffer
     ("C5", 100_000, 10_000, (4_800, 1_777, 220), 3e-11, 1e-8, "auto", binding.FTK_HOGWILD),
     ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "auto", binding.FTK_HOGWILD_MODEWISE),
