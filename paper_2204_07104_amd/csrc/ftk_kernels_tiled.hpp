@@ -207,12 +207,19 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 
     const long long M = g.M;
     const float lambda_scaled = g.lambda_A * g.scale;
-    const long long n_groups = (M + 63) / 64;
-    const long long group_stride = (long long)gridDim.x * WAVES;
+    // Every wave takes a contiguous share of Psi, a whole number of tiles (the same for all waves, the last ones get
+    // what is left): the waves' work then differs by one tile at most, where whole groups of 64 dealt round-robin leave
+    // up to four tiles between them.  The wave goes through its share in groups of 64; the last group may hold fewer
+    // than four tiles, and the tiles it does not hold are not run.
+    const long long n_waves = (long long)gridDim.x * WAVES;
+    const long long share = ((M + n_waves - 1) / n_waves + 15) / 16 * 16;
+    const long long first = ((long long)blockIdx.x * WAVES + wave) * share;
+    const int mine = first < M ? (int)min(share, M - first) : 0;   // this wave's samples are [first, first + mine)
+    const int n_groups = (mine + 63) / 64;
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
-    auto load_record = [&](long long grp, uint4 (&rec)[W4]) {
-        const long long k = grp * 64 + lane;
-        const uint32_t p = k < M ? sample_place(g.seed, (uint64_t)k, g.rule) : 0u;
+    auto load_record = [&](int grp, uint4 (&rec)[W4]) {
+        const int local = grp * 64 + lane;
+        const uint32_t p = local < mine ? sample_place(g.seed, (uint64_t)(first + local), g.rule) : 0u;
 #pragma unroll
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
@@ -221,8 +228,8 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     // the end of the mode, which reads as zeros) and the route word; per sample the value (lanes past the end: 0).
     // ROWS: every (sample, mode) whose row is outside the tables also takes its place in the list of
     // its row's bucket here (one LDS counter increment per lane and mode); its route word names that place.
-    auto park_record = [&](long long grp, const uint4 (&rec)[W4], float* park, unsigned int* was_full) {
-        const bool act = grp * 64 + lane < M;
+    auto park_record = [&](int grp, const uint4 (&rec)[W4], float* park, unsigned int* was_full) {
+        const bool act = grp * 64 + lane < mine;
         uint32_t flat[4 * W4];
 #pragma unroll
         for (int q = 0; q < W4; ++q) {
@@ -335,19 +342,20 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     };
 
     uint4 rec[W4];
-    long long group = (long long)blockIdx.x * WAVES + wave;
+    int group = 0;
     floatx4 cur[N][P];
     int buf = 0;
     if (group < n_groups) {
         load_record(group, rec);
         park_record(group, rec, wave_lds, wave_full);
         lds_wave_sync();
-        if (group + group_stride < n_groups) load_record(group + group_stride, rec);
+        if (group + 1 < n_groups) load_record(group + 1, rec);
         gather_rows(wave_lds, 0, cur);
     }
 
 #pragma unroll 1
-    for (; group < n_groups; group += group_stride, buf ^= 1) {
+    for (; group < n_groups; ++group, buf ^= 1) {
+        const int tiles = min(4, (mine - 64 * group + 15) / 16);   // four, but for the last group of the share
         const float* park = wave_lds + buf * tiled_grad_park_words(N);
         float* park_next = wave_lds + (buf ^ 1) * tiled_grad_park_words(N);
         const unsigned int* routes = reinterpret_cast<const unsigned int*>(park) + N * 64;
@@ -356,7 +364,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         unsigned int* was_full_next = wave_full + (buf ^ 1);
 
 #pragma unroll 1
-        for (int sub = 0; sub < 4; ++sub) {
+        for (int sub = 0; sub < tiles; ++sub) {
             // Request the next tile's rows (past the last group every lane is past the end of Psi and
             // nothing is read).  X4: into the registers of this tile's rows as soon as the projections
             // have consumed them; otherwise those registers stay in use as the gradient's layout, and
@@ -365,10 +373,10 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 if (sub < 3) {
                     gather_rows(park, sub + 1, rows);
                 } else {
-                    if (group + group_stride < n_groups) {
-                        park_record(group + group_stride, rec, park_next, was_full_next);
+                    if (group + 1 < n_groups) {
+                        park_record(group + 1, rec, park_next, was_full_next);
                         lds_wave_sync();
-                        if (group + 2 * group_stride < n_groups) load_record(group + 2 * group_stride, rec);
+                        if (group + 2 < n_groups) load_record(group + 2, rec);
                     }
                     gather_rows(park_next, 0, rows);
                 }
