@@ -453,7 +453,12 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                 }
             }
 
-            if constexpr (X4) request_next(cur);
+            // P = 4: the request waits until the last mode's gradients are under way: the registers it fills are then free
+            // for the leave-one-out products and the A-gradient stage, which otherwise shuttle values through the
+            // other half of the register file (C5 0.780 -> 0.761 ms per launch); the rows still have a third of the
+            // tile's matrix work to arrive in.
+            constexpr bool LATE_REQUEST = P == 4;
+            if constexpr (X4 && !LATE_REQUEST) request_next(cur);
 
             // leave-one-out products, prediction, error
             floatx4 w[N][P];
@@ -485,6 +490,9 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             }
 #pragma unroll
             for (int n = 0; n < N; ++n) {
+                if constexpr (X4 && LATE_REQUEST) {
+                    if (n == N - 1) request_next(cur);
+                }
                 // -e w^(n) (layout X), -e GS^(n) (layout Y), and -e w^(n) in layout Y through LDS
                 floatx4 gs[P];
                 float wY[P][4];
