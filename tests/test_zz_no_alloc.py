@@ -23,6 +23,8 @@ def close(got, want, what):
 @pytest.mark.parametrize("kernel,dims,zipf,J,R", [
     ("mfma16", (9_000, 2_500, 300), (1.1, 1.1, None), (16, 16, 16), 16),
     ("tiled", (5_000, 1_200, 90), (1.1, None, None), (20, 32, 12), 24),
+    # 64-wide blocks: the factor-row tables are part of the context's parameter allocation, the core-gradient tables use the static array
+    ("tiled", (5_000, 1_200, 90), (1.1, None, None), (64, 40, 52), 48),
 ])
 def test_step_without_allocation_matches_the_allocating_step(kernel, dims, zipf, J, R):
     print("[case] no-alloc step, kernel=%s" % kernel, flush=True)
