@@ -264,7 +264,9 @@ int ftk_get_timing(ftk_ctx* ctx, int which, double* total_ms, int64_t* launches,
  *              that are not summed in the on-chip tables are written to per-workgroup lists, one list per
  *              bucket of rows, and a second kernel gives every bucket to one workgroup, which sums the
  *              bucket's lists on chip and writes the rows of A^(n): no float atomics on A^(n) or on an
- *              accumulator.  Never chosen by "auto" (measured slower than "tiled" on this GPU).  Synchronous
+ *              accumulator (at ranks above 32 the workgroups' own tables, which hold the most frequent rows,
+ *              are in device memory and are still filled by atomics).  Never chosen by "auto" (measured
+ *              slower than "tiled" on this GPU).  Synchronous
  *              step only; needs the shapes of "tiled" with every J_n a multiple of 4 and at most 4096
  *              buckets; allocates the lists (sized from |Psi| and the rows' frequencies) on the device.
  *              "rows:tight" is the same with lists of half the expected length, so that many rows take the
