@@ -396,19 +396,29 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A, int pass = -1) {
     }
 }
 
-template <int N, int P, int WAVES, bool X4, bool ROWS>
+template <int N, int P, int WAVES, bool X4, bool ROWS, int MODE = kSyncPass>
 int launch_tiled_npwxr(ftk_ctx* c, const TiledArgs& g) {
-    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4, ROWS>), c->max_lds)) return rc;
+    if (const int rc = raise_lds_limit(c, reinterpret_cast<const void*>(grad_tiled_kernel<N, P, WAVES, X4, ROWS, MODE>), c->max_lds)) return rc;
     if (c->prepare_only) return FTK_OK;
     Bracket t(c, FTK_K_GRAD);
-    hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES, X4, ROWS>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
+    hipLaunchKernelGGL((grad_tiled_kernel<N, P, WAVES, X4, ROWS, MODE>), dim3(c->mfma_grid), dim3(WAVES * 64), c->tiled_lds_bytes,
                        c->stream, g);
     FTK_HIP(c, hipGetLastError());
     return FTK_OK;
 }
 
+// The mode-by-mode order runs on the tiled kernel where rows are fetched 16 bytes per lane (every J_n a multiple of four).
+inline bool tiled_modewise_ok(const ftk_ctx* c) { return c->variant == V_TILED && c->tiled_x4 && !c->rows; }
+// ... and on the J_n = R = 16 kernel; every other shape takes it on the one-lane-per-sample kernels
+inline bool modewise_on_matrix_cores(const ftk_ctx* c) { return c->variant == V_MFMA16 || tiled_modewise_ok(c); }
+
 template <int N, int P, int WAVES>
-int launch_tiled_npw(ftk_ctx* c, const TiledArgs& g) {
+int launch_tiled_npw(ftk_ctx* c, const TiledArgs& g, int pass) {
+    if (pass == kFactorPhase || pass == kCorePhase) {
+        if (!tiled_modewise_ok(c)) return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order on the tiled kernel needs every J_n to be a multiple of 4");
+        return pass == kFactorPhase ? launch_tiled_npwxr<N, P, WAVES, true, false, kFactorPhase>(c, g)
+                                    : launch_tiled_npwxr<N, P, WAVES, true, false, kCorePhase>(c, g);
+    }
     // the rows form is built for rows fetched 16 bytes per lane (every J_n a multiple of four) only
     if (c->rows) {
         // the row owners' table (up to 64 KB, dynamic) sits next to 4 KB of static LDS
@@ -419,19 +429,21 @@ int launch_tiled_npw(ftk_ctx* c, const TiledArgs& g) {
 }
 
 template <int N>
-int launch_tiled_n(ftk_ctx* c, const TiledArgs& g) {
+int launch_tiled_n(ftk_ctx* c, const TiledArgs& g, int pass) {
     switch (c->tiled_P) {
-        case 1: return launch_tiled_npw<N, 1, 8>(c, g);
-        case 2: return launch_tiled_npw<N, 2, 8>(c, g);
-        default: return launch_tiled_npw<N, 4, 4>(c, g);
+        case 1: return launch_tiled_npw<N, 1, 8>(c, g, pass);
+        case 2: return launch_tiled_npw<N, 2, 8>(c, g, pass);
+        default: return launch_tiled_npw<N, 4, 4>(c, g, pass);
     }
 }
 
 // Ranks above 32 on the tiled kernel: the workgroups' tables of the frequent rows are the ones behind dA, filled by atomics.
 inline bool wide_tables(const ftk_ctx* c) { return c->variant == V_TILED && c->tiled_P == 4 && c->d_wide_tables != nullptr; }
 
-int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
-    const bool in_place = c->mode == FTK_HOGWILD;
+// pass: the synchronous or the fused in-place pass by the context's mode (pass < 0), or one of the two phases of the
+// mode-by-mode order
+int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A, int pass = -1) {
+    const bool in_place = c->mode == FTK_HOGWILD || pass == kFactorPhase || pass == kCorePhase;
     TiledArgs g;
     g.coo = sampled_records(c);
     g.rule = sample_rule(c);
@@ -491,17 +503,17 @@ int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A) {
         c->tiled_lds_bytes > (size_t)c->max_lds || (size_t)c->hot_H * 64 * c->tiled_P > (size_t)c->max_lds)
         return fail(c, FTK_EUNSUPPORTED, "tiled kernel is not available for this shape");
     switch (c->order) {
-        case 1: return launch_tiled_n<1>(c, g);
-        case 2: return launch_tiled_n<2>(c, g);
-        case 3: return launch_tiled_n<3>(c, g);
-        case 4: return launch_tiled_n<4>(c, g);
-        case 5: return launch_tiled_n<5>(c, g);
-        case 6: return launch_tiled_n<6>(c, g);
-        case 7: return launch_tiled_n<7>(c, g);
-        case 8: return launch_tiled_n<8>(c, g);
+        case 1: return launch_tiled_n<1>(c, g, pass);
+        case 2: return launch_tiled_n<2>(c, g, pass);
+        case 3: return launch_tiled_n<3>(c, g, pass);
+        case 4: return launch_tiled_n<4>(c, g, pass);
+        case 5: return launch_tiled_n<5>(c, g, pass);
+        case 6: return launch_tiled_n<6>(c, g, pass);
+        case 7: return launch_tiled_n<7>(c, g, pass);
+        case 8: return launch_tiled_n<8>(c, g, pass);
         // orders 9 and 10 (the paper's sweep ends at 10) are built for ranks up to 16 only
-        case 9: return launch_tiled_npw<9, 1, 8>(c, g);
-        default: return launch_tiled_npw<10, 1, 8>(c, g);
+        case 9: return launch_tiled_npw<9, 1, 8>(c, g, pass);
+        default: return launch_tiled_npw<10, 1, 8>(c, g, pass);
     }
 }
 
@@ -1150,7 +1162,9 @@ int ftk_sgd_step_noalloc(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, flo
     if (!c) return FTK_EINVAL;
     if (const int rc_dev = check_device(c)) return rc_dev;
     if (c->n_samples < 1) return fail(c, FTK_ESTATE, "ftk_sgd_step_noalloc before ftk_sample");
-    if (c->variant == V_GENERIC || c->mode == FTK_HOGWILD_MODEWISE)
+    if (c->mode == FTK_HOGWILD_MODEWISE)
+        return fail(c, FTK_EUNSUPPORTED, "ftk_sgd_step_noalloc serves the one-pass modes (FTK_SYNC, FTK_HOGWILD) only");
+    if (c->variant == V_GENERIC)
         return fail(c, FTK_EUNSUPPORTED, "ftk_sgd_step_noalloc runs on the matrix-core kernels only: the one-lane-per-sample "
                                          "kernels keep Psi in arrays that are allocated on demand");
     if (c->rows) return fail(c, FTK_EUNSUPPORTED, "ftk_sgd_step_noalloc does not serve the \"rows\" kernel (its lists are allocated buffers)");
@@ -1187,10 +1201,12 @@ int launch_apply_parts(ftk_ctx* c, bool hot, bool core, float lr_A, float lr_B, 
     p.n4 = c->A_total / 4;
     p.dense_blocks = 0;
     if (hot) {
-        p.hot_partial = c->use_hot_partial;
+        // tables behind dA were filled by atomics: cleared as they are read, for the next step
+        p.hot_clear = wide_tables(c);
+        p.hot_partial = p.hot_clear ? c->d_wide_tables : c->use_hot_partial;
         p.hot_parts = c->mfma_grid;
         p.H = c->hot_H;
-        p.J = 16;
+        p.J = c->variant == V_TILED ? 16 * c->tiled_P : 16;
         p.hot_blocks = (c->hot_H * p.J + 63) / 64;
         p.order = c->order;
         for (int n = 0; n < kMaxOrder; ++n) {
@@ -1217,21 +1233,22 @@ int launch_apply_parts(ftk_ctx* c, bool hot, bool core, float lr_A, float lr_B, 
     return FTK_OK;
 }
 
-// Algorithm 1 in the order it is printed, on the matrix cores (J_n = R = 16 kernel): the factor phase (lines
-// 1-16: the modes of a sample in turn, rows changed in place), the tables of the frequent rows added to A, then
-// the core phase (lines 17-39) over the same Psi at the rows the factor phase left, and one update of B.
-int step_modewise_mfma16(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
-    if (int rc = launch_grad_mfma16(c, lambda_A, lr_A, kFactorPhase)) return rc;
+// Algorithm 1 in the order it is printed, on the matrix cores (J_n = R = 16 kernel or tiled kernel): the factor
+// phase (lines 1-16: the modes of a sample in turn, rows changed in place), the tables of the frequent rows added
+// to A, then the core phase (lines 17-39) over the same Psi at the rows the factor phase left, and one update of B.
+int step_modewise_matrix_cores(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
+    const bool tiled = c->variant == V_TILED;
+    if (int rc = tiled ? launch_grad_tiled(c, lambda_A, lr_A, kFactorPhase) : launch_grad_mfma16(c, lambda_A, lr_A, kFactorPhase)) return rc;
     if (int rc = launch_apply_parts(c, true, false, -1.0f, lr_B, lambda_B)) return rc;
-    if (int rc = launch_grad_mfma16(c, lambda_A, lr_A, kCorePhase)) return rc;
+    if (int rc = tiled ? launch_grad_tiled(c, lambda_A, lr_A, kCorePhase) : launch_grad_mfma16(c, lambda_A, lr_A, kCorePhase)) return rc;
     return launch_apply_parts(c, false, true, -1.0f, lr_B, lambda_B);
 }
 
 // One step over the current Psi with the partial tables c->use_hot_partial / c->use_gb_partial.
 int step_impl(ftk_ctx* c, float lr_A, float lr_B, float lambda_A, float lambda_B) {
-    // the mode-by-mode in-place order: on the J_n = R = 16 kernel, else on the one-lane-per-sample kernels
+    // the mode-by-mode in-place order: on the matrix cores where a kernel is built for it, else on the one-lane-per-sample kernels
     const bool modewise = c->mode == FTK_HOGWILD_MODEWISE;
-    if (modewise && c->variant == V_MFMA16) return step_modewise_mfma16(c, lr_A, lr_B, lambda_A, lambda_B);
+    if (modewise && modewise_on_matrix_cores(c)) return step_modewise_matrix_cores(c, lr_A, lr_B, lambda_A, lambda_B);
     const bool mfma = c->variant != V_GENERIC && !modewise;   // a matrix-core variant: per-workgroup tables
     const bool tiled = c->variant == V_TILED && !modewise;
     const bool in_place = c->mode != FTK_SYNC;
@@ -1317,6 +1334,9 @@ int prepare_variant(ftk_ctx* c) {
     if (modewise && c->variant == V_MFMA16) {
         rc = launch_grad_mfma16(c, 0.0f, 0.0f, kFactorPhase);
         if (rc == FTK_OK) rc = launch_grad_mfma16(c, 0.0f, 0.0f, kCorePhase);
+    } else if (modewise && tiled_modewise_ok(c)) {
+        rc = launch_grad_tiled(c, 0.0f, 0.0f, kFactorPhase);
+        if (rc == FTK_OK) rc = launch_grad_tiled(c, 0.0f, 0.0f, kCorePhase);
     } else {
         rc = (c->variant == V_TILED && !modewise) ? launch_grad_tiled(c, 0.0f, 0.0f)
              : (c->variant == V_MFMA16 && !modewise) ? launch_grad_mfma16(c, 0.0f, 0.0f)
@@ -1491,8 +1511,8 @@ int ftk_set_mode(ftk_ctx* c, int mode) {
         return fail(c, FTK_EINVAL, "unknown mode %d", mode);
     if (mode != FTK_SYNC && c->rows)
         return fail(c, FTK_EUNSUPPORTED, "the \"rows\" kernel serves the synchronous step only");
-    if (mode == FTK_HOGWILD_MODEWISE && c->variant != V_MFMA16 && c->gen_threads == 0)
-        return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the J_n = R = 16 kernel or on the one-lane-per-sample kernels, which do not fit this shape");
+    if (mode == FTK_HOGWILD_MODEWISE && !modewise_on_matrix_cores(c) && c->gen_threads == 0)
+        return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the matrix-core kernels (tiled: every J_n a multiple of 4) or on the one-lane-per-sample kernels, which do not fit this shape");
     const int old_mode = c->mode;
     c->mode = mode;
     const int rc = prepare_variant(c);

@@ -11,9 +11,11 @@
     X(N, true, ftk::kSyncPass) X(N, true, ftk::kInPlacePass) X(N, true, ftk::kFactorPhase) X(N, true, ftk::kCorePhase)     \
     XE(N)
 // general matrix-core kernel, order N, ranks padded to 16 P (WAVES waves per workgroup): rows fetched 16 bytes per
-// lane or float by float, the row-owner form for the former; the evaluation pass for both
-#define FTK_TILED_INSTANCES_P(X, XE, N, P, WAVES)                                         \
-    X(N, P, WAVES, true, false) X(N, P, WAVES, false, false) X(N, P, WAVES, true, true) XE(N, P, true) XE(N, P, false)
+// lane or float by float, the row-owner form and the two phases of the mode-by-mode order for the former; the
+// evaluation pass for both
+#define FTK_TILED_INSTANCES_P(X, XE, N, P, WAVES)                                                                               \
+    X(N, P, WAVES, true, false, ftk::kSyncPass) X(N, P, WAVES, false, false, ftk::kSyncPass) X(N, P, WAVES, true, true, ftk::kSyncPass) \
+    X(N, P, WAVES, true, false, ftk::kFactorPhase) X(N, P, WAVES, true, false, ftk::kCorePhase) XE(N, P, true) XE(N, P, false)
 #define FTK_TILED_INSTANCES(X, XE, N) \
     FTK_TILED_INSTANCES_P(X, XE, N, 1, 8) FTK_TILED_INSTANCES_P(X, XE, N, 2, 8) FTK_TILED_INSTANCES_P(X, XE, N, 4, 4)
 // orders 9 and 10 (the end of the paper's order sweep): ranks up to 16 only
@@ -22,7 +24,7 @@
 #define FTK_GRAD_MFMA16(N, T, M) template __global__ void ftk::grad_mfma16_kernel<N, T, M>(ftk::Mfma16Args);
 #define FTK_ERRORS_MFMA16(N) \
     template __global__ void ftk::errors_mfma16_kernel<N>(ftk::Coo, uint64_t, const float*, const float*, ftk::Layout, ftk::ModeBytes, double*);
-#define FTK_GRAD_TILED(N, P, W, X4, R) template __global__ void ftk::grad_tiled_kernel<N, P, W, X4, R>(ftk::TiledArgs);
+#define FTK_GRAD_TILED(N, P, W, X4, R, M) template __global__ void ftk::grad_tiled_kernel<N, P, W, X4, R, M>(ftk::TiledArgs);
 #define FTK_ERRORS_TILED(N, P, X4) \
     template __global__ void ftk::errors_tiled_kernel<N, P, X4>(ftk::Coo, uint64_t, const float*, const float*, ftk::Layout, ftk::TiledModeBytes, double*);
 
@@ -40,7 +42,7 @@
 // the host file: every instance is defined elsewhere
 #define FTK_X_GM(N, T, M) extern FTK_GRAD_MFMA16(N, T, M)
 #define FTK_X_EM(N) extern FTK_ERRORS_MFMA16(N)
-#define FTK_X_GT(N, P, W, X4, R) extern FTK_GRAD_TILED(N, P, W, X4, R)
+#define FTK_X_GT(N, P, W, X4, R, M) extern FTK_GRAD_TILED(N, P, W, X4, R, M)
 #define FTK_X_ET(N, P, X4) extern FTK_ERRORS_TILED(N, P, X4)
 FTK_ALL_INSTANCES(FTK_X_GM, FTK_X_EM, FTK_X_GT, FTK_X_ET)
 #endif

@@ -130,8 +130,15 @@ __host__ __device__ constexpr size_t tiled_lds_floats(int order, int P, int wave
     return (size_t)2 * order * 256 * P * P + (size_t)H * 16 * P + (size_t)waves * tiled_wave_scratch(order, P);
 }
 
-template <int N, int P, int WAVES, bool X4, bool ROWS>
+// MODE (see process_group in ftk_kernels_mfma16.hpp): kSyncPass serves the synchronous and the fused in-place step
+// (g.scale tells them apart); kFactorPhase and kCorePhase are the two passes of Algorithm 1's printed order: in the
+// factor phase a tile takes its modes in turn, each with the prediction and GS^(n) at the projections as the modes
+// before it left them, adds the row's change to A (scatter as in the in-place step) and advances the samples'
+// projections of that mode by the change, c^(n) += delta B^(n) (P x P more products); the core phase takes only the core
+// gradient, at the rows the factor phase left.
+template <int N, int P, int WAVES, bool X4, bool ROWS, int MODE = kSyncPass>
 __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
+    static_assert(MODE == kSyncPass || ((MODE == kFactorPhase || MODE == kCorePhase) && X4 && !ROWS), "passes of the printed order: 16-byte row fetches, no lists");
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;
     constexpr int D = 16 * P;            // padded rank
@@ -460,11 +467,11 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             constexpr bool LATE_REQUEST = P == 4;
             if constexpr (X4 && !LATE_REQUEST) request_next(cur);
 
-            // leave-one-out products, prediction, error
+            // leave-one-out products, prediction, error (factor phase: per mode, further down)
             floatx4 w[N][P];
             float xhat = 0.0f;
 #pragma unroll
-            for (int rb = 0; rb < P; ++rb) {
+            for (int rb = 0; rb < (MODE == kFactorPhase ? 0 : P); ++rb) {
                 floatx4 run = {1.0f, 1.0f, 1.0f, 1.0f};
 #pragma unroll
                 for (int n = 0; n < N; ++n) {
@@ -481,7 +488,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             }
             xhat += __shfl_xor(xhat, 16);
             xhat += __shfl_xor(xhat, 32);
-            const float neg_e = xhat - x;
+            float neg_e = xhat - x;
 
             float4 top_[P];   // operands of the next block of the A-gradient products, read one block ahead
             if constexpr (AHEAD) {
@@ -492,6 +499,23 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
             for (int n = 0; n < N; ++n) {
                 if constexpr (X4 && LATE_REQUEST) {
                     if (n == N - 1) request_next(cur);
+                }
+                if constexpr (MODE == kFactorPhase) {
+                    // w^(n), prediction and error from the projections as they stand: those of modes < n already advanced
+                    float part = 0.0f;
+#pragma unroll
+                    for (int rb = 0; rb < P; ++rb) {
+                        floatx4 wn = {1.0f, 1.0f, 1.0f, 1.0f};
+#pragma unroll
+                        for (int k = 0; k < N; ++k)
+                            if (k != n) wn *= s[k][rb];
+                        w[n][rb] = wn;
+                        const floatx4 full = wn * s[n][rb];
+                        part += (full[0] + full[1]) + (full[2] + full[3]);
+                    }
+                    part += __shfl_xor(part, 16);
+                    part += __shfl_xor(part, 32);
+                    neg_e = part - x;
                 }
                 // -e w^(n) (layout X), -e GS^(n) (layout Y), and -e w^(n) in layout Y through LDS
                 floatx4 gs[P];
@@ -517,12 +541,14 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     }
                     const floatx4 wp = w[n][rb] * neg_e;
                     *reinterpret_cast<float4*>(tbuf + c * 20 + 4 * g4) = make_float4(wp[0], wp[1], wp[2], wp[3]);
+                    if constexpr (MODE != kCorePhase) {
 #pragma unroll
-                    for (int jb = 0; jb < P; ++jb) {
-                        const float tk[4] = {tcur[jb].x, tcur[jb].y, tcur[jb].z, tcur[jb].w};
+                        for (int jb = 0; jb < P; ++jb) {
+                            const float tk[4] = {tcur[jb].x, tcur[jb].y, tcur[jb].z, tcur[jb].w};
 #pragma unroll
-                        for (int k = 0; k < 4; ++k)
-                            gs[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(wp[k], tk[k], gs[jb], 0, 0, 0);
+                            for (int k = 0; k < 4; ++k)
+                                gs[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(wp[k], tk[k], gs[jb], 0, 0, 0);
+                        }
                     }
                     lds_wave_sync();
 #pragma unroll
@@ -530,6 +556,17 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                     lds_wave_sync();
                 }
 
+                if constexpr (MODE == kCorePhase) {
+#pragma unroll
+                    for (int jb = 0; jb < P; ++jb)
+#pragma unroll
+                        for (int rb = 0; rb < P; ++rb)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                GBacc[n][jb][rb] =
+                                    __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][jb][v], wY[rb][v], GBacc[n][jb][rb], 0, 0, 0);
+                    continue;
+                }
                 // factor-row gradients: where each row's goes was decided when the group was parked (route words, see
                 // tiled_grad_park_words).  Padding columns and samples past the end of Psi have a = 0 and -e GS = 0, so
                 // their gradient is zero without a test; what keeps them out of dA is the offset.
@@ -635,13 +672,34 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
                         for (int k = 0; k < 4; ++k)
                             Top[n][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(onehot[k], grad[k], Top[n][jb], 0, 0, 0);
                     }
-                    // core gradient block: GB[j = 16 jb + 4g + v'][r = 16 rb + c]
+                    if constexpr (MODE == kFactorPhase) {
+                        // the block of the row's change (layout Y) goes through LDS into layout X and advances the
+                        // sample's projections of this mode: c^(n)[rb] += delta[jb] B^(n)[jb][rb]
+                        if (n + 1 < N) {
 #pragma unroll
-                    for (int rb = 0; rb < P; ++rb)
+                            for (int v = 0; v < 4; ++v) tbuf[(4 * g4 + v) * 20 + c] = grad[v];
+                            lds_wave_sync();
+                            const float4 dx4 = *reinterpret_cast<const float4*>(tbuf + c * 20 + 4 * g4);
+                            lds_wave_sync();
+                            const float dx[4] = {dx4.x, dx4.y, dx4.z, dx4.w};
 #pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            GBacc[n][jb][rb] =
-                                __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][jb][v], wY[rb][v], GBacc[n][jb][rb], 0, 0, 0);
+                            for (int rb = 0; rb < P; ++rb) {
+                                const float4 b4 = *reinterpret_cast<const float4*>(Bl + ((n * P + jb) * P + rb) * 256 + lane * 4);
+                                const float bk[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                                for (int k = 0; k < 4; ++k)
+                                    s[n][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk[k], dx[k], s[n][rb], 0, 0, 0);
+                            }
+                        }
+                    } else {
+                        // core gradient block: GB[j = 16 jb + 4g + v'][r = 16 rb + c]
+#pragma unroll
+                        for (int rb = 0; rb < P; ++rb)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                GBacc[n][jb][rb] =
+                                    __builtin_amdgcn_mfma_f32_16x16x4f32(aY[n][jb][v], wY[rb][v], GBacc[n][jb][rb], 0, 0, 0);
+                    }
                 }
                 if constexpr (LDS_TABLE) {
                     if (any_table) table_batch();
@@ -667,7 +725,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 
     // rows 0..15 of each mode: from the wave's accumulators into the workgroup's LDS table
 #pragma unroll
-    for (int n = 0; n < N; ++n)
+    for (int n = 0; n < (MODE == kCorePhase ? 0 : N); ++n)
         if (g.top[n] > 0) {
 #pragma unroll
             for (int jb = 0; jb < P; ++jb)
@@ -680,7 +738,7 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
     __syncthreads();
     float* gb_sum = lds;   // [N][D][D]
 #pragma unroll 1
-    for (int turn = 0; turn < WAVES; ++turn) {
+    for (int turn = 0; turn < (MODE == kFactorPhase ? 0 : WAVES); ++turn) {
         if (wave == turn) {
 #pragma unroll
             for (int n = 0; n < N; ++n)
@@ -696,12 +754,15 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
         }
         __syncthreads();
     }
-    float* gb_out = g.gb_partial + (size_t)blockIdx.x * g.B_total;
-    for (int q = tid; q < N * D * D; q += THREADS) {
-        const int n = q / (D * D), rem = q - n * D * D, j = rem / D, r = rem - j * D;
-        if (j < g.J[n] && r < g.R) gb_out[g.B_off[n] + j * g.R + r] = gb_sum[q];
+    if constexpr (MODE != kFactorPhase) {
+        float* gb_out = g.gb_partial + (size_t)blockIdx.x * g.B_total;
+        for (int q = tid; q < N * D * D; q += THREADS) {
+            const int n = q / (D * D), rem = q - n * D * D, j = rem / D, r = rem - j * D;
+            if (j < g.J[n] && r < g.R) gb_out[g.B_off[n] + j * g.R + r] = gb_sum[q];
+        }
+        __syncthreads();
     }
-    __syncthreads();
+    if constexpr (MODE == kCorePhase) return;
     float* hot_out = g.hot_partial + (size_t)blockIdx.x * g.H * D;
     if constexpr (LDS_TABLE) {
         for (int q = tid; q < g.H * D; q += THREADS) hot_out[q] = hot[q];

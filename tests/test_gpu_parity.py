@@ -737,6 +737,10 @@ def test_other_workloads_full_size_one_step(name):
     ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "auto", binding.FTK_HOGWILD_MODEWISE),
     ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "generic", binding.FTK_HOGWILD_MODEWISE),
     ("C2", 300_000, 30_000, (4_800, 1_777, 220), 2e-7, 1e-4, "generic", binding.FTK_HOGWILD_MODEWISE),
+    # the mode-by-mode order on the general matrix-core kernel, at its three block widths
+    ("C1", 100_000, 10_000, (1000, 800, 600), 1e-3, 1e-3, "tiled", binding.FTK_HOGWILD_MODEWISE),
+    ("C3", 100_000, 10_000, (10_000, 6_250, 300), 3e-9, 3e-7, "auto", binding.FTK_HOGWILD_MODEWISE),
+    ("C5", 100_000, 10_000, (4_800, 1_777, 220), 3e-11, 1e-8, "auto", binding.FTK_HOGWILD_MODEWISE),
 ])
 def test_hogwild_mode_rmse_curve(name, nnz, M, dims, lr_A, lr_B, kernel, mode):
     """10 steps with factor rows updated in place.  The result depends on scheduling, so it is held
@@ -773,15 +777,20 @@ def test_hogwild_mode_rmse_curve(name, nnz, M, dims, lr_A, lr_B, kernel, mode):
     assert_params_close(gB, B0, "B")
 
 
-@pytest.mark.parametrize("kernel,N,J,R,lr_A", [("mfma16", 3, (16, 8, 12), 8, 5e-2), ("generic", 3, (16, 8, 12), 8, 5e-2),
-                                               ("mfma16", 5, (16, 16, 16, 16, 16), 16, 1e-3), ("mfma16", 2, (4, 16), 11, 5e-2)])
-def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared(kernel, N, J, R, lr_A):
+@pytest.mark.parametrize("kernel,N,J,R,lr_A,lr_B", [
+    ("mfma16", 3, (16, 8, 12), 8, 5e-2, 1e-2), ("generic", 3, (16, 8, 12), 8, 5e-2, 1e-2),
+    ("mfma16", 5, (16, 16, 16, 16, 16), 16, 1e-3, 1e-2), ("mfma16", 2, (4, 16), 11, 5e-2, 1e-2),
+    # the general matrix-core kernel: one, two and four blocks of 16 ranks, and orders the J_n = R = 16 kernel is not built for
+    ("tiled", 3, (16, 8, 12), 8, 5e-2, 1e-2), ("tiled", 3, (32, 24, 20), 24, 3e-5, 1e-3), ("tiled", 3, (64, 48, 40), 48, 3e-7, 1e-5),
+    ("tiled", 4, (32, 32, 16, 20), 32, 3e-6, 1e-3), ("tiled", 6, (32, 16, 32, 16, 32, 16), 32, 3e-7, 1e-4),
+    ("tiled", 7, (16,) * 7, 16, 1e-4, 1e-3)])
+def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared(kernel, N, J, R, lr_A, lr_B):
     """Every stored entry has rows of its own in every mode, and Psi holds no position twice: then
     no two samples touch the same row, running them at once changes nothing, and one step in
     FTK_HOGWILD_MODEWISE has to give what Algorithm 1 gives when its lines are followed one sample
     after the other -- parameter by parameter.  The step is large enough that following the modes in
     turn matters: the same step with all gradients taken at the starting rows lands elsewhere.
-    On the matrix cores (J_n = R = 16 kernel, ranks padded to 16) and on the one-lane-per-sample kernels."""
+    On the matrix cores (both kernels, ranks padded to blocks of 16) and on the one-lane-per-sample kernels."""
     announce("modewise in-place, conflict-free, kernel=%s order=%d" % (kernel, N))
     nnz = 6000
     rng = np.random.default_rng(11)
@@ -794,7 +803,7 @@ def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared(k
         if len(set(pos.tolist())) == M:
             break
         seed += 1
-    lr_B, lam_A, lam_B = 1e-2, 1e-2, 1e-2
+    lam_A, lam_B = 1e-2, 1e-2
     A, B = oracle.init_factors(3, dims, J, R)
     A_sync, B_sync = [a.copy() for a in A], [b.copy() for b in B]
     with binding.FastTucker(dims, idx, vals, J, R, 3) as ft:
