@@ -112,12 +112,9 @@ def main() -> int:
         ft.ftk_set_mode(binding.FTK_HOGWILD)
     elif args.mode == "modewise":
         ft.ftk_set_mode(binding.FTK_HOGWILD_MODEWISE)
-    # the mode-by-mode in-place order runs on the matrix-core kernels (the general one: where every J_n is a multiple
-    # of four), or else on the one-lane-per-sample kernels
     kernel_label = ft.ftk_kernel_name()
     if args.mode == "modewise":
-        on_matrix_cores = kernel_label == "mfma16" or (kernel_label == "tiled" and all(j % 4 == 0 for j in w.J))
-        kernel_label = "%s, factor phase + core phase" % (kernel_label if on_matrix_cores else "generic")
+        kernel_label = "%s, factor phase + core phase" % kernel_label
     print("[bench] context ready, gradient kernel = %s" % kernel_label, file=sys.stderr, flush=True)
 
     def run_steps(first: int, count: int) -> None:

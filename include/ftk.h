@@ -136,11 +136,11 @@ int ftk_get_samples(ftk_ctx* ctx, int64_t* pos_out);
  * updated rows (lines 17-39) and updates every B^(n) once.  Samples still run concurrently, so
  * samples that share a row see each other's updates in no fixed order; on a Psi whose samples share
  * no row the result is that of the printed order up to fp32 rounding.
- * It runs on the matrix cores where the "mfma16" kernel is in use, or the "tiled" kernel with every
- * J_n a multiple of four (16 samples at a time; rows outside the workgroup tables are changed by float
- * atomics as they are met, the most frequently hit rows are accumulated per workgroup and added when
- * the factor phase ends), and on the one-lane-per-sample kernels otherwise (every row update a float
- * atomic; FTK_EUNSUPPORTED where they do not fit the shape).
+ * It runs on the matrix cores where the "mfma16" or the "tiled" kernel is in use (16 samples at a
+ * time; rows outside the workgroup tables are changed by float atomics as they are met, the most
+ * frequently hit rows are accumulated per workgroup and added when the factor phase ends), and on the
+ * one-lane-per-sample kernels otherwise (every row update a float atomic; FTK_EUNSUPPORTED where they
+ * do not fit the shape).
  * Non-finite parameters: the kernels keep the sample slots behind the end of Psi and the padding of
  * short ranks out of the sums by arithmetic (their operands are zero), which holds while A and B
  * are finite.  Once a step has produced inf or NaN (a step size far too large), every later call

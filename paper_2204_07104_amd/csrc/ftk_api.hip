@@ -407,17 +407,20 @@ int launch_tiled_npwxr(ftk_ctx* c, const TiledArgs& g) {
     return FTK_OK;
 }
 
-// The mode-by-mode order runs on the tiled kernel where rows are fetched 16 bytes per lane (every J_n a multiple of four).
-inline bool tiled_modewise_ok(const ftk_ctx* c) { return c->variant == V_TILED && c->tiled_x4 && !c->rows; }
-// ... and on the J_n = R = 16 kernel; every other shape takes it on the one-lane-per-sample kernels
+// The mode-by-mode order runs on both matrix-core kernels (the row-owner form of the tiled kernel serves the synchronous
+// step only), else on the one-lane-per-sample kernels.
+inline bool tiled_modewise_ok(const ftk_ctx* c) { return c->variant == V_TILED && !c->rows; }
 inline bool modewise_on_matrix_cores(const ftk_ctx* c) { return c->variant == V_MFMA16 || tiled_modewise_ok(c); }
 
 template <int N, int P, int WAVES>
 int launch_tiled_npw(ftk_ctx* c, const TiledArgs& g, int pass) {
     if (pass == kFactorPhase || pass == kCorePhase) {
-        if (!tiled_modewise_ok(c)) return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order on the tiled kernel needs every J_n to be a multiple of 4");
-        return pass == kFactorPhase ? launch_tiled_npwxr<N, P, WAVES, true, false, kFactorPhase>(c, g)
-                                    : launch_tiled_npwxr<N, P, WAVES, true, false, kCorePhase>(c, g);
+        if (!tiled_modewise_ok(c)) return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order is not built for the rows form of the tiled kernel");
+        if (c->tiled_x4)
+            return pass == kFactorPhase ? launch_tiled_npwxr<N, P, WAVES, true, false, kFactorPhase>(c, g)
+                                        : launch_tiled_npwxr<N, P, WAVES, true, false, kCorePhase>(c, g);
+        return pass == kFactorPhase ? launch_tiled_npwxr<N, P, WAVES, false, false, kFactorPhase>(c, g)
+                                    : launch_tiled_npwxr<N, P, WAVES, false, false, kCorePhase>(c, g);
     }
     // the rows form is built for rows fetched 16 bytes per lane (every J_n a multiple of four) only
     if (c->rows) {
@@ -1512,7 +1515,7 @@ int ftk_set_mode(ftk_ctx* c, int mode) {
     if (mode != FTK_SYNC && c->rows)
         return fail(c, FTK_EUNSUPPORTED, "the \"rows\" kernel serves the synchronous step only");
     if (mode == FTK_HOGWILD_MODEWISE && !modewise_on_matrix_cores(c) && c->gen_threads == 0)
-        return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the matrix-core kernels (tiled: every J_n a multiple of 4) or on the one-lane-per-sample kernels, which do not fit this shape");
+        return fail(c, FTK_EUNSUPPORTED, "the mode-by-mode order runs on the matrix-core kernels or on the one-lane-per-sample kernels, which do not fit this shape");
     const int old_mode = c->mode;
     c->mode = mode;
     const int rc = prepare_variant(c);

@@ -11,11 +11,12 @@
     X(N, true, ftk::kSyncPass) X(N, true, ftk::kInPlacePass) X(N, true, ftk::kFactorPhase) X(N, true, ftk::kCorePhase)     \
     XE(N)
 // general matrix-core kernel, order N, ranks padded to 16 P (WAVES waves per workgroup): rows fetched 16 bytes per
-// lane or float by float, the row-owner form and the two phases of the mode-by-mode order for the former; the
-// evaluation pass for both
+// lane or float by float (one pass, and the two phases of the mode-by-mode order), the row-owner form for the
+// former; the evaluation pass for both
 #define FTK_TILED_INSTANCES_P(X, XE, N, P, WAVES)                                                                               \
     X(N, P, WAVES, true, false, ftk::kSyncPass) X(N, P, WAVES, false, false, ftk::kSyncPass) X(N, P, WAVES, true, true, ftk::kSyncPass) \
-    X(N, P, WAVES, true, false, ftk::kFactorPhase) X(N, P, WAVES, true, false, ftk::kCorePhase) XE(N, P, true) XE(N, P, false)
+    X(N, P, WAVES, true, false, ftk::kFactorPhase) X(N, P, WAVES, true, false, ftk::kCorePhase)                                 \
+    X(N, P, WAVES, false, false, ftk::kFactorPhase) X(N, P, WAVES, false, false, ftk::kCorePhase) XE(N, P, true) XE(N, P, false)
 #define FTK_TILED_INSTANCES(X, XE, N) \
     FTK_TILED_INSTANCES_P(X, XE, N, 1, 8) FTK_TILED_INSTANCES_P(X, XE, N, 2, 8) FTK_TILED_INSTANCES_P(X, XE, N, 4, 4)
 // orders 9 and 10 (the end of the paper's order sweep): ranks up to 16 only

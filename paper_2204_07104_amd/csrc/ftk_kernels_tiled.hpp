@@ -138,7 +138,7 @@ __host__ __device__ constexpr size_t tiled_lds_floats(int order, int P, int wave
 // gradient, at the rows the factor phase left.
 template <int N, int P, int WAVES, bool X4, bool ROWS, int MODE = kSyncPass>
 __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
-    static_assert(MODE == kSyncPass || ((MODE == kFactorPhase || MODE == kCorePhase) && X4 && !ROWS), "passes of the printed order: 16-byte row fetches, no lists");
+    static_assert(MODE == kSyncPass || ((MODE == kFactorPhase || MODE == kCorePhase) && !ROWS), "the passes of the printed order keep no lists");
     extern __shared__ float lds[];
     constexpr int W4 = (N + 1 + 3) / 4;
     constexpr int D = 16 * P;            // padded rank

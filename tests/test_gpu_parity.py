@@ -783,7 +783,9 @@ def test_hogwild_mode_rmse_curve(name, nnz, M, dims, lr_A, lr_B, kernel, mode):
     # the general matrix-core kernel: one, two and four blocks of 16 ranks, and orders the J_n = R = 16 kernel is not built for
     ("tiled", 3, (16, 8, 12), 8, 5e-2, 1e-2), ("tiled", 3, (32, 24, 20), 24, 3e-5, 1e-3), ("tiled", 3, (64, 48, 40), 48, 3e-7, 1e-5),
     ("tiled", 4, (32, 32, 16, 20), 32, 3e-6, 1e-3), ("tiled", 6, (32, 16, 32, 16, 32, 16), 32, 3e-7, 1e-4),
-    ("tiled", 7, (16,) * 7, 16, 1e-4, 1e-3)])
+    ("tiled", 7, (16,) * 7, 16, 1e-4, 1e-3),
+    # ranks that are no multiples of four: rows fetched float by float
+    ("tiled", 3, (6, 10, 7), 5, 5e-2, 1e-2), ("tiled", 3, (18, 30, 9), 20, 3e-4, 1e-3), ("tiled", 2, (50, 33), 40, 1e-5, 1e-5)])
 def test_modewise_in_place_step_equals_the_printed_order_when_no_row_is_shared(kernel, N, J, R, lr_A, lr_B):
     """Every stored entry has rows of its own in every mode, and Psi holds no position twice: then
     no two samples touch the same row, running them at once changes nothing, and one step in
