@@ -148,11 +148,13 @@ def main() -> int:
     per_kernel = {}
     for slot, name in enumerate(KERNEL_SLOTS):
         ms, cnt = ft.ftk_get_timing(slot)
-        per_kernel[name] = {"avg_ms": ms / max(cnt, 1), "launches": cnt}
+        per_kernel[name] = {"avg_ms": ms / max(cnt, 1), "launches": cnt, "ms_per_step": ms / K}
     ft.ftk_set_timing(False)
     rmse_after = ft.ftk_rmse()
-    dominant = max(per_kernel, key=lambda k: per_kernel[k]["avg_ms"])
-    dom_ms = per_kernel[dominant]["avg_ms"]
+    # the kernel's time per pass over Psi: its average launch (the two-phase mode launches it twice per step, and the
+    # roofline is then held against both launches together)
+    dominant = max(per_kernel, key=lambda k: per_kernel[k]["ms_per_step"])
+    dom_ms = per_kernel[dominant]["ms_per_step"]
     bytes_per_launch = algorithmic_bytes_per_sample(w) * w.n_samples
     flops_per_launch = algorithmic_flops_per_sample(w) * w.n_samples
     achieved_gbs = bytes_per_launch / (dom_ms * 1e-3) / 1e9
@@ -182,6 +184,7 @@ def main() -> int:
         "whole_step_effective_frac": bytes_per_launch / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "flops_per_sample": algorithmic_flops_per_sample(w), "fp32_tflops_in_kernel": achieved_tflops,
         "per_kernel_ms": {k: v["avg_ms"] for k, v in per_kernel.items()},
+        "launches_per_step": {k: v["launches"] / K for k, v in per_kernel.items()},
     }
     ft.close()
     if args.calibrate_copy:
