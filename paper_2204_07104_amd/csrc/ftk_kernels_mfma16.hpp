@@ -164,7 +164,8 @@ __device__ __forceinline__ void gather_rows(const __amdgpu_buffer_rsrc_t (&rsrc_
     }
 }
 
-// One group of 64 samples parked at `scur` (row words, values, scatter lists): four tiles of 16.
+// One group of 64 samples parked at `scur` (row words, values, scatter lists): four tiles of 16 (the
+// first n_tiles of them in the last group of a wave's share).
 // While tile t is computed, the rows of tile t + 3 are requested: tile 3 of this group during
 // tile 0, then tiles 0..2 of the wave's next group (parked at `snxt`).  The requests are
 // unconditional, so that the compiler's count of outstanding memory operations is exact.
@@ -186,7 +187,7 @@ constexpr int kSyncPass = 0, kInPlacePass = 1, kFactorPhase = 2, kCorePhase = 3;
 template <int N, int MODE>
 __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>& st, unsigned int hot_addr,
                                               unsigned int top_key, const unsigned int* scur, const unsigned int* snxt,
-                                              float* tbuf, int c, int g4) {
+                                              float* tbuf, int c, int g4, int n_tiles) {
     __amdgpu_buffer_rsrc_t rsrc_A[N];
 #pragma unroll
     for (int n = 0; n < N; ++n) rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
@@ -199,6 +200,8 @@ __device__ __forceinline__ void process_group(const Mfma16Args& g, WaveState<N>&
 
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
+        // (wave-uniform) only the last group of a wave's share holds fewer than four tiles (n_tiles >= 1)
+        if (sub > 0 && sub >= n_tiles) break;
         // The tile's scatter lists were written when the group was parked: their first batches and
         // lengths are asked for now, long before they are used.
         // (Up to order 3, where the registers allow it; above, everything is read where it is used.)
@@ -533,10 +536,6 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     float* tbuf = wave_lds + 2 * kGroupWords;                          // [N][16][20]
     float* gbred = lds + (size_t)(g.H + kSinkRows) * 16 + kMfmaWaves * mfma16_wave_scratch(N);
 
-    for (int q = tid; q < g.H * 16; q += kMfmaThreads) hot[q] = 0.0f;
-    for (int q = tid; q < kSinkRows * 16; q += kMfmaThreads) hot[g.H * 16 + q] = __uint_as_float(0x7f800000u);
-    for (int q = tid; q < N * 256; q += kMfmaThreads) gbred[q] = 0.0f;
-
     WaveState<N> st;
 #pragma unroll
     for (int n = 0; n < N; ++n) {
@@ -551,7 +550,6 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
 #pragma unroll
         for (int t = 0; t < 4; ++t) st.ring[t][n] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
     }
-    __syncthreads();
 
     const long long M = g.M;
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
@@ -560,37 +558,49 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     unsigned int top_key = (2u << kRouteShift) + (unsigned int)c * 64u;
     asm volatile("" : "+v"(top_key));
 
-    // Which samples a wave takes.  Its turns are numbered t = 0, 1, 2, ...; the wave is number
-    // `wave_id` of `n_waves` in the launch.
-    //   paired turns (entry rule, when every wave has several turns: g.pair_turns): turns 2u and
-    //     2u + 1 share the 128 samples [128 q, 128 q + 128), q = wave_id + u * n_waves: lane l takes
-    //     sample 128 q + 2 l in the even turn and 128 q + 2 l + 1 in the odd one.  Both come out of ONE
-    //     Philox block (counter 64 q + l, low and high pair of words), evaluated in the even turn only.
-    //   otherwise: turn t is the group of 64 samples (tile rule: the run) number t * n_waves + wave_id,
-    //     lane l its l-th sample.
+    // Which samples a wave takes: a share [s0, s_end) of Psi made of whole tiles of 16 samples, the shares of a launch
+    // differing by at most one tile (the kernel lasts as long as its longest wave: with |Psi| = 1e6 on 2048 waves
+    // every wave works through 30 or 31 tiles, where whole groups dealt round-robin gave most of them 32).  The
+    // longer shares go round the workgroups.  The wave's turns are numbered t = 0, 1, 2, ...:
+    //   paired turns (entry rule, when every wave has several turns: g.pair_turns), as long as 128 samples are left:
+    //     turns 2u and 2u + 1 share the samples [s0 + 128 u, s0 + 128 u + 128): lane l takes the (2 l)-th of them in
+    //     the even turn and the (2 l + 1)-th in the odd one.  Both come out of ONE Philox block (s0 is even: low
+    //     and high pair of words), evaluated in the even turn only.
+    //   then, and otherwise: turn t is the 64 samples from s0 + 64 t on, lane l its l-th sample; the last turn of
+    //     the share may hold fewer than four tiles.
     // Which lane and turn a sample lands in changes the order of the sums only.
-    const long long wave_id = (long long)blockIdx.x * kMfmaWaves + wave;
     const long long n_waves = (long long)gridDim.x * kMfmaWaves;
     const bool paired = !TILES && g.pair_turns != 0;
-    const long long n_turns_all = paired ? 2 * ((M + 127) / 128) : (M + 63) / 64;   // over all waves
+    long long s0, s_end;
+    int n_pair_turns, n_turns, last_tiles;
+    {
+        const long long T = (M + 15) / 16;
+        const long long w = (long long)wave * gridDim.x + blockIdx.x;
+        const long long base = T / n_waves, extra = T % n_waves;
+        const long long tiles = base + (w < extra ? 1 : 0);
+        s0 = (w * base + (w < extra ? w : extra)) * 16;
+        s_end = s0 + tiles * 16 < M ? s0 + tiles * 16 : M;
+        n_pair_turns = paired ? 2 * (int)(tiles / 8) : 0;
+        const long long rest = tiles - 4LL * n_pair_turns;        // tiles of the turns that are not paired
+        n_turns = n_pair_turns + (int)((rest + 3) / 4);
+        last_tiles = rest % 4 == 0 ? 4 : (int)(rest % 4);
+    }
     auto sample_of = [&](long long t) -> long long {   // this lane's sample number in turn t
-        if (!paired) return (t * n_waves + wave_id) * 64 + lane;
-        return ((t >> 1) * n_waves + wave_id) * 128 + 2 * lane + (t & 1);
+        if (t < n_pair_turns) return s0 + 128 * (t >> 1) + 2 * lane + (t & 1);
+        return s0 + 64 * t + lane;
     };
-    auto turn_exists = [&](long long t) -> bool {      // wave-uniform: the turn holds at least one sample slot below M's last group
-        if (!paired) return t * n_waves + wave_id < n_turns_all;
-        return 2 * ((t >> 1) * n_waves + wave_id) < n_turns_all;
-    };
+    auto turn_exists = [&](long long t) -> bool { return t < n_turns; };   // wave-uniform
+    auto tiles_of = [&](long long t) -> int { return t == n_turns - 1 ? last_tiles : 4; };
     uint32_t odd_place = 0u;   // entry rule: where the odd turn's sample is read, kept from the even turn
 
     // record of this lane's sample in turn t: N row numbers and the value's bits.  A slot with no
-    // sample behind it reads record 0 and is parked as an empty slot.
+    // sample of the share behind it reads record 0 and is parked as an empty slot.
     auto load_record = [&](long long t, uint4 (&rec)[W4]) {
         const long long k = sample_of(t);
         uint32_t p;
         if constexpr (TILES) {
             p = tile_place(g.seed, (uint64_t)k, g.rule);
-        } else if (!paired) {
+        } else if (t >= n_pair_turns) {
             p = sample_position(g.seed, (uint64_t)k, g.rule.nnz);
         } else {
             if ((t & 1) == 0) {
@@ -602,7 +612,7 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
                 p = odd_place;
             }
         }
-        if (k >= M) p = 0u;
+        if (k >= s_end) p = 0u;
 #pragma unroll
         for (int q = 0; q < W4; ++q) rec[q] = rec4[(size_t)p * W4 + q];
     };
@@ -611,7 +621,7 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     const unsigned long long tile_lanes = 0xffffull << (16 * my_tile);
     const unsigned long long lanes_below = tile_lanes & ((1ull << lane) - 1ull);   // of my tile
     auto park_record = [&](long long t, const uint4 (&rec)[W4], unsigned int* dst) {
-        const bool act = sample_of(t) < M;
+        const bool act = sample_of(t) < s_end;
         uint32_t flat[4 * W4];
 #pragma unroll
         for (int q = 0; q < W4; ++q) {
@@ -663,19 +673,24 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
         }
     };
 
-    if (turn_exists(0)) {
+    // fill the pipeline: the records of the wave's first two turns are on their way while the workgroup clears its tables
+    uint4 rec[W4], rec0[W4];
+    const bool has_turns = turn_exists(0);
+    if (has_turns) {
+        load_record(0, rec0);
+        load_record(1, rec);
+    }
+    for (int q = tid; q < g.H * 4; q += kMfmaThreads) reinterpret_cast<float4*>(hot)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int q = tid; q < kSinkRows * 16; q += kMfmaThreads) hot[g.H * 16 + q] = __uint_as_float(0x7f800000u);
+    for (int q = tid; q < N * 256; q += kMfmaThreads) gbred[q] = 0.0f;
+    __syncthreads();
+    if (has_turns) {
         __amdgpu_buffer_rsrc_t rsrc_A[N];
 #pragma unroll
         for (int n = 0; n < N; ++n) rsrc_A[n] = make_rsrc(g.A + g.A_off[n], g.row_bytes[n]);
 
-        // fill the pipeline: records of this wave's first two turns, rows of the first three tiles
-        uint4 rec[W4];
-        {
-            uint4 rec0[W4];
-            load_record(0, rec0);
-            load_record(1, rec);
-            park_record(0, rec0, sbuf);
-        }
+        // ... then the rows of the first three tiles
+        park_record(0, rec0, sbuf);
         lds_wave_sync();
 #pragma unroll
         for (int t = 0; t < 3; ++t) gather_rows<N>(rsrc_A, sbuf, t, c, g4, st.ring[t]);
@@ -689,7 +704,7 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
             park_record(t + 1, rec, snxt);
             load_record(t + 2, rec);
             lds_wave_sync();
-            process_group<N, MODE>(g, st, hot_addr, top_key, scur, snxt, tbuf, c, g4);
+            process_group<N, MODE>(g, st, hot_addr, top_key, scur, snxt, tbuf, c, g4, tiles_of(t));
         };
         // The first turn is peeled off the loop: the loop proper is then entered with the same
         // sequence of outstanding memory operations as its own back edge, and the compiler's
@@ -699,25 +714,42 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
         for (int parity = 1; turn_exists(t); ++t, parity ^= 1) one_turn(t, parity);
     }
 
-    // rows 0..15 of each mode: from the wave's accumulators into the workgroup's LDS table
-    // (a mode whose table holds fewer than 16 rows never used its accumulator)
+    // rows 0..15 of each mode: from the wave's accumulators into the workgroup's LDS table (a mode whose table
+    // holds fewer than 16 rows never used its accumulator: its zeros aim at the rows of +inf), and the workgroup
+    // reduction of the core gradient.  All cells are read, then all swaps issued, then the lost ones repeated, so that
+    // the round trips of a wave overlap.  Then one table of plain stores per workgroup.
+    {
+        unsigned int cell[8 * N], seen[8 * N], got[8 * N];
+        float val[8 * N];
 #pragma unroll
-    for (int n = 0; n < N; ++n)
-        if (g.top[n] > 0) {
+        for (int n = 0; n < N; ++n)
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                lds_float_add(hot + (size_t)(g.hot_off[n] + 4 * g4 + v) * 16 + c, st.Top[n][v]);
+            for (int v = 0; v < 4; ++v) {
+                const int row = g.top[n] > 0 ? g.hot_off[n] + 4 * g4 + v : g.H + v;
+                cell[8 * n + v] = hot_addr + (unsigned int)(row * 16 + c) * 4u;
+                val[8 * n + v] = st.Top[n][v];
+                cell[8 * n + 4 + v] = lds_address(gbred + n * 256 + (4 * g4 + v) * 16 + c);
+                val[8 * n + 4 + v] = st.GBacc[n][v];
+            }
+#pragma unroll
+        for (int i = 0; i < 8 * N; ++i) seen[i] = *(lds_u32*)(uintptr_t)cell[i];
+#pragma unroll
+        for (int i = 0; i < 8 * N; ++i) got[i] = lds_cas(cell[i], seen[i], __float_as_uint(__uint_as_float(seen[i]) + val[i]));
+#pragma unroll
+        for (int i = 0; i < 8 * N; ++i) {
+            bool again = got[i] != seen[i];
+            while (again) {
+                const unsigned int expect = got[i];
+                got[i] = lds_cas(cell[i], expect, __float_as_uint(__uint_as_float(expect) + val[i]));
+                again = got[i] != expect;
+            }
         }
-    // workgroup reduction of the core gradient, then one table of plain stores per workgroup
-#pragma unroll
-    for (int n = 0; n < N; ++n)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) lds_float_add(gbred + n * 256 + (4 * g4 + v) * 16 + c, st.GBacc[n][v]);
+    }
     __syncthreads();
     float* gb_out = g.gb_partial + (size_t)blockIdx.x * (N * 256);
     for (int q = tid; q < N * 256; q += kMfmaThreads) gb_out[q] = gbred[q];
     float* hot_out = g.hot_partial + (size_t)blockIdx.x * g.H * 16;
-    for (int q = tid; q < g.H * 16; q += kMfmaThreads) hot_out[q] = hot[q];
+    for (int q = tid; q < g.H * 4; q += kMfmaThreads) reinterpret_cast<float4*>(hot_out)[q] = reinterpret_cast<const float4*>(hot)[q];
 }
 
 // ---------------------------------------------------------------------------------------------
