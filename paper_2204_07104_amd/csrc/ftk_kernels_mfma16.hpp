@@ -558,10 +558,13 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     unsigned int top_key = (2u << kRouteShift) + (unsigned int)c * 64u;
     asm volatile("" : "+v"(top_key));
 
-    // Which samples a wave takes: a share [s0, s_end) of Psi made of whole tiles of 16 samples, the shares of a launch
-    // differing by at most one tile (the kernel lasts as long as its longest wave: with |Psi| = 1e6 on 2048 waves
-    // every wave works through 30 or 31 tiles, where whole groups dealt round-robin gave most of them 32).  The
-    // longer shares go round the workgroups.  The wave's turns are numbered t = 0, 1, 2, ...:
+    // Which samples a wave takes: a share [s0, s_end) of Psi made of whole tiles of 16 samples.  The kernel lasts as long
+    // as its slowest wave, so the tiles are dealt out evenly: to the workgroups, inside a workgroup to its four pairs of
+    // waves w, w + 4 -- the two that share a SIMD -- and inside a pair 9 : 7, because the SIMD serves its older wave
+    // first: measured on the benchmark shape, wave w takes 2.5 us per tile and wave w + 4 takes 3.0 us while both run
+    // (with |Psi| = 1e6 on 2048 waves: 35 and 26 tiles, where whole groups dealt round-robin gave most waves 32).
+    // Which wave sits where is the hardware's choice; a wrong guess costs balance, not correctness.
+    // The wave's turns are numbered t = 0, 1, 2, ...:
     //   paired turns (entry rule, when every wave has several turns: g.pair_turns), as long as 128 samples are left:
     //     turns 2u and 2u + 1 share the samples [s0 + 128 u, s0 + 128 u + 128): lane l takes the (2 l)-th of them in
     //     the even turn and the (2 l + 1)-th in the odd one.  Both come out of ONE Philox block (s0 is even: low
@@ -569,16 +572,21 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     //   then, and otherwise: turn t is the 64 samples from s0 + 64 t on, lane l its l-th sample; the last turn of
     //     the share may hold fewer than four tiles.
     // Which lane and turn a sample lands in changes the order of the sums only.
-    const long long n_waves = (long long)gridDim.x * kMfmaWaves;
     const bool paired = !TILES && g.pair_turns != 0;
     long long s0, s_end;
     int n_pair_turns, n_turns, last_tiles;
     {
         const long long T = (M + 15) / 16;
-        const long long w = (long long)wave * gridDim.x + blockIdx.x;
-        const long long base = T / n_waves, extra = T % n_waves;
-        const long long tiles = base + (w < extra ? 1 : 0);
-        s0 = (w * base + (w < extra ? w : extra)) * 16;
+        const long long G = gridDim.x, b = blockIdx.x;
+        const long long Tb = T / G + (b < T % G ? 1 : 0);                      // the workgroup's tiles, from tile b0 on
+        const long long b0 = b * (T / G) + (b < T % G ? b : T % G);
+        static_assert(kMfmaWaves == 8, "the shares are dealt to four pairs of waves");
+        const int pr = wave & 3;
+        const long long Tp = Tb / 4 + (pr < Tb % 4 ? 1 : 0);                   // the pair's tiles, from tile p0 on
+        const long long p0 = b0 + pr * (Tb / 4) + (pr < Tb % 4 ? pr : Tb % 4);
+        const long long older = Tp >= 16 ? (9 * Tp + 15) / 16 : (Tp + 1) / 2;
+        const long long tiles = wave < 4 ? older : Tp - older;
+        s0 = (wave < 4 ? p0 : p0 + older) * 16;
         s_end = s0 + tiles * 16 < M ? s0 + tiles * 16 : M;
         n_pair_turns = paired ? 2 * (int)(tiles / 8) : 0;
         const long long rest = tiles - 4LL * n_pair_turns;        // tiles of the turns that are not paired
