@@ -367,6 +367,12 @@ int launch_grad_mfma16(ftk_ctx* c, float lambda_A, float lr_A, int pass = -1) {
     g.dA = in_place ? c->d_A : c->d_dA;
     g.scale = in_place ? -lr_A : 1.0f;
     g.pair_turns = c->pair_turns ? 1 : 0;
+    {
+        const long long T = (c->n_samples + 15) / 16;
+        if (T / c->mfma_grid >= (1LL << 27)) return fail(c, FTK_EUNSUPPORTED, "mfma16 kernel: more than 2^31 samples per workgroup");
+        g.tiles_each = (int)(T / c->mfma_grid);
+        g.tiles_more = (int)(T % c->mfma_grid);
+    }
     for (int n = 0; n < kMfma16MaxOrder; ++n) {
         g.A_off[n] = c->L.A_off[n];
         g.B_off[n] = c->L.B_off[n];

@@ -99,6 +99,7 @@ struct Mfma16Args {
     float lambda_A;
     float scale;              // 1 (synchronous: the update pass applies -lr_A) or -lr_A (in-place mode)
     int pair_turns;           // entry-sampling rule: a wave's turns come in pairs that share their Philox blocks (see the kernel)
+    int tiles_each, tiles_more;   // ceil(M / 16) tiles over the launch's workgroups: each gets tiles_each, the first tiles_more one more
 };
 
 __device__ __forceinline__ void lds_wave_sync() {
@@ -576,22 +577,22 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
     long long s0, s_end;
     int n_pair_turns, n_turns, last_tiles;
     {
-        const long long T = (M + 15) / 16;
-        const long long G = gridDim.x, b = blockIdx.x;
-        const long long Tb = T / G + (b < T % G ? 1 : 0);                      // the workgroup's tiles, from tile b0 on
-        const long long b0 = b * (T / G) + (b < T % G ? b : T % G);
+        // (the host has done the division: no 64-bit divide on the way to the first record)
         static_assert(kMfmaWaves == 8, "the shares are dealt to four pairs of waves");
+        const int b = (int)blockIdx.x;
+        const int Tb = g.tiles_each + (b < g.tiles_more ? 1 : 0);              // the workgroup's tiles, from tile b0 on
+        const long long b0 = (long long)b * g.tiles_each + (b < g.tiles_more ? b : g.tiles_more);
         const int pr = wave & 3;
-        const long long Tp = Tb / 4 + (pr < Tb % 4 ? 1 : 0);                   // the pair's tiles, from tile p0 on
-        const long long p0 = b0 + pr * (Tb / 4) + (pr < Tb % 4 ? pr : Tb % 4);
-        const long long older = Tp >= 16 ? (9 * Tp + 15) / 16 : (Tp + 1) / 2;
-        const long long tiles = wave < 4 ? older : Tp - older;
+        const int Tp = (Tb >> 2) + (pr < (Tb & 3) ? 1 : 0);                    // the pair's tiles, from tile p0 on
+        const long long p0 = b0 + pr * (Tb >> 2) + (pr < (Tb & 3) ? pr : (Tb & 3));
+        const int older = Tp >= 16 ? (9 * Tp + 15) >> 4 : (Tp + 1) >> 1;
+        const int tiles = wave < 4 ? older : Tp - older;
         s0 = (wave < 4 ? p0 : p0 + older) * 16;
         s_end = s0 + tiles * 16 < M ? s0 + tiles * 16 : M;
-        n_pair_turns = paired ? 2 * (int)(tiles / 8) : 0;
-        const long long rest = tiles - 4LL * n_pair_turns;        // tiles of the turns that are not paired
-        n_turns = n_pair_turns + (int)((rest + 3) / 4);
-        last_tiles = rest % 4 == 0 ? 4 : (int)(rest % 4);
+        n_pair_turns = paired ? 2 * (tiles >> 3) : 0;
+        const int rest = tiles - 4 * n_pair_turns;                // tiles of the turns that are not paired
+        n_turns = n_pair_turns + ((rest + 3) >> 2);
+        last_tiles = (rest & 3) == 0 ? 4 : (rest & 3);
     }
     auto sample_of = [&](long long t) -> long long {   // this lane's sample number in turn t
         if (t < n_pair_turns) return s0 + 128 * (t >> 1) + 2 * lane + (t & 1);
