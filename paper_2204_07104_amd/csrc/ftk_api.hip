@@ -491,6 +491,12 @@ int launch_grad_tiled(ftk_ctx* c, float lambda_A, float lr_A, int pass = -1) {
     g.B_total = c->L.B_total;
     g.lambda_A = lambda_A;
     g.sort_mode = c->sort_mode;
+    {
+        const long long T = (c->n_samples + 15) / 16;
+        if (T / c->mfma_grid >= (1LL << 27)) return fail(c, FTK_EUNSUPPORTED, "tiled kernel: more than 2^31 samples per workgroup");
+        g.tiles_each = (int)(T / c->mfma_grid);
+        g.tiles_more = (int)(T % c->mfma_grid);
+    }
     g.lists = c->d_lists;
     g.list_fill = c->d_list_fill;
     g.bucket_info = c->d_bucket_info;

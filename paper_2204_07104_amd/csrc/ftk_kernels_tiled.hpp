@@ -88,6 +88,7 @@ struct TiledArgs {
     float lambda_A;
     float scale;                 // 1, or -lr_A in in-place mode
     int sort_mode;               // P <= 2: the samples of a group are parked sorted by their route in this mode (-1: as drawn)
+    int tiles_each, tiles_more;  // ceil(M / 16) tiles over the launch's workgroups: each gets tiles_each, the first tiles_more one more
     // ROWS only: the per-workgroup lists of gradient rows (see the header comment)
     float* lists;                // [gridDim.x][list_words]
     unsigned int* list_fill;     // [n_buckets][gridDim.x]: entries in each list when the kernel ends
@@ -214,24 +215,29 @@ __global__ void __launch_bounds__(WAVES * 64) grad_tiled_kernel(TiledArgs g) {
 
     const long long M = g.M;
     const float lambda_scaled = g.lambda_A * g.scale;
-    // Every wave takes a contiguous share of Psi, a whole number of tiles (the same for all waves, the last ones get
-    // what is left): the waves' work then differs by one tile at most, where whole groups of 64 dealt round-robin leave
-    // up to four tiles between them.  The wave goes through its share in groups of 64; the last group may hold fewer
-    // than four tiles, and the tiles it does not hold are not run.
-    // Eight waves: waves w and w + 4 share a SIMD, which serves the older one (w) first, so the two split their
+    // Every wave takes a contiguous share of Psi made of whole tiles: the launch's ceil(M / 16) tiles go evenly to the
+    // workgroups (the host has done that division), a workgroup's tiles evenly to its four SIMDs, so that the work
+    // differs by one tile at most, where whole groups of 64 dealt round-robin leave up to four tiles between the waves.
+    // The wave goes through its share in groups of 64; the last group may hold fewer than four tiles, and the tiles it
+    // does not hold are not run.
+    // Eight waves: waves w and w + 4 share a SIMD, which serves the older one (w) first, so the two split the SIMD's
     // tiles 9 : 7 and finish together (measured: 1 % of the pass on C3, C4 and the order sweep; 10 : 6 is too much).
     // Which wave sits where is the hardware's choice; a wrong guess costs balance, not correctness.
-    const long long n_waves = (long long)gridDim.x * WAVES;
-    const long long share = ((M + n_waves - 1) / n_waves + 15) / 16 * 16;
-    long long first = ((long long)blockIdx.x * WAVES + wave) * share, my_share = share;
+    static_assert(WAVES == 4 || WAVES == 8, "one or two waves per SIMD");
+    const int wg = (int)blockIdx.x;
+    const int wg_tiles = g.tiles_each + (wg < g.tiles_more ? 1 : 0);
+    const long long wg_first = (long long)wg * g.tiles_each + (wg < g.tiles_more ? wg : g.tiles_more);
+    const int simd = wave & 3;
+    const int simd_tiles = (wg_tiles >> 2) + (simd < (wg_tiles & 3) ? 1 : 0);
+    long long first_tile = wg_first + simd * (wg_tiles >> 2) + (simd < (wg_tiles & 3) ? simd : (wg_tiles & 3));
+    int my_tiles = simd_tiles;
     if constexpr (WAVES == 8) {
-        const long long pair_first = ((long long)blockIdx.x * 4 + (wave & 3)) * 2 * share;
-        const long long pair_tiles = 2 * share / 16;
-        const long long older = pair_tiles >= 16 ? (9 * pair_tiles + 15) / 16 * 16 : share;   // samples of wave w
-        first = wave < 4 ? pair_first : pair_first + older;
-        my_share = wave < 4 ? older : 2 * share - older;
+        const int older = simd_tiles >= 16 ? (9 * simd_tiles + 15) >> 4 : (simd_tiles + 1) >> 1;
+        my_tiles = wave < 4 ? older : simd_tiles - older;
+        first_tile += wave < 4 ? 0 : older;
     }
-    const int mine = first < M ? (int)min(my_share, M - first) : 0;   // this wave's samples are [first, first + mine)
+    const long long first = first_tile * 16;
+    const int mine = first < M ? (int)min((long long)my_tiles * 16, M - first) : 0;   // this wave's samples are [first, first + mine)
     const int n_groups = (mine + 63) / 64;
     const uint4* rec4 = reinterpret_cast<const uint4*>(g.coo.rec);
     auto load_record = [&](int grp, uint4 (&rec)[W4]) {
