@@ -420,6 +420,9 @@ COLD_ROW_CASES = [
     # kernel, dims, power-law exponent per mode, J, R, stored entries, |Psi| (ragged last group), lr_A
     ("mfma16", (40_000, 60_000, 1_500), (1.1, None, None), (16, 16, 16), 16, 400_000, 60_013, 1e-2),
     ("mfma16", (60_000, 30_000), (None, 1.1), (16, 16), 16, 300_000, 50_001, 1e-2),
+    # |Psi| large enough for the turns that share their Philox blocks: shares of 11 and 7 tiles for the two waves of a SIMD
+    # (one pair of turns and a turn of three tiles; two plain turns), and the ragged end of Psi inside the last share
+    ("mfma16", (400_000, 600_000, 1_500), (1.1, None, None), (16, 16, 16), 16, 1_200_000, 300_007, 1e-2),
     ("mfma16", (20_000, 50_000, 300, 40, 1_200), (1.1, None, None, None, None), (16,) * 5, 16, 300_000, 40_007, 0.3),
     ("tiled", (30_000, 50_000, 900), (1.1, None, None), (32, 32, 32), 32, 300_000, 40_011, 1e-2),   # 32-wide blocks
     ("tiled", (40_000, 60_000, 1_500), (1.1, None, None), (16, 16, 16), 16, 400_000, 60_013, 1e-2),
