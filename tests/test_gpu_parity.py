@@ -501,6 +501,33 @@ def test_rows_outside_the_tables_hit_once_or_twice(kernel, dims, zipf, J, R, nnz
     assert_params_close(gB, B, "B")
 
 
+@pytest.mark.parametrize("kernel", ["mfma16", "tiled"])
+def test_every_sample_is_taken_exactly_once_whatever_the_size_of_psi(kernel):
+    """The waves' shares of Psi (whole tiles, dealt to workgroups, SIMDs and the two waves of a SIMD; turns in pairs
+    where |Psi| allows) at sample counts around every edge of that deal: fewer samples than a tile, than waves, one
+    tile per wave and one sample more, the first count that takes the paired turns and its neighbours, a count
+    that leaves every wave whole tiles.  Inputs as in the test above: one hit moves a row by about a hundred
+    tolerances, so a sample left out or taken twice fails the comparison."""
+    announce("shares of Psi at edge sizes, kernel=%s" % kernel)
+    dims, zipf, J, R = (400_000, 600_000, 1_500), (1.1, None, None), (16, 16, 16), 16
+    w, idx, vals, A0, B0 = cold_row_inputs(dims, zipf, J, R, 1_200_000, 1, 1e-2)
+    with binding.FastTucker(w.dims, idx, vals, w.J, w.R, w.init_seed, flags=binding.FTK_LAYOUT_EXACT) as ft:
+        ft.ftk_set_kernel(kernel)
+        for M in (1, 15, 17, 2_047, 2_048 * 16, 2_048 * 16 + 1, 262_079, 262_081, 262_145, 2_048 * 16 * 9):
+            ft.ftk_set_factors(A0, B0)
+            ft.ftk_sample(w.sample_seed0 + M, M)
+            ft.ftk_sgd_step(w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+            gA, gB = ft.ftk_get_factors()
+            pos = oracle.sample_positions(w.sample_seed0 + M, M, w.nnz)
+            A, B = [a.copy() for a in A0], [b.copy() for b in B0]
+            oracle.sgd_step_sync(w.dims, idx, vals, A, B, pos, w.lr_A, w.lr_B, w.lambda_A, w.lambda_B)
+            assert_params_close(gA, A, "A, |Psi| = %d" % M)
+            assert_params_close(gB, B, "B, |Psi| = %d" % M)
+            if M >= 2_047:
+                moved = max(float(np.abs(a.astype(np.float64) - a0).max()) for a, a0 in zip(A, A0))
+                assert moved > 1e-3, (M, moved)
+
+
 # ------------------------------------------------------------------------------------------------
 # invariants and error paths through the ABI
 # ------------------------------------------------------------------------------------------------
