@@ -662,18 +662,16 @@ int plan_rows(ftk_ctx* c, long long n_samples);
 
 int pick_hot_rows(ftk_ctx* c, long long n_samples) {
     const int N = c->order;
-    // One workgroup per CU, but no more than there are groups of 64 samples to give every wave
+    // One workgroup per CU, but no more than there are tiles of 16 samples to give every wave
     // one: every workgroup writes (and the update pass reads) a whole partial table.
     {
-        // a wave's unit of work: 64 samples, or 128 (two turns that share their Philox blocks) in the
-        // J = R = 16 kernel under the entry-sampling rule
         const long long waves = c->variant == V_TILED ? c->tiled_waves : kMfmaWaves;
-        // pairs only where every wave of a full launch has at least two groups of 64 anyway
+        // turns in pairs that share their Philox blocks (J = R = 16 kernel, entry-sampling rule) only where every
+        // wave of a full launch has at least two groups of 64 anyway
         c->pair_turns = c->variant == V_MFMA16 && c->sampling == FTK_SAMPLE_ENTRIES &&
                         (n_samples + 63) / 64 >= 2LL * c->mfma_grid_max * kMfmaWaves;
-        const long long unit = c->pair_turns ? 128 : 64;
-        const long long units = (n_samples + unit - 1) / unit;
-        c->mfma_grid = (int)std::max<long long>(1, std::min<long long>(c->mfma_grid_max, (units + waves - 1) / waves));
+        const long long tiles = (n_samples + 15) / 16;
+        c->mfma_grid = (int)std::max<long long>(1, std::min<long long>(c->mfma_grid_max, (tiles + waves - 1) / waves));
     }
     long long rows_total = 0;
     for (int n = 0; n < N; ++n) rows_total += c->dims[n];
