@@ -715,12 +715,19 @@ __global__ void __launch_bounds__(kMfmaThreads) grad_mfma16_kernel(Mfma16Args g)
             lds_wave_sync();
             process_group<N, MODE>(g, st, hot_addr, top_key, scur, snxt, tbuf, c, g4, tiles_of(t));
         };
-        // The first turn is peeled off the loop: the loop proper is then entered with the same
-        // sequence of outstanding memory operations as its own back edge, and the compiler's
-        // wait counts in the steady state are exact instead of the minimum over both entries.
-        one_turn(0, 0);
-        long long t = 1;
-        for (int parity = 1; turn_exists(t); ++t, parity ^= 1) one_turn(t, parity);
+        // From order 4 on the first turn is peeled off the loop: the loop proper is then entered with the same sequence
+        // of outstanding memory operations as its own back edge, and the compiler's wait counts in the steady state
+        // are exact instead of the minimum over both entries (order 5, 1e6 samples: 270 us against 273 us).  Up to order
+        // 3 there is one copy of the loop body: a wave has less than ten turns on the benchmark shape, and a second
+        // copy of 40 KB of code has to be fetched before it runs (100.1 us against 100.9 us).
+        long long t = 0;
+        int parity = 0;
+        if constexpr (N >= 4) {
+            one_turn(0, 0);
+            t = 1;
+            parity = 1;
+        }
+        for (; turn_exists(t); ++t, parity ^= 1) one_turn(t, parity);
     }
 
     // rows 0..15 of each mode: from the wave's accumulators into the workgroup's LDS table (a mode whose table
